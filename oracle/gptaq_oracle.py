@@ -1,0 +1,316 @@
+"""fp64 CPU oracle for the GPTAQ per-layer solve.  TEST INFRASTRUCTURE ONLY.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import this
+module.  It shares no code with the HIP library: numpy in float64, one function per
+step of Algorithm 1 of the paper, in the paper's order and notation, unblocked and
+unfused so that it can be checked against the paper by eye.
+
+Orientation.  The paper writes X as n x k (neurons x tokens).  Activations arrive
+here token-major, shape (k, n), as bfloat16 bit patterns (uint16); Xk below is that
+array widened exactly to float64, so the paper's X is Xk.T.
+
+Readings taken where the paper is silent (each is listed in the design doc):
+  * H and dXXT are plain sums over tokens (Algorithm 1, line 2).
+  * the W_{:,j} that multiplies P_{j,:} is the current, error-compensated value of
+    column j *before* it is quantised (the W_{:,q} of Eq. 15), both inside the block
+    and in the lazy trailing update; this is what makes lazy batching (Step 4) exact.
+  * dead inputs (H_qq = 0): H_qq <- 1, row q of dXXT <- 0, column q of W <- 0, then
+    lambda = damp * mean(diag H).
+  * the weight quantiser is the uniform affine min-max grid with 0 inside the range;
+    group parameters are taken from the current weights at the first column of a
+    group; rounding is half-to-even; the scale is rounded to fp32 (the library hands
+    fp32 scales to its caller, the oracle quantises on that same grid).
+
+Pins (tests/test_oracle_pins.py): Eq. 2-3 explicit-inverse GPTQ when dX = 0, a
+per-column constrained least-squares solved by a library lstsq (Eq. 14), Eq. 15 with
+explicit inverses, Lemma 4.1, Theorem 4.2 vs Eq. 16, ridge-regression rows of P,
+closed form W (I - P)^-1 for the identity quantiser, a hand-worked quantiser example.
+Every function in this file has at least one such pin; none is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+
+# ----------------------------------------------------------------------- inputs
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact widening of bfloat16 patterns (uint16) to float64."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+# ------------------------------------------------ Algorithm 1, line 2: H and dXXT
+def accumulate(X_bits: np.ndarray, Xtilde_bits: np.ndarray):
+    """H = X X^T and dXXT = (X~ - X) X^T (Algorithm 1, line 2), token-major inputs.
+
+    dXXT[q, j] = sum_t dX[q, t] X[j, t]: row = neuron of dX, column = neuron of X
+    (the row vector dX_{q,:} X^T of Eq. 16).
+    """
+    Xk = bf16_bits_to_f64(X_bits)
+    Xtk = bf16_bits_to_f64(Xtilde_bits)
+    H = Xk.T @ Xk
+    dXXT = (Xtk - Xk).T @ Xk
+    return H, dXXT
+
+
+# ------------------------------------- Algorithm 1, line 3: damping, H^-1 = L L^T
+def dampen(H: np.ndarray, dXXT: np.ndarray, damp: float):
+    """H + lambda I with lambda = damp * mean(diag H) ("dampened by 1% of the average
+    values", end of Section 4.2), after the dead-input rule."""
+    H = np.array(H, dtype=np.float64, copy=True)
+    A = np.array(dXXT, dtype=np.float64, copy=True)
+    dead = np.diag(H) == 0.0
+    idx = np.nonzero(dead)[0]
+    H[idx, idx] = 1.0
+    A[idx, :] = 0.0
+    lam = damp * np.mean(np.diag(H))
+    H[np.diag_indices_from(H)] += lam
+    return H, A, dead, lam
+
+
+def inverse_cholesky(H_lam: np.ndarray) -> np.ndarray:
+    """Lower-triangular L with H_lam^-1 = L L^T (Step 3), by the literal route:
+    invert, then factor."""
+    Hinv = np.linalg.inv(H_lam)
+    Hinv = 0.5 * (Hinv + Hinv.T)
+    return np.linalg.cholesky(Hinv)
+
+
+# ------------------------------------------- Algorithm 1, line 4 / Theorem 4.2: P
+def correction_matrix(dXXT: np.ndarray, L: np.ndarray) -> np.ndarray:
+    """P = ((dXXT L) (.) M_U) L^T with M_U the strictly-upper 0/1 mask (Eq. 17)."""
+    O = np.triu(dXXT @ L, k=1)
+    return O @ L.T
+
+
+def prepare(H: np.ndarray, dXXT: np.ndarray, damp: float):
+    """Lines 3-4 of Algorithm 1.  Returns U = L^T (upper), P (strictly upper), dead."""
+    H_lam, A, dead, _ = dampen(H, dXXT, damp)
+    L = inverse_cholesky(H_lam)
+    P = correction_matrix(A, L)
+    return L.T.copy(), P, dead
+
+
+# -------------------------------------------------------------------- quantiser
+def quant_params(xmin: np.ndarray, xmax: np.ndarray, bits: int, sym: bool):
+    """Scale and zero-point of the uniform affine grid for ranges [xmin, xmax].
+
+    The range always contains 0.  Symmetric: the range is widened to +-max|w| and the
+    zero-point sits at mid-grid.  The scale is rounded to fp32 once.
+    """
+    maxq = float(2 ** bits - 1)
+    xmin = np.minimum(np.asarray(xmin, np.float64), 0.0)
+    xmax = np.maximum(np.asarray(xmax, np.float64), 0.0)
+    if sym:
+        xmax = np.maximum(np.abs(xmin), xmax)
+        xmin = -xmax
+    flat = (xmin == 0.0) & (xmax == 0.0)
+    xmin = np.where(flat, -1.0, xmin)
+    xmax = np.where(flat, 1.0, xmax)
+    scale = ((xmax - xmin) / maxq).astype(np.float32).astype(np.float64)
+    if sym:
+        zero = np.full_like(scale, (maxq + 1.0) / 2.0)
+    else:
+        zero = np.rint(-xmin / scale)
+    return scale, zero
+
+
+def quantize_column(w: np.ndarray, scale: np.ndarray, zero: np.ndarray, bits: int):
+    """quant(.) for one column.  Returns integer codes, dequantised values and
+    t = w / scale (the value whose rounding decides the code)."""
+    maxq = float(2 ** bits - 1)
+    t = w / scale
+    q = np.clip(np.rint(t) + zero, 0.0, maxq)
+    return q, scale * (q - zero), t
+
+
+# ------------------------------- Algorithm 1, lines 5-13 with B = 1 (no batching)
+def quantize_layer(W, U, P, bits, group=0, sym=False, dead=None,
+                   identity_quantizer=False, use_E=True, use_P=True,
+                   hint_codes=None, hint_zeros=None, tau=0.0):
+    """The column loop of Algorithm 1, one column at a time (Eq. 15 with the Cholesky
+    rows of Step 3): for each j
+
+        v = W[:, j];  Q[:, j] = quant(v);  e = (v - Q[:, j]) / U[j, j]
+        W[:, j:] += - e (x) U[j, j:]  +  v (x) P[j, j:]
+
+    `hint_codes` / `hint_zeros` implement the near-tie protocol of the parity tests:
+    where the pre-rounding value lies within `tau` of a rounding boundary and the
+    hinted integer is the neighbour on the other side of it, the hinted integer is
+    taken.  Returns a dict with codes (uint8), scales, zeros, What (float64), t,
+    and the numbers of hints used.
+    """
+    W = np.array(W, dtype=np.float64, copy=True)
+    m, n = W.shape
+    maxq = float(2 ** bits - 1)
+    if dead is not None:
+        W[:, np.asarray(dead, bool)] = 0.0
+    G = 1 if group <= 0 else n // group
+    if group > 0 and n % group:
+        raise ValueError("n must be a multiple of the group size")
+    codes = np.zeros((m, n), np.uint8)
+    What = np.zeros((m, n))
+    T = np.zeros((m, n))
+    scales = np.zeros((m, G))
+    zeros = np.zeros((m, G))
+    hints_used = 0
+    zero_hints_used = 0
+
+    def params(block, g):
+        nonlocal zero_hints_used
+        s, z = quant_params(block.min(axis=1), block.max(axis=1), bits, sym)
+        if hint_zeros is not None and not sym:
+            xmin = np.minimum(block.min(axis=1), 0.0)
+            r = -xmin / s
+            near = np.abs(np.abs(r - np.floor(r)) - 0.5) < tau
+            hz = hint_zeros[:, g].astype(np.float64)
+            take = near & (np.abs(hz - z) == 1.0)
+            zero_hints_used += int(take.sum())
+            z = np.where(take, hz, z)
+        return s, z
+
+    if group <= 0:
+        scale, zero = params(W, 0)
+        scales[:, 0], zeros[:, 0] = scale, zero
+    for j in range(n):
+        if group > 0 and j % group == 0:
+            g = j // group
+            scale, zero = params(W[:, j:j + group], g)
+            scales[:, g], zeros[:, g] = scale, zero
+        v = W[:, j].copy()
+        if identity_quantizer:
+            q, w_hat, t = np.zeros(m), v.copy(), v / scale
+        else:
+            q, w_hat, t = quantize_column(v, scale, zero, bits)
+            if hint_codes is not None:
+                frac = t - np.floor(t)
+                near = np.abs(frac - 0.5) < tau
+                hq = hint_codes[:, j].astype(np.float64)
+                take = near & (np.abs(hq - q) == 1.0) & (hq >= 0) & (hq <= maxq)
+                hints_used += int(take.sum())
+                q = np.where(take, hq, q)
+                w_hat = scale * (q - zero)
+        codes[:, j] = q.astype(np.uint8)
+        What[:, j] = w_hat
+        T[:, j] = t
+        e = (v - w_hat) / U[j, j]
+        if use_E:
+            W[:, j:] -= np.outer(e, U[j, j:])
+        if use_P:
+            W[:, j:] += np.outer(v, P[j, j:])
+        W[:, j] = w_hat
+    return dict(codes=codes, scales=scales, zeros=zeros, What=What, t=T,
+                hints_used=hints_used, zero_hints_used=zero_hints_used)
+
+
+# ----------------------------------- Algorithm 1 as printed, block size B (Step 4)
+def quantize_layer_blocked(W, U, P, bits, group=0, sym=False, blocksize=128, dead=None):
+    """Algorithm 1 with lazy batching: inside a block of B columns the update is
+    applied at once, the columns after the block receive it once per block (Eq. 18).
+    V keeps each column's value as it stood just before it was quantised."""
+    W = np.array(W, dtype=np.float64, copy=True)
+    m, n = W.shape
+    if dead is not None:
+        W[:, np.asarray(dead, bool)] = 0.0
+    if group > 0 and (n % group or blocksize % group):
+        raise ValueError("group must divide n and the block size")
+    G = 1 if group <= 0 else n // group
+    codes = np.zeros((m, n), np.uint8)
+    What = np.zeros((m, n))
+    scales = np.zeros((m, G))
+    zeros = np.zeros((m, G))
+    if group <= 0:
+        scale, zero = quant_params(W.min(axis=1), W.max(axis=1), bits, sym)
+        scales[:, 0], zeros[:, 0] = scale, zero
+    for i in range(0, n, blocksize):
+        i2 = min(i + blocksize, n)
+        E = np.zeros((m, i2 - i))
+        V = np.zeros((m, i2 - i))
+        for j in range(i, i2):
+            if group > 0 and j % group == 0:
+                g = j // group
+                blk = W[:, j:j + group]
+                scale, zero = quant_params(blk.min(axis=1), blk.max(axis=1), bits, sym)
+                scales[:, g], zeros[:, g] = scale, zero
+            v = W[:, j].copy()
+            q, w_hat, _ = quantize_column(v, scale, zero, bits)
+            codes[:, j] = q.astype(np.uint8)
+            What[:, j] = w_hat
+            E[:, j - i] = (v - w_hat) / U[j, j]
+            V[:, j - i] = v
+            W[:, j:i2] += -np.outer(E[:, j - i], U[j, j:i2]) + np.outer(v, P[j, j:i2])
+            W[:, j] = w_hat
+        W[:, i2:] += -E @ U[i:i2, i2:] + V @ P[i:i2, i2:]
+    return dict(codes=codes, scales=scales, zeros=zeros, What=What)
+
+
+# --------------------------------------------------------------- Eq. 4 objective
+def layer_output_error(W, What, X_bits, Xtilde_bits) -> float:
+    """|| What X - W X~ ||_F^2 (Eq. 4), original W, undamped data."""
+    Xk = bf16_bits_to_f64(X_bits)
+    Xtk = bf16_bits_to_f64(Xtilde_bits)
+    D = np.asarray(What, np.float64) @ Xk.T - np.asarray(W, np.float64) @ Xtk.T
+    return float(np.sum(D * D))
+
+
+def layer_output_error_from_moments(W, What, H, dXXT, C) -> float:
+    """The same objective without touching tokens:  with D = What - W,
+    ||What X - W X~||^2 = tr(D H D^T) - 2 tr(D dXXT^T W^T) + tr(W C W^T),
+    H = X X^T, dXXT = dX X^T, C = dX dX^T (all undamped)."""
+    W = np.asarray(W, np.float64)
+    D = np.asarray(What, np.float64) - W
+    return float(np.sum((D @ H) * D) - 2.0 * np.sum((D @ dXXT.T) * W) + np.sum((W @ C) * W))
+
+
+# ------------------------------------------------------- independent cross-checks
+def gptq_explicit_inverse(W, H_lam, bits, group=0, sym=False):
+    """Plain GPTQ/OBQ in its original form (Eq. 2-3): explicit inverse Hessian, update
+    of the whole row from column q of H^-1, then Gaussian elimination of row/column q.
+    No Cholesky factor anywhere.  Used to pin the dX = 0 case."""
+    W = np.array(W, dtype=np.float64, copy=True)
+    m, n = W.shape
+    Hinv = np.linalg.inv(H_lam)
+    codes = np.zeros((m, n), np.uint8)
+    What = np.zeros((m, n))
+    if group <= 0:
+        scale, zero = quant_params(W.min(axis=1), W.max(axis=1), bits, sym)
+    for q in range(n):
+        if group > 0 and q % group == 0:
+            blk = W[:, q:q + group]
+            scale, zero = quant_params(blk.min(axis=1), blk.max(axis=1), bits, sym)
+        c, w_hat, _ = quantize_column(W[:, q], scale, zero, bits)
+        codes[:, q] = c.astype(np.uint8)
+        What[:, q] = w_hat
+        W += np.outer((w_hat - W[:, q]) / Hinv[q, q], Hinv[q, :])
+        W[:, q] = w_hat
+        Hinv = Hinv - np.outer(Hinv[:, q], Hinv[q, :]) / Hinv[q, q]
+        Hinv[q, :] = 0.0
+        Hinv[:, q] = 0.0
+    return dict(codes=codes, What=What)
+
+
+def gptaq_explicit_inverse(W, H_lam, dXXT, bits, group=0, sym=False):
+    """Eq. 15 taken literally: at column q recompute, from H_lam alone, the inverse of
+    the Hessian of the not-yet-quantised inputs (H~^-1) and of the inputs after q
+    (H~^-1_{-q}), no factor L and no matrix P."""
+    W = np.array(W, dtype=np.float64, copy=True)
+    m, n = W.shape
+    codes = np.zeros((m, n), np.uint8)
+    What = np.zeros((m, n))
+    if group <= 0:
+        scale, zero = quant_params(W.min(axis=1), W.max(axis=1), bits, sym)
+    for q in range(n):
+        if group > 0 and q % group == 0:
+            blk = W[:, q:q + group]
+            scale, zero = quant_params(blk.min(axis=1), blk.max(axis=1), bits, sym)
+        w_q = W[:, q].copy()
+        c, w_hat, _ = quantize_column(w_q, scale, zero, bits)
+        codes[:, q] = c.astype(np.uint8)
+        What[:, q] = w_hat
+        Ht = np.linalg.inv(H_lam[q:, q:])
+        W[:, q:] += np.outer((w_hat - w_q) / Ht[0, 0], Ht[0, :])
+        if q + 1 < n:
+            Hm = np.linalg.inv(H_lam[q + 1:, q + 1:])
+            W[:, q + 1:] += np.outer(w_q, dXXT[q, q + 1:] @ Hm)
+        W[:, q] = w_hat
+    return dict(codes=codes, What=What)
