@@ -1,0 +1,121 @@
+/*
+ * libgptaq - the GPTAQ per-layer asymmetric-calibration solve on one MI355X (gfx950).
+ *
+ * Three stages, in the order of Algorithm 1 of the paper (arXiv 2504.02692):
+ *
+ *   gptaq_accumulate      line 2   : H += X X^T,  dXXT += (X~ - X) X^T   (streamed over tokens)
+ *   gptaq_prepare         lines 3-4: damping, H_lam^-1 = L L^T, U = L^T, and the fused
+ *                                    correction matrix P = ((dXXT L) (.) M_U) L^T (Theorem 4.2)
+ *   gptaq_quantize_layer  lines 5-13: the blocked column loop with lazy trailing updates
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates no
+ *     device memory; scratch comes in through `ws` (size from the matching *_workspace_bytes).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it and the calls return without waiting for the GPU.
+ *   - Matrices are row-major with a leading dimension in ELEMENTS.  Activations are
+ *     token-major, (tokens x n): the transpose of the paper's n x k matrix X.
+ *   - bf16 values travel as uint16_t bit patterns.
+ *   - Return value: GPTAQ_OK or a negative GPTAQ_E* code for argument errors, detected on
+ *     the host before anything is launched.  Numerical trouble (a non-positive pivot) is
+ *     reported asynchronously through the caller's device `info` words.
+ *   - Calls that share a workspace or an output must be ordered by the caller (same stream).
+ */
+#ifndef GPTAQ_H
+#define GPTAQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define GPTAQ_OK             0
+#define GPTAQ_ENULL         -1   /* a required pointer is NULL                              */
+#define GPTAQ_EDIM          -2   /* a dimension or leading dimension is out of range       */
+#define GPTAQ_EUNSUPPORTED  -3   /* bits/group/blocksize combination not supported         */
+#define GPTAQ_EWORKSPACE    -4   /* workspace too small or misaligned (needs 256 B)        */
+#define GPTAQ_ELAUNCH       -5   /* the HIP runtime refused a launch; see gptaq_last_hip_error */
+
+/* Human-readable text for a status code. */
+const char* gptaq_status_string(int status);
+/* hipError_t of the most recent failed launch on this thread (0 if none). */
+int gptaq_last_hip_error(void);
+
+/* ---------------------------------------------------------------------------------------
+ * Algorithm 1, line 2.  H += X^T X and dXXT += (X~ - X)^T X over `tokens` rows of the
+ * token-major bf16 activations X (quantised model's input) and Xtilde (full-precision
+ * model's input).  dXXT[q][j] = sum_t (X~[t][q] - X[t][q]) * X[t][j]  (row: neuron of dX,
+ * column: neuron of X - the row vector dX_{q,:} X^T of Eq. 16).  Plain sums, fp32.
+ *
+ *   X, Xtilde : (tokens x n) bf16, leading dimension ldx >= n, ldx % 8 == 0, 16-byte aligned.
+ *   H         : (n x n) fp32, ldh >= n.  Only the upper triangle (col >= row) is maintained;
+ *               entries below the diagonal of H are never read and are left in an unspecified
+ *               state (gptaq_symmetrize fills them).  Caller zero-initialises before the
+ *               first chunk; call again with more tokens to continue the sums.
+ *   dXXT      : (n x n) fp32, ldh >= n, all entries maintained (not symmetric).
+ *   ws        : >= gptaq_accumulate_workspace_bytes(tokens, n) bytes, 256-byte aligned.  A
+ *               smaller workspace is accepted down to the size for 64 tokens; the chunk is
+ *               then processed in several passes.
+ * dX is formed in fp32 and split exactly into two bf16 terms, so products are exact and
+ * only fp32 accumulation rounding remains.
+ */
+size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n);
+int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                     int64_t ldx, float* H, float* dXXT, int64_t ldh,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* Copies the upper triangle of the n x n fp32 matrix H onto its lower triangle. */
+int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Algorithm 1, lines 3-4.  Consumes H and dXXT.
+ *   dead inputs (H_qq == 0): H_qq <- 1, row q of dXXT <- 0, dead[q] <- 1;
+ *   lambda = damp * mean(diag H)  ("dampened by 1% of the average", end of Section 4.2);
+ *   H + lambda I = V V^T with V upper triangular, U = V^-1, so that (H + lambda I)^-1 = L L^T
+ *   with L = U^T the lower factor of Step 3 / Lemma 4.1 (factorisation in fp64);
+ *   P = ((dXXT L) (.) M_U) L^T = triu(dXXT U^T, 1) U   (Eq. 17).
+ *
+ *   H    : in: upper triangle of H.  out: U (upper triangular, zeros below), fp32.
+ *   dXXT : in: dXXT.                 out: P (strictly upper triangular, zeros elsewhere).
+ *   dead : n bytes, out: 1 for dead inputs else 0.  May be NULL.
+ *   info : 2 x int32, out: info[0] = 0, or 1 + index of the first non-positive pivot (U, P are
+ *          then garbage); info[1] = number of dead inputs.
+ */
+size_t gptaq_prepare_workspace_bytes(int64_t n);
+int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, float damp,
+                  uint8_t* dead, int32_t* info, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------------------
+ * Algorithm 1, lines 5-13.  For every block of `blocksize` columns: quantise column by
+ * column, all m rows in parallel, feeding  -E_j U[j, j:] + v_j P[j, j:]  to the remaining
+ * columns of the block (E_j = (v_j - quant(v_j)) / U_jj, v_j the column's current value
+ * just before it is quantised, Eq. 15), then apply the block's accumulated update to all
+ * later columns at once (Eq. 18).  The result does not depend on blocksize.
+ *
+ *   W      : (m x n) fp32, ldw >= n.  in: weights.  out: dequantised quantised weights (Q).
+ *   U, P   : outputs of gptaq_prepare, read-only, so one prepare serves every layer that
+ *            shares the input (q/k/v, gate/up).
+ *   dead   : n bytes from gptaq_prepare or NULL; dead columns of W are taken as 0.
+ *   bits   : 2..8.  group: columns per (scale, zero) group, <= 0 for one group per row
+ *            (range taken from the original row); else n % group == 0, blocksize % group == 0
+ *            and group <= 128.  Group ranges come from the current (error-compensated)
+ *            weights at the group's first column.  sym != 0: symmetric grid, zero = 2^(bits-1).
+ *   blocksize : 1..128.
+ *   codes  : (m x n) uint8, one code per byte, leading dimension n.
+ *   scales, zeros : (m x G) fp32, G = max(1, n / group); zeros hold integers.
+ * Quantiser: range [min(0,min w), max(0,max w)], scale = (max-min)/(2^bits-1),
+ * zero = rint(-min/scale), q = clamp(rint(w/scale)+zero), rint = half-to-even.
+ */
+size_t gptaq_quantize_workspace_bytes(int64_t m, int64_t n);
+int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
+                         const float* U, const float* P, int64_t ldh, const uint8_t* dead,
+                         int bits, int group, int sym, int blocksize,
+                         uint8_t* codes, float* scales, float* zeros,
+                         void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GPTAQ_H */

@@ -1,0 +1,148 @@
+"""Thin ctypes binding of libgptaq.so.  Argument marshalling only: every step of the solve
+runs in the library's HIP kernels.  torch is used for device memory and the current stream.
+
+The functions carry the names of the C entry points (include/gptaq.h).  There is no CPU or
+PyTorch fallback: if the shared library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgptaq.so")
+_lib: Optional[ctypes.CDLL] = None
+
+_c = ctypes
+_SIGS = {
+    "gptaq_status_string": (_c.c_char_p, [_c.c_int]),
+    "gptaq_last_hip_error": (_c.c_int, []),
+    "gptaq_accumulate_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64]),
+    "gptaq_accumulate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
+                                    _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "gptaq_symmetrize": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p]),
+    "gptaq_prepare_workspace_bytes": (_c.c_size_t, [_c.c_int64]),
+    "gptaq_prepare": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_float,
+                                 _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "gptaq_quantize_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64]),
+    "gptaq_quantize_layer": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p,
+                                        _c.c_int64, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                        _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
+                                        _c.c_void_p]),
+}
+EXPORTS = tuple(_SIGS)
+
+
+class GptaqError(RuntimeError):
+    pass
+
+
+def load() -> ctypes.CDLL:
+    """Load libgptaq.so (built by paper_2504_02692_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise GptaqError(f"{LIB_PATH} is missing: build it with `python -m paper_2504_02692_amd.build` "
+                             "(there is no fallback path)")
+        lib = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        lib = load()
+        msg = lib.gptaq_status_string(status).decode()
+        raise GptaqError(f"{what}: {msg} (status {status}, hip error {lib.gptaq_last_hip_error()})")
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _need(t: torch.Tensor, dtype, name: str) -> None:
+    if not t.is_cuda or t.dtype != dtype or t.dim() != 2 or t.stride(1) != 1:
+        raise GptaqError(f"{name}: expected a 2-D row-major {dtype} CUDA tensor")
+
+
+def workspace(nbytes: int, device="cuda") -> torch.Tensor:
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def gptaq_accumulate_workspace_bytes(tokens: int, n: int) -> int:
+    return load().gptaq_accumulate_workspace_bytes(tokens, n)
+
+
+def gptaq_prepare_workspace_bytes(n: int) -> int:
+    return load().gptaq_prepare_workspace_bytes(n)
+
+
+def gptaq_quantize_workspace_bytes(m: int, n: int) -> int:
+    return load().gptaq_quantize_workspace_bytes(m, n)
+
+
+def gptaq_accumulate(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXXT: torch.Tensor,
+                     ws: torch.Tensor) -> None:
+    """H += X^T X (upper triangle), dXXT += (Xtilde - X)^T X for token-major bf16 X, Xtilde."""
+    _need(X, torch.bfloat16, "X"); _need(Xtilde, torch.bfloat16, "Xtilde")
+    _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
+    tokens, n = X.shape
+    if Xtilde.shape != X.shape or Xtilde.stride(0) != X.stride(0) or H.shape != (n, n) or dXXT.shape != (n, n) \
+            or H.stride(0) != dXXT.stride(0):
+        raise GptaqError("gptaq_accumulate: shape mismatch")
+    _check(load().gptaq_accumulate(_ptr(X), _ptr(Xtilde), tokens, n, X.stride(0), _ptr(H), _ptr(dXXT),
+                                   H.stride(0), _ptr(ws), ws.numel(), _stream()), "gptaq_accumulate")
+
+
+def gptaq_symmetrize(H: torch.Tensor) -> None:
+    _need(H, torch.float32, "H")
+    _check(load().gptaq_symmetrize(_ptr(H), H.shape[0], H.stride(0), _stream()), "gptaq_symmetrize")
+
+
+def gptaq_prepare(H: torch.Tensor, dXXT: torch.Tensor, damp: float, ws: torch.Tensor,
+                  dead: Optional[torch.Tensor] = None, info: Optional[torch.Tensor] = None):
+    """In place: H -> U = L^T (upper), dXXT -> P (strictly upper).  Returns (dead, info) device tensors."""
+    _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
+    n = H.shape[0]
+    if H.shape != (n, n) or dXXT.shape != (n, n) or H.stride(0) != dXXT.stride(0):
+        raise GptaqError("gptaq_prepare: shape mismatch")
+    if dead is None:
+        dead = torch.empty(n, dtype=torch.uint8, device=H.device)
+    if info is None:
+        info = torch.empty(2, dtype=torch.int32, device=H.device)
+    _check(load().gptaq_prepare(_ptr(H), _ptr(dXXT), n, H.stride(0), float(damp), _ptr(dead), _ptr(info),
+                                _ptr(ws), ws.numel(), _stream()), "gptaq_prepare")
+    return dead, info
+
+
+def gptaq_quantize_layer(W: torch.Tensor, U: torch.Tensor, P: torch.Tensor, bits: int, group: int, sym: bool,
+                         blocksize: int, ws: torch.Tensor, dead: Optional[torch.Tensor] = None,
+                         codes: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
+                         zeros: Optional[torch.Tensor] = None):
+    """In place: W -> dequantised quantised weights.  Returns (codes, scales, zeros)."""
+    _need(W, torch.float32, "W"); _need(U, torch.float32, "U"); _need(P, torch.float32, "P")
+    m, n = W.shape
+    if U.shape != (n, n) or P.shape != (n, n) or U.stride(0) != P.stride(0):
+        raise GptaqError("gptaq_quantize_layer: shape mismatch")
+    G = max(1, n // group) if group > 0 else 1
+    if codes is None:
+        codes = torch.empty((m, n), dtype=torch.uint8, device=W.device)
+    if scales is None:
+        scales = torch.empty((m, G), dtype=torch.float32, device=W.device)
+    if zeros is None:
+        zeros = torch.empty((m, G), dtype=torch.float32, device=W.device)
+    _check(load().gptaq_quantize_layer(_ptr(W), m, n, W.stride(0), _ptr(U), _ptr(P), U.stride(0), _ptr(dead),
+                                       int(bits), int(group), int(bool(sym)), int(blocksize), _ptr(codes),
+                                       _ptr(scales), _ptr(zeros), _ptr(ws), ws.numel(), _stream()),
+           "gptaq_quantize_layer")
+    return codes, scales, zeros

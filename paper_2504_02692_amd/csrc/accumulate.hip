@@ -1,0 +1,136 @@
+// Algorithm 1, line 2:  H += X X^T,  dXXT += (X~ - X) X^T, streamed over token chunks.
+//
+// Two steps per chunk.  (1) A bandwidth-bound pass reads the token-major bf16 X and X~,
+// forms dX = X~ - X in fp32, splits it exactly into two bf16 terms (hi = rne(dX),
+// lo = dX - hi) and writes X, hi, lo transposed, i.e. neuron-major with tokens contiguous,
+// which is the operand layout the MFMA GEMM wants (K-contiguous rows on both sides).
+// (2) One launch of the MFMA GEMM computes dXXT += hi X^T + lo X^T on all tiles and
+// H += X X^T on the tiles that touch the upper triangle.
+#include "common.h"
+
+namespace gptaq {
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
+  __bf16 b = (__bf16)f;                       // v_cvt_pk_bf16_f32: round to nearest even
+  return (uint32_t)__builtin_bit_cast(uint16_t, b);
+}
+
+// grid: (n_pad / 64, c_pad / 64).  Writes zeros where the source is out of range, so the
+// GEMM can run on whole tiles.
+__global__ __launch_bounds__(256) void split_transpose_kernel(
+    const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xt, int64_t ldx,
+    int tokens, int n, uint16_t* __restrict__ oX, uint16_t* __restrict__ oHi,
+    uint16_t* __restrict__ oLo, int64_t ldo) {
+  constexpr int LS = 72;                                  // padded LDS row, 144 bytes
+  __shared__ __attribute__((aligned(16))) uint16_t sx[64 * LS], sh[64 * LS], sl[64 * LS];
+  const int n0 = blockIdx.x * 64, t0 = blockIdx.y * 64;
+  const int tid = threadIdx.x, r = tid >> 3, c = tid & 7;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int t = t0 + r + 32 * p, col = n0 + c * 8;
+    u32x4 a = {0, 0, 0, 0}, b = {0, 0, 0, 0};
+    if (t < tokens && col < n) {
+      a = *reinterpret_cast<const u32x4*>(X + (int64_t)t * ldx + col);
+      b = *reinterpret_cast<const u32x4*>(Xt + (int64_t)t * ldx + col);
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t xa = (a[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+      const uint32_t xb = (b[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+      const float d = bf16_to_f32(xb) - bf16_to_f32(xa);
+      const uint32_t hi = f32_to_bf16_rne(d);
+      const uint32_t lo = f32_to_bf16_rne(d - bf16_to_f32(hi));
+      const int o = (c * 8 + e) * LS + r + 32 * p;
+      sx[o] = (uint16_t)xa;
+      sh[o] = (uint16_t)hi;
+      sl[o] = (uint16_t)lo;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    const int nl = r + 32 * p;
+    const int64_t g = (int64_t)(n0 + nl) * ldo + t0 + c * 8;
+    *reinterpret_cast<u32x4*>(oX + g) = *reinterpret_cast<const u32x4*>(sx + nl * LS + c * 8);
+    *reinterpret_cast<u32x4*>(oHi + g) = *reinterpret_cast<const u32x4*>(sh + nl * LS + c * 8);
+    *reinterpret_cast<u32x4*>(oLo + g) = *reinterpret_cast<const u32x4*>(sl + nl * LS + c * 8);
+  }
+}
+
+__global__ void symmetrize_kernel(float* H, int n, int64_t ldh) {
+  __shared__ float t[32][33];
+  const int bi = blockIdx.y, bj = blockIdx.x;
+  if (bj < bi) return;                                     // handle pairs once, from the upper side
+  const int i = bi * 32 + threadIdx.y, j = bj * 32 + threadIdx.x;
+  if (i < n && j < n) t[threadIdx.y][threadIdx.x] = H[(int64_t)i * ldh + j];
+  __syncthreads();
+  const int li = bj * 32 + threadIdx.y, lj = bi * 32 + threadIdx.x;   // transposed position
+  if (li < n && lj < n && li > lj) H[(int64_t)li * ldh + lj] = t[threadIdx.x][threadIdx.y];
+}
+
+static int64_t padded_n(int64_t n) { return round_up(n, gemm_tile_for(n, n)); }
+
+}  // namespace gptaq
+
+using namespace gptaq;
+
+extern "C" size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n) {
+  if (tokens <= 0 || n <= 0) return 0;
+  const int64_t c = round_up(tokens < 16384 ? tokens : 16384, kGemmBK);
+  return (size_t)(3 * padded_n(n) * c * 2);
+}
+
+extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens,
+                                int64_t n, int64_t ldx, float* H, float* dXXT, int64_t ldh,
+                                void* ws, size_t ws_bytes, void* stream) {
+  if (!X || !Xtilde || !H || !dXXT || !ws) return GPTAQ_ENULL;
+  if (tokens < 0 || n <= 0 || n % 8 || ldx < n || ldx % 8 || ldh < n || n > (1 << 20) ||
+      tokens > (int64_t)1 << 30)
+    return GPTAQ_EDIM;
+  if (((uintptr_t)X | (uintptr_t)Xtilde) & 15) return GPTAQ_EDIM;
+  if ((uintptr_t)ws & 255) return GPTAQ_EWORKSPACE;
+  if (tokens == 0) return GPTAQ_OK;
+  hipStream_t s = (hipStream_t)stream;
+  const int tile = gemm_tile_for(n, n);
+  const int64_t np = padded_n(n);
+  int64_t cmax = (int64_t)(ws_bytes / (size_t)(6 * np)) / kGemmBK * kGemmBK;
+  if (cmax < kGemmBK) return GPTAQ_EWORKSPACE;
+  if (cmax > 32768) cmax = 32768;    // keeps one fp32 running sum short (accuracy), and K in int32
+  for (int64_t t0 = 0; t0 < tokens; t0 += cmax) {
+    const int64_t c = tokens - t0 < cmax ? tokens - t0 : cmax;
+    const int64_t cp = round_up(c, kGemmBK);
+    uint16_t* oX = (uint16_t*)ws;
+    uint16_t* oHi = oX + np * cp;
+    uint16_t* oLo = oHi + np * cp;
+    hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)),
+                       dim3(256), 0, s, X + t0 * ldx, Xtilde + t0 * ldx, ldx, (int)c, (int)n,
+                       oX, oHi, oLo, cp);
+    GPTAQ_LAUNCH_CHECK();
+    GemmBatch b;
+    b.nprob = 2;
+    b.tile = tile;
+    GemmProblem& a = b.p[0];
+    a.C = dXXT; a.ldc = ldh; a.M = (int)n; a.N = (int)n; a.K = (int)cp;
+    a.tiles_m = a.tiles_n = (int)(np / tile);
+    a.nseg = 2; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
+    a.seg[0] = {oHi, oX, cp, cp};
+    a.seg[1] = {oLo, oX, cp, cp};
+    GemmProblem& h = b.p[1];
+    h = a;
+    h.C = H; h.nseg = 1; h.tile_mode = 1;
+    h.seg[0] = {oX, oX, cp, cp};
+    hipError_t e = launch_gemm(b, s);
+    if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+  }
+  return GPTAQ_OK;
+}
+
+extern "C" int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream) {
+  if (!H) return GPTAQ_ENULL;
+  if (n <= 0 || ldh < n || n > (1 << 20)) return GPTAQ_EDIM;
+  const unsigned g = (unsigned)((n + 31) / 32);
+  hipLaunchKernelGGL(symmetrize_kernel, dim3(g, g), dim3(32, 32), 0, (hipStream_t)stream, H, (int)n, ldh);
+  GPTAQ_LAUNCH_CHECK();
+  return GPTAQ_OK;
+}

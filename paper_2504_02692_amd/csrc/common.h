@@ -1,0 +1,60 @@
+// Internal declarations shared by the translation units of libgptaq (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/gptaq.h"
+
+namespace gptaq {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+constexpr int kGemmBK = 64;          // bf16 elements per k-tile of the MFMA GEMM
+constexpr int kMaxSeg = 6;
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// One K-segment of a split GEMM: rows of L and R are K-contiguous bf16.
+struct GemmSeg {
+  const uint16_t* L;
+  const uint16_t* R;
+  int64_t ldl, ldr;
+};
+
+// C (+)= sum_s L_s R_s^T.  Operand buffers are zero-padded to whole tiles in rows and to a
+// multiple of kGemmBK in K, so the main loop needs no bounds checks; stores are bounded by
+// M and N.
+struct GemmProblem {
+  float* C;
+  int64_t ldc;
+  int32_t M, N, K;       // K per segment (multiple of kGemmBK)
+  int32_t tiles_m, tiles_n;
+  int32_t nseg;
+  int32_t tile_mode;     // 0: all tiles; 1: tiles lying entirely below the diagonal are skipped
+  int32_t k_mode;        // 0: all k; 1: k >= first column of the tile; 2: tile row0 <= k < tile col end
+  int32_t store_mode;    // 0: C += acc; 1: C = acc; 2: C = acc where col > row, else 0
+  GemmSeg seg[kMaxSeg];
+};
+
+struct GemmBatch {
+  int32_t nprob;
+  int32_t tile;          // 128 or 256 (square block tile)
+  GemmProblem p[2];
+};
+
+// Enqueue the batch; problems are scheduled in order (put the heavier one first).
+hipError_t launch_gemm(const GemmBatch& b, hipStream_t s);
+// Row padding the GEMM expects from an operand with `rows` logical rows.
+inline int gemm_tile_for(int64_t M, int64_t N) { return (M >= 1024 && N >= 1024) ? 256 : 128; }
+
+void set_last_hip_error(hipError_t e);
+
+#define GPTAQ_LAUNCH_CHECK()                                   \
+  do {                                                         \
+    hipError_t e__ = hipGetLastError();                        \
+    if (e__ != hipSuccess) { set_last_hip_error(e__); return GPTAQ_ELAUNCH; } \
+  } while (0)
+
+}  // namespace gptaq

@@ -1,0 +1,320 @@
+// Algorithm 1, lines 5-13: the blocked column loop and the lazy trailing update.
+//
+// Column loop (lines 7-10).  A wavefront owns R rows of W and keeps their slice of the
+// active block (up to 128 columns) in registers, two columns per lane.  The block's
+// U = L^T rows and P rows (128 x 128 fp32 each) live in LDS, shared by the workgroup's four
+// wavefronts.  For column j the wave broadcasts v = W[r][j] out of the owning lane,
+// quantises it (every lane redundantly, the value is wave-uniform), and each lane applies
+//   W[r][j'] += -E_j U[j][j'] + v P[j][j']          (Eq. 15 in the form of Algorithm 1)
+// to its two columns; U and P are zero left of the diagonal so no lane masking is needed.
+// Group ranges are wave reductions (min/max over the lanes that hold the group).
+// The kernel leaves the quantised block in W, the codes, and -E and V (the pre-quantisation
+// columns) split into bf16 hi+lo as the left operand of the trailing GEMM.
+//
+// Trailing update (lines 11-12, Eq. 18):  W[:, i+B:] += [-E | V] [U; P][i:i+B, i+B:] on the
+// MFMA GEMM with three bf16 cross products per term (fp32-accurate).
+#include "common.h"
+
+namespace gptaq {
+
+constexpr int QB = 128;                       // widest block the column-loop kernel holds
+constexpr int Q_LDS = 2 * QB * QB * 4 + QB * 4;
+
+__device__ __forceinline__ uint16_t q_bf16_rne(float f) {
+  __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(uint16_t, b);
+}
+__device__ __forceinline__ float q_bf16_f32(uint16_t h) { return __uint_as_float((uint32_t)h << 16); }
+
+__device__ __forceinline__ float wave_min(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fminf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Uniform affine min-max grid with 0 inside the range.  The few operations per group are done
+// in fp64 so that the fp32 scale is the correctly rounded (xmax - xmin) / maxq.
+__device__ __forceinline__ void grid_params(float xmin, float xmax, float maxq, int sym, float& scale, float& zero) {
+  double lo = fmin((double)xmin, 0.0), hi = fmax((double)xmax, 0.0);
+  if (sym) { hi = fmax(fabs(lo), hi); lo = -hi; }
+  if (lo == 0.0 && hi == 0.0) { lo = -1.0; hi = 1.0; }
+  scale = (float)((hi - lo) / (double)maxq);
+  zero = sym ? (maxq + 1.f) * 0.5f : (float)rint(-lo / (double)scale);
+}
+
+// One wavefront per row: range of the whole (original) row -> one (scale, zero) per row.
+__global__ __launch_bounds__(256) void row_params_kernel(const float* W, int64_t ldw, int m, int n, const uint8_t* dead,
+                                                         float maxq, int sym, float* scales, float* zeros) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= m) return;
+  float mn = 0.f, mx = 0.f;
+  for (int c = lane; c < n; c += 64) {
+    float v = W[(int64_t)row * ldw + c];
+    if (dead && dead[c]) v = 0.f;
+    mn = fminf(mn, v);
+    mx = fmaxf(mx, v);
+  }
+  mn = wave_min(mn);
+  mx = wave_max(mx);
+  float sc, zr;
+  grid_params(mn, mx, maxq, sym, sc, zr);
+  if (lane == 0) { scales[row] = sc; zeros[row] = zr; }
+}
+
+struct QuantArgs {
+  float* W; int64_t ldw; int m, n, i0, bw;
+  const float* U; const float* P; int64_t ldh;
+  const uint8_t* dead;
+  float maxq; int group, sym, G;
+  float* scales; float* zeros; uint8_t* codes;
+  uint16_t *Eh, *El, *Vh, *Vl;          // (rows x 128) bf16, -E and V split hi/lo
+};
+
+template <int R>
+__global__ __launch_bounds__(256) void quant_block_kernel(QuantArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  float* Us = reinterpret_cast<float*>(smem_raw);
+  float* Ps = Us + QB * QB;
+  float* dinv = Ps + QB * QB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int i0 = a.i0, bw = a.bw;
+
+  for (int idx = tid; idx < QB * QB; idx += 256) {
+    const int r = idx >> 7, c = idx & 127;
+    float u = 0.f, p = 0.f;
+    if (r < bw && c < bw && c >= r) {
+      const int64_t o = (int64_t)(i0 + r) * a.ldh + i0 + c;
+      u = a.U[o];
+      if (c > r) p = a.P[o];
+    }
+    Us[idx] = u;
+    Ps[idx] = p;
+  }
+  if (tid < QB) dinv[tid] = tid < bw ? 1.f / a.U[(int64_t)(i0 + tid) * a.ldh + i0 + tid] : 0.f;
+
+  const int row0 = (blockIdx.x * 4 + wave) * R;
+  float w0[R], w1[R], c0[R], c1[R], e0[R], e1[R], v0[R], v1[R], sc[R], zr[R], isc[R];
+  const bool col0 = lane < bw && !(a.dead && a.dead[i0 + lane]);
+  const bool col1 = lane + 64 < bw && !(a.dead && a.dead[i0 + 64 + lane]);
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int row = row0 + r;
+    const bool ok = row < a.m;
+    w0[r] = ok && col0 ? a.W[(int64_t)row * a.ldw + i0 + lane] : 0.f;
+    w1[r] = ok && col1 ? a.W[(int64_t)row * a.ldw + i0 + 64 + lane] : 0.f;
+    c0[r] = c1[r] = e0[r] = e1[r] = v0[r] = v1[r] = 0.f;
+    sc[r] = 1.f; zr[r] = 0.f;
+    if (a.group <= 0 && ok) { sc[r] = a.scales[row]; zr[r] = a.zeros[row]; }
+    isc[r] = 1.f / sc[r];
+  }
+  __syncthreads();
+
+  for (int j = 0; j < bw; ++j) {
+    const int jl = j & 63;
+    const bool second = j >= 64;
+    if (a.group > 0 && (i0 + j) % a.group == 0) {
+      const int jend = j + a.group;
+      const bool in0 = lane >= j && lane < jend, in1 = lane + 64 >= j && lane + 64 < jend;
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        float mn = fminf(in0 ? w0[r] : 0.f, in1 ? w1[r] : 0.f);
+        float mx = fmaxf(in0 ? w0[r] : 0.f, in1 ? w1[r] : 0.f);
+        mn = wave_min(mn);
+        mx = wave_max(mx);
+        grid_params(mn, mx, a.maxq, a.sym, sc[r], zr[r]);
+        isc[r] = 1.f / sc[r];
+        const int row = row0 + r;
+        if (lane == 0 && row < a.m) {
+          const int64_t o = (int64_t)row * a.G + (i0 + j) / a.group;
+          a.scales[o] = sc[r];
+          a.zeros[o] = zr[r];
+        }
+      }
+    }
+    const float u0 = Us[j * QB + lane], u1 = Us[j * QB + 64 + lane];
+    const float p0 = Ps[j * QB + lane], p1 = Ps[j * QB + 64 + lane];
+    const float dj = dinv[j];
+    const bool mine = lane == jl;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float src = second ? w1[r] : w0[r];
+      const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(src), jl));
+      const float t = v * isc[r];
+      const float q = fminf(fmaxf(rintf(t) + zr[r], 0.f), a.maxq);
+      const float wh = sc[r] * (q - zr[r]);
+      const float ne = (wh - v) * dj;                   // -E_j
+      if (!second) {
+        w0[r] = fmaf(v, p0, fmaf(ne, u0, w0[r]));
+        if (mine) { w0[r] = wh; c0[r] = q; e0[r] = ne; v0[r] = v; }
+      }
+      w1[r] = fmaf(v, p1, fmaf(ne, u1, w1[r]));
+      if (second && mine) { w1[r] = wh; c1[r] = q; e1[r] = ne; v1[r] = v; }
+    }
+  }
+
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int row = row0 + r;
+    if (row >= a.m) continue;
+    if (lane < bw) {
+      a.W[(int64_t)row * a.ldw + i0 + lane] = w0[r];
+      a.codes[(int64_t)row * a.n + i0 + lane] = (uint8_t)c0[r];
+    }
+    if (lane + 64 < bw) {
+      a.W[(int64_t)row * a.ldw + i0 + 64 + lane] = w1[r];
+      a.codes[(int64_t)row * a.n + i0 + 64 + lane] = (uint8_t)c1[r];
+    }
+    const int64_t o = (int64_t)row * QB + lane;
+    uint16_t h;
+    h = q_bf16_rne(e0[r]); a.Eh[o] = h; a.El[o] = q_bf16_rne(e0[r] - q_bf16_f32(h));
+    h = q_bf16_rne(e1[r]); a.Eh[o + 64] = h; a.El[o + 64] = q_bf16_rne(e1[r] - q_bf16_f32(h));
+    h = q_bf16_rne(v0[r]); a.Vh[o] = h; a.Vl[o] = q_bf16_rne(v0[r] - q_bf16_f32(h));
+    h = q_bf16_rne(v1[r]); a.Vh[o + 64] = h; a.Vl[o + 64] = q_bf16_rne(v1[r] - q_bf16_f32(h));
+  }
+}
+
+// Right operands of the trailing GEMM: rows i0..i0+bw of U and P restricted to the columns
+// after the block, transposed to (column x 128) and split into bf16 hi+lo.
+// grid (ceil(ntrail_padded / 64), 2): blockIdx.y = 0 for U, 1 for P.
+__global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* U, const float* P, int64_t ldh, int n,
+                                                                   int i0, int bw, int i2, uint16_t* Uth, uint16_t* Utl,
+                                                                   uint16_t* Pth, uint16_t* Ptl) {
+  __shared__ uint16_t th[64][QB + 2], tl[64][QB + 2];
+  const float* S = blockIdx.y ? P : U;
+  uint16_t* oh = blockIdx.y ? Pth : Uth;
+  uint16_t* ol = blockIdx.y ? Ptl : Utl;
+  const int j0 = blockIdx.x * 64;
+  const int c = threadIdx.x & 63, kq = threadIdx.x >> 6;
+  const int col = i2 + j0 + c;
+  for (int p = 0; p < QB / 4; ++p) {
+    const int kk = kq + 4 * p;
+    float v = 0.f;
+    if (kk < bw && col < n) v = S[(int64_t)(i0 + kk) * ldh + col];
+    const uint16_t h = q_bf16_rne(v);
+    th[c][kk] = h;
+    tl[c][kk] = q_bf16_rne(v - q_bf16_f32(h));
+  }
+  __syncthreads();
+  // 64 rows x 128 bf16 = 64 x 64 dwords; thread t writes dword (t & 63) of rows (t >> 6) + 4p
+  const int d = threadIdx.x & 63;
+  for (int p = 0; p < 16; ++p) {
+    const int r = (threadIdx.x >> 6) + 4 * p;
+    const uint32_t vh = (uint32_t)th[r][2 * d] | ((uint32_t)th[r][2 * d + 1] << 16);
+    const uint32_t vl = (uint32_t)tl[r][2 * d] | ((uint32_t)tl[r][2 * d + 1] << 16);
+    reinterpret_cast<uint32_t*>(oh + (int64_t)(j0 + r) * QB)[d] = vh;
+    reinterpret_cast<uint32_t*>(ol + (int64_t)(j0 + r) * QB)[d] = vl;
+  }
+}
+
+}  // namespace gptaq
+
+using namespace gptaq;
+
+namespace {
+struct QLayout {
+  int64_t mp, np;
+  size_t off[8], total;
+};
+QLayout q_layout(int64_t m, int64_t n) {
+  QLayout L;
+  L.mp = round_up(m, 256);
+  L.np = round_up(n, 256);
+  size_t o = 0;
+  for (int i = 0; i < 8; ++i) {
+    L.off[i] = o;
+    o += (size_t)((i < 4 ? L.mp : L.np) * QB * 2);
+  }
+  L.total = o;
+  return L;
+}
+bool g_q_attr = false;
+
+template <int R>
+void launch_quant(const QuantArgs& a, hipStream_t s) {
+  const int rows_per_wg = 4 * R;
+  hipLaunchKernelGGL(quant_block_kernel<R>, dim3((a.m + rows_per_wg - 1) / rows_per_wg), dim3(256), Q_LDS, s, a);
+}
+}  // namespace
+
+extern "C" size_t gptaq_quantize_workspace_bytes(int64_t m, int64_t n) {
+  if (m <= 0 || n <= 0) return 0;
+  return q_layout(m, n).total;
+}
+
+extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
+                                    int64_t ldh, const uint8_t* dead, int bits, int group, int sym, int blocksize,
+                                    uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  if (!W || !U || !P || !codes || !scales || !zeros || !ws) return GPTAQ_ENULL;
+  if (m <= 0 || n <= 0 || ldw < n || ldh < n || m > (1 << 24) || n > (1 << 24)) return GPTAQ_EDIM;
+  if (bits < 2 || bits > 8 || blocksize < 1 || blocksize > QB) return GPTAQ_EUNSUPPORTED;
+  if (group > 0 && (n % group || blocksize % group || group > QB)) return GPTAQ_EUNSUPPORTED;
+  if ((uintptr_t)ws & 255) return GPTAQ_EWORKSPACE;
+  const QLayout L = q_layout(m, n);
+  if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  if (!g_q_attr) {
+    const void* fns[4] = {(const void*)&quant_block_kernel<1>, (const void*)&quant_block_kernel<2>,
+                          (const void*)&quant_block_kernel<4>, (const void*)&quant_block_kernel<8>};
+    for (const void* f : fns) {
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Q_LDS);
+      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+    }
+    g_q_attr = true;
+  }
+  unsigned char* base = (unsigned char*)ws;
+  uint16_t* buf[8];
+  for (int i = 0; i < 8; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
+
+  QuantArgs a;
+  a.W = W; a.ldw = ldw; a.m = (int)m; a.n = (int)n;
+  a.U = U; a.P = P; a.ldh = ldh; a.dead = dead;
+  a.maxq = (float)((1 << bits) - 1); a.group = group; a.sym = sym;
+  a.G = group > 0 ? (int)(n / group) : 1;
+  a.scales = scales; a.zeros = zeros; a.codes = codes;
+  a.Eh = buf[0]; a.El = buf[1]; a.Vh = buf[2]; a.Vl = buf[3];
+  uint16_t *Uth = buf[4], *Utl = buf[5], *Pth = buf[6], *Ptl = buf[7];
+
+  if (group <= 0) {
+    hipLaunchKernelGGL(row_params_kernel, dim3((unsigned)((m + 3) / 4)), dim3(256), 0, s, W, ldw, (int)m, (int)n, dead,
+                       a.maxq, sym, scales, zeros);
+    GPTAQ_LAUNCH_CHECK();
+  }
+  for (int64_t i0 = 0; i0 < n; i0 += blocksize) {
+    const int bw = (int)(n - i0 < blocksize ? n - i0 : blocksize);
+    const int64_t i2 = i0 + bw;
+    a.i0 = (int)i0; a.bw = bw;
+    if (m <= 1024) launch_quant<1>(a, s);
+    else if (m <= 2048) launch_quant<2>(a, s);
+    else if (m <= 8192) launch_quant<4>(a, s);
+    else launch_quant<8>(a, s);
+    GPTAQ_LAUNCH_CHECK();
+    if (i2 >= n) break;
+    const int64_t nt = n - i2;
+    const int tile = gemm_tile_for(m, nt);
+    const int64_t ntp = round_up(nt, tile);
+    hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(ntp / 64), 2), dim3(256), 0, s, U, P, ldh, (int)n,
+                       (int)i0, bw, (int)i2, Uth, Utl, Pth, Ptl);
+    GPTAQ_LAUNCH_CHECK();
+    GemmBatch b;
+    b.nprob = 1; b.tile = tile;
+    GemmProblem& g = b.p[0];
+    g.C = W + i2; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = QB;
+    g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(ntp / tile);
+    g.nseg = 6; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
+    g.seg[0] = {a.Eh, Uth, QB, QB};
+    g.seg[1] = {a.Eh, Utl, QB, QB};
+    g.seg[2] = {a.El, Uth, QB, QB};
+    g.seg[3] = {a.Vh, Pth, QB, QB};
+    g.seg[4] = {a.Vh, Ptl, QB, QB};
+    g.seg[5] = {a.Vl, Pth, QB, QB};
+    hipError_t e = launch_gemm(b, s);
+    if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+  }
+  return GPTAQ_OK;
+}

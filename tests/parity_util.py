@@ -1,0 +1,81 @@
+"""Helpers shared by the GPU parity tests: move seeded inputs to the device, run the HIP
+path through the binding, and compare with the fp64 oracle (near-tie protocol included)."""
+import numpy as np
+import torch
+
+from oracle import gptaq_oracle as O
+from paper_2504_02692_amd import binding as B
+
+TAU = 5e-5          # half-width of the near-tie window, in units of one quantisation step
+MAX_HINT_FRAC = 1e-4
+
+
+def to_dev_bf16(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16).copy()).cuda().view(torch.bfloat16)
+
+
+def rel_fro(a, b) -> float:
+    a = np.asarray(a, np.float64); b = np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+def gpu_accumulate(Xb, Xtb, chunks=None, ws_bytes=None):
+    tokens, n = Xb.shape
+    X, Xt = to_dev_bf16(Xb), to_dev_bf16(Xtb)
+    H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
+    A = torch.zeros_like(H)
+    bounds = [0, tokens] if not chunks else chunks
+    for t0, t1 in zip(bounds[:-1], bounds[1:]):
+        nb = B.gptaq_accumulate_workspace_bytes(t1 - t0, n) if ws_bytes is None else ws_bytes
+        ws = B.workspace(nb)
+        B.gptaq_accumulate(X[t0:t1], Xt[t0:t1], H, A, ws)
+    torch.cuda.synchronize()
+    return H, A
+
+
+def gpu_prepare(H, A, damp):
+    n = H.shape[0]
+    ws = B.workspace(B.gptaq_prepare_workspace_bytes(n))
+    dead, info = B.gptaq_prepare(H, A, damp, ws)
+    torch.cuda.synchronize()
+    return dead, info
+
+
+def gpu_quantize(W, U, P, bits, group, sym, blocksize, dead=None):
+    Wd = torch.from_numpy(np.asarray(W, np.float32).copy()).cuda()
+    m, n = Wd.shape
+    ws = B.workspace(B.gptaq_quantize_workspace_bytes(m, n))
+    codes, scales, zeros = B.gptaq_quantize_layer(Wd, U, P, bits, group, sym, blocksize, ws, dead=dead)
+    torch.cuda.synchronize()
+    return dict(What=Wd.cpu().numpy(), codes=codes.cpu().numpy(), scales=scales.cpu().numpy(),
+                zeros=zeros.cpu().numpy())
+
+
+def check_against_oracle(W, U64, P64, got, bits, group, sym, dead=None, Xb=None, Xtb=None, label=""):
+    """The parity bar: raw code mismatches reported; with near-tie hints (|frac - 1/2| < TAU, at most
+    1e-4 of the entries) every code, zero and scale must agree and the dequantised weights must
+    match to 1e-4 relative; the layer output error must agree to 0.5 %."""
+    W = np.asarray(W, np.float64)
+    m, n = W.shape
+    raw = O.quantize_layer(W, U64, P64, bits, group, sym, dead=dead)
+    raw_mis = float((raw["codes"] != got["codes"]).mean())
+    hinted = O.quantize_layer(W, U64, P64, bits, group, sym, dead=dead,
+                              hint_codes=got["codes"], hint_zeros=got["zeros"], tau=TAU)
+    nh = hinted["hints_used"] + hinted["zero_hints_used"]
+    print(f"[{label}] raw code mismatch {raw_mis:.3e}; hints used {nh} of {m * n}")
+    assert nh <= max(1, MAX_HINT_FRAC * m * n), f"{nh} near-tie hints"
+    assert np.array_equal(hinted["zeros"], got["zeros"].astype(np.float64)), "zero points differ"
+    ds = float(np.max(np.abs(hinted["scales"] - got["scales"]) / hinted["scales"]))
+    print(f"[{label}] largest relative scale difference {ds:.3e}")
+    assert ds <= 1e-4, "scales differ"
+    mism = int((hinted["codes"] != got["codes"]).sum())
+    assert mism == 0, f"{mism} codes differ after near-tie hints"
+    rf = rel_fro(got["What"], hinted["What"])
+    print(f"[{label}] dequantised weights rel. Frobenius error {rf:.3e}")
+    assert rf <= 1e-4
+    if Xb is not None:
+        e_gpu = O.layer_output_error(W, got["What"], Xb, Xtb)
+        e_ref = O.layer_output_error(W, raw["What"], Xb, Xtb)
+        print(f"[{label}] layer output error gpu {e_gpu:.6e} oracle {e_ref:.6e}")
+        assert abs(e_gpu - e_ref) <= 5e-3 * e_ref
+    return raw_mis, nh

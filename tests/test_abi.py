@@ -1,0 +1,74 @@
+"""The C-ABI library builds, loads, exports every symbol include/gptaq.h declares, and
+rejects bad arguments on the host before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "gptaq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gptaq_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2504_02692_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2504_02692_amd import build
+        build.build(verbose=False)
+    return binding.load()
+
+
+def test_header_symbols_are_exported(lib):
+    from paper_2504_02692_amd import binding
+    names = declared_symbols()
+    assert len(names) >= 9
+    for name in names:
+        assert hasattr(lib, name), name
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    from paper_2504_02692_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", "/nonexistent/libgptaq.so")
+    with pytest.raises(binding.GptaqError):
+        binding.load()
+
+
+def test_workspace_queries(lib):
+    assert lib.gptaq_accumulate_workspace_bytes(4096, 512) == 3 * 512 * 4096 * 2
+    assert lib.gptaq_accumulate_workspace_bytes(262144, 4096) == 3 * 4096 * 16384 * 2
+    assert lib.gptaq_accumulate_workspace_bytes(0, 512) == 0
+    assert lib.gptaq_prepare_workspace_bytes(512) > 512 * 512 * 8
+    assert lib.gptaq_quantize_workspace_bytes(512, 512) == 8 * 512 * 128 * 2
+    assert lib.gptaq_status_string(0) == b"ok"
+
+
+def test_argument_errors_are_reported_before_any_launch(lib):
+    one = ctypes.c_void_p(256)      # a non-null, aligned, never dereferenced address
+    null = ctypes.c_void_p(0)
+    f = lib.gptaq_accumulate
+    assert f(null, one, 64, 64, 64, one, one, 64, one, 1 << 20, null) == -1
+    assert f(one, one, 64, 60, 64, one, one, 64, one, 1 << 20, null) == -2          # n % 8
+    assert f(one, one, 64, 64, 32, one, one, 64, one, 1 << 20, null) == -2          # ldx < n
+    assert f(one, one, 64, 64, 64, one, one, 64, one, 16, null) == -4               # workspace
+    assert f(one, one, 64, 64, 64, one, one, 64, ctypes.c_void_p(264), 1 << 20, null) == -4
+    assert f(one, one, 0, 64, 64, one, one, 64, one, 1 << 20, null) == 0            # empty chunk: no-op
+    p = lib.gptaq_prepare
+    assert p(one, one, 64, 64, 0.01, null, null, one, 1 << 30, null) == -1          # info required
+    assert p(one, one, 64, 32, 0.01, null, one, one, 1 << 30, null) == -2
+    assert p(one, one, 64, 64, 0.01, null, one, one, 1024, null) == -4
+    q = lib.gptaq_quantize_layer
+    ok = (one, 64, 64, 64, one, one, 64, null)
+    assert q(*ok, 1, 0, 0, 128, one, one, one, one, 1 << 30, null) == -3            # bits
+    assert q(*ok, 4, 48, 0, 128, one, one, one, one, 1 << 30, null) == -3           # n % group
+    assert q(*ok, 4, 32, 0, 48, one, one, one, one, 1 << 30, null) == -3            # blocksize % group
+    assert q(*ok, 4, 0, 0, 256, one, one, one, one, 1 << 30, null) == -3            # blocksize > 128
+    assert q(*ok, 4, 0, 0, 128, one, one, one, one, 16, null) == -4
+    assert b"workspace" in lib.gptaq_status_string(-4)

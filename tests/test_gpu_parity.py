@@ -1,0 +1,175 @@
+"""Parity of the HIP path (through the C ABI) with the fp64 oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gptaq_oracle as O
+from paper_2504_02692_amd import synth
+from tests import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def c1():
+    wl = synth.workload("c1")
+    Xb, Xtb = synth.make_activations(wl.tokens, 512, wl.seed, "x", wl.n_outliers, wl.outlier_scale, wl.noise)
+    W = synth.make_weights(512, 512, wl.seed, "fc")
+    H, A = O.accumulate(Xb, Xtb)
+    U, P, dead = O.prepare(H, A, wl.damp)
+    return dict(wl=wl, Xb=Xb, Xtb=Xtb, W=W, H=H, A=A, U=U, P=P)
+
+
+def upper_to_full(Hd):
+    h = Hd.cpu().numpy().astype(np.float64)
+    return np.triu(h) + np.triu(h, 1).T
+
+
+# ------------------------------------------------------------------ accumulate
+def test_accumulate_c1(c1):
+    Hd, Ad = PU.gpu_accumulate(c1["Xb"], c1["Xtb"])
+    eh, ea = PU.rel_fro(upper_to_full(Hd), c1["H"]), PU.rel_fro(Ad.cpu().numpy(), c1["A"])
+    print(f"H rel. Frobenius {eh:.3e}  dXXT rel. Frobenius {ea:.3e}")
+    assert eh <= 1e-5 and ea <= 1e-5
+
+
+def test_accumulate_streamed_chunks_and_small_workspace(c1):
+    # three unequal chunks, the last one through a workspace that only holds 128 tokens
+    Hd, Ad = PU.gpu_accumulate(c1["Xb"], c1["Xtb"], chunks=[0, 1000, 3000, 4096],
+                               ws_bytes=3 * 512 * 128 * 2)
+    assert PU.rel_fro(upper_to_full(Hd), c1["H"]) <= 1e-5
+    assert PU.rel_fro(Ad.cpu().numpy(), c1["A"]) <= 1e-5
+
+
+@pytest.mark.parametrize("tokens,n", [(1, 8), (77, 200), (333, 1096), (640, 2304)])
+def test_accumulate_ragged_shapes(tokens, n):
+    Xb, Xtb = synth.make_activations(tokens, n, 4, "rag", 3, 20.0)
+    H, A = O.accumulate(Xb, Xtb)
+    Hd, Ad = PU.gpu_accumulate(Xb, Xtb)
+    assert PU.rel_fro(upper_to_full(Hd), H) <= 1e-5
+    assert PU.rel_fro(Ad.cpu().numpy(), A) <= 1e-5
+
+
+def test_symmetrize(c1):
+    from paper_2504_02692_amd import binding as B
+    Hd, _ = PU.gpu_accumulate(c1["Xb"], c1["Xtb"])
+    B.gptaq_symmetrize(Hd)
+    h = Hd.cpu().numpy()
+    assert np.array_equal(h, h.T)
+    assert PU.rel_fro(h, c1["H"]) <= 1e-5
+
+
+# --------------------------------------------------------------------- prepare
+def run_prepare(H64, A64, damp):
+    n = H64.shape[0]
+    Hd = torch.from_numpy(np.triu(H64).astype(np.float32)).cuda()      # lower triangle deliberately absent
+    Ad = torch.from_numpy(A64.astype(np.float32)).cuda()
+    dead, info = PU.gpu_prepare(Hd, Ad, damp)
+    return Hd, Ad, dead, info
+
+
+def test_prepare_c1(c1):
+    Ud, Pd, dead, info = run_prepare(c1["H"], c1["A"], c1["wl"].damp)
+    assert info.cpu().tolist() == [0, 0]
+    U, P = Ud.cpu().numpy(), Pd.cpu().numpy()
+    assert np.all(np.tril(U, -1) == 0) and np.all(np.tril(P) == 0)
+    eu, ep = PU.rel_fro(U, c1["U"]), PU.rel_fro(P, c1["P"])
+    print(f"U rel. Frobenius {eu:.3e}  P rel. Frobenius {ep:.3e}")
+    assert eu <= 1e-6 and ep <= 5e-5
+
+
+@pytest.mark.parametrize("n,k", [(8, 64), (100, 400), (200, 1000), (1160, 2400)])
+def test_prepare_ragged_sizes(n, k):
+    Xb, Xtb = synth.make_activations(k, n, 5, "prep", 2, 20.0)
+    H, A = O.accumulate(Xb, Xtb)
+    U, P, _ = O.prepare(H, A, 0.01)
+    Ud, Pd, dead, info = run_prepare(H, A, 0.01)
+    assert info.cpu().tolist() == [0, 0]
+    assert PU.rel_fro(Ud.cpu().numpy(), U) <= 1e-6
+    assert PU.rel_fro(Pd.cpu().numpy(), P) <= 5e-5
+
+
+def test_prepare_reports_dead_inputs_and_bad_pivots():
+    Xb, Xtb = synth.make_activations(300, 96, 6, "dead", 2, 20.0)
+    Xb = Xb.copy(); Xb[:, 17] = 0
+    H, A = O.accumulate(Xb, Xtb)
+    U, P, dead = O.prepare(H, A, 0.01)
+    Ud, Pd, dd, info = run_prepare(H, A, 0.01)
+    assert info.cpu().tolist() == [0, 1]
+    assert dd.cpu().numpy().astype(bool).tolist() == dead.tolist()
+    assert PU.rel_fro(Ud.cpu().numpy(), U) <= 1e-6 and PU.rel_fro(Pd.cpu().numpy(), P) <= 5e-5
+    # an indefinite "Hessian" with no damping: the factorisation must flag a pivot, not hang or fault
+    Hbad = np.eye(70); Hbad[40, 40] = -1.0
+    _, _, _, info = run_prepare(Hbad, np.zeros((70, 70)), 0.0)
+    assert info.cpu().tolist()[0] == 41
+
+
+# -------------------------------------------------------------------- quantize
+def dev(a):
+    return torch.from_numpy(np.asarray(a, np.float32).copy()).cuda()
+
+
+def test_quantize_c1_from_oracle_factors(c1):
+    """Column loop + trailing update in isolation: U, P come from the oracle (rounded to fp32)."""
+    wl = c1["wl"]
+    U32, P32 = c1["U"].astype(np.float32), c1["P"].astype(np.float32)
+    got = PU.gpu_quantize(c1["W"], dev(U32), dev(P32), wl.bits, wl.group, wl.sym, wl.blocksize)
+    PU.check_against_oracle(c1["W"], U32.astype(np.float64), P32.astype(np.float64), got, wl.bits, wl.group,
+                            wl.sym, Xb=c1["Xb"], Xtb=c1["Xtb"], label="c1 loop only")
+
+
+def test_whole_path_c1(c1):
+    """accumulate -> prepare -> quantize, all on the GPU, against the all-fp64 oracle."""
+    wl = c1["wl"]
+    Hd, Ad = PU.gpu_accumulate(c1["Xb"], c1["Xtb"])
+    dead, info = PU.gpu_prepare(Hd, Ad, wl.damp)
+    assert info.cpu().tolist() == [0, 0]
+    got = PU.gpu_quantize(c1["W"], Hd, Ad, wl.bits, wl.group, wl.sym, wl.blocksize)
+    PU.check_against_oracle(c1["W"], c1["U"], c1["P"], got, wl.bits, wl.group, wl.sym,
+                            Xb=c1["Xb"], Xtb=c1["Xtb"], label="c1 whole path")
+
+
+@pytest.mark.parametrize("bits,group,sym,blocksize,m,n", [
+    (4, 128, False, 128, 512, 512),      # W4 g128 (Llama-7B setting)
+    (3, 128, False, 128, 300, 512),      # W3 g128, ragged rows
+    (2, 64, False, 128, 512, 512),       # W2 g64
+    (3, 128, True, 128, 512, 512),       # symmetric, 3-bit (weight-only setting)
+    (4, 0, True, 128, 512, 512),         # per-channel symmetric
+    (4, 32, False, 96, 200, 480),        # block not a power of two, ragged last block
+    (4, 0, False, 50, 64, 130),          # tiny, ragged everything
+    (8, 16, False, 16, 1100, 256),       # two rows per wavefront
+    (4, 128, False, 128, 2500, 384),     # four rows per wavefront
+    (4, 64, False, 64, 8200, 256),       # eight rows per wavefront
+])
+def test_quantize_variants(c1, bits, group, sym, blocksize, m, n):
+    Hn = c1["H"][:n, :n]; An = c1["A"][:n, :n]
+    U, P, _ = O.prepare(Hn, An, 0.01)
+    U32, P32 = U.astype(np.float32), P.astype(np.float32)
+    W = synth.make_weights(m, n, 3, f"v{m}x{n}")
+    got = PU.gpu_quantize(W, dev(U32), dev(P32), bits, group, sym, blocksize)
+    PU.check_against_oracle(W, U32.astype(np.float64), P32.astype(np.float64), got, bits, group, sym,
+                            label=f"W{bits} g{group} sym{int(sym)} B{blocksize} {m}x{n}")
+
+
+def test_quantize_does_not_depend_on_blocksize(c1):
+    U32, P32 = c1["U"].astype(np.float32), c1["P"].astype(np.float32)
+    W = c1["W"][:256]
+    outs = [PU.gpu_quantize(W, dev(U32), dev(P32), 4, 16, False, B) for B in (16, 64, 128)]
+    for o in outs[1:]:
+        # lazy batching only re-associates sums: a handful of near-tie flips at most
+        assert (o["codes"] != outs[0]["codes"]).mean() <= 1e-4
+    again = PU.gpu_quantize(W, dev(U32), dev(P32), 4, 16, False, 128)
+    assert np.array_equal(again["codes"], outs[2]["codes"]) and np.array_equal(again["What"], outs[2]["What"])
+
+
+def test_quantize_with_dead_input():
+    Xb, Xtb = synth.make_activations(600, 128, 8, "deadq", 2, 20.0)
+    Xb = Xb.copy(); Xb[:, 70] = 0
+    W = synth.make_weights(96, 128, 8, "deadq")
+    H, A = O.accumulate(Xb, Xtb)
+    U, P, dead = O.prepare(H, A, 0.01)
+    Hd, Ad = PU.gpu_accumulate(Xb, Xtb)
+    dd, info = PU.gpu_prepare(Hd, Ad, 0.01)
+    got = PU.gpu_quantize(W, Hd, Ad, 4, 0, False, 128, dead=dd)
+    assert np.all(got["What"][:, 70] == 0)
+    PU.check_against_oracle(W, U, P, got, 4, 0, False, dead=dead, Xb=Xb, Xtb=Xtb, label="dead input")
