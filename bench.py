@@ -1,0 +1,180 @@
+#!/usr/bin/env python3
+"""Benchmark of the GPTAQ per-layer solve on one MI355X.
+
+A "step" is one pass of the whole hot path over one transformer block's layer set:
+for every distinct layer input  H, dXXT <- accumulate over all calibration tokens,
+U, P <- prepare; then for every layer that reads that input  quantize_layer.
+Inputs are synthetic (paper_2504_02692_amd/synth.py) and resident in HBM before the timed
+region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 16384]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+
+
+def cpu_baseline(wl, budget_s: float = 20.0):
+    """Times the fp64 oracle (as it stands) on a bounded sample of the first layer's problem and
+    extrapolates each stage by its exact operation count to one average layer of the workload."""
+    import threadpoolctl  # noqa: F401  (only to report the BLAS thread count)
+    from oracle import gptaq_oracle as O
+    from paper_2504_02692_amd import synth
+    cores = os.cpu_count() or 1
+    try:
+        cores = max(i["num_threads"] for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else cores
+    except Exception:
+        pass
+    n_s, tok_s, m_s = 1024, 8192, 64
+    Xb, Xtb = synth.make_activations(tok_s, n_s, wl.seed, "cpu", wl.n_outliers, wl.outlier_scale, wl.noise,
+                                     empirical_sigma=False)
+    W = synth.make_weights(m_s, n_s, wl.seed, "cpu")
+    t0 = time.perf_counter(); H, A = O.accumulate(Xb, Xtb); t_acc = time.perf_counter() - t0
+    t0 = time.perf_counter(); U, P, dead = O.prepare(H, A, wl.damp); t_prep = time.perf_counter() - t0
+    t0 = time.perf_counter(); O.quantize_layer(W, U, P, wl.bits, wl.group, wl.sym); t_q = time.perf_counter() - t0
+    # operation counts: accumulate ~ n^2 k, prepare ~ n^3, quantize ~ m n^2
+    acc = sum(n * n * wl.tokens for n in wl.inputs().values()) / (n_s * n_s * tok_s) * t_acc
+    prep = sum(n ** 3 for n in wl.inputs().values()) / n_s ** 3 * t_prep
+    quant = sum(l.m * l.n * l.n for l in wl.layers) / (m_s * n_s * n_s) * t_q
+    ms_per_layer = (acc + prep + quant) * 1e3 / len(wl.layers)
+    return {"value": ms_per_layer, "unit": "ms/layer", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 numpy oracle timed on n={n_s}, {tok_s} tokens, {m_s} rows "
+                      f"(accumulate {t_acc:.2f}s, prepare {t_prep:.2f}s, quantize {t_q:.2f}s), each stage scaled by "
+                      f"its operation count (n^2 k, n^3, m n^2) to the workload's layer set: extrapolated"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="llama7b")
+    ap.add_argument("--chunk", type=int, default=16384, help="tokens per gptaq_accumulate call")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the solve has no collective step); use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2504_02692_amd import binding as B
+    from paper_2504_02692_amd import synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU", file=sys.stderr)
+        return 2
+    B.load()
+    dev = torch.device("cuda:0")
+    wl = synth.workload(args.workload)
+    inputs = wl.inputs()
+
+    # ---- resident inputs
+    acts = {iid: synth.make_activations_device(wl.tokens, n, wl.seed, iid, dev, wl.n_outliers, wl.outlier_scale,
+                                               wl.noise) for iid, n in inputs.items()}
+    W0 = {l.name: synth.make_weights_device(l.m, l.n, wl.seed, l.name, dev) for l in wl.layers}
+    rounds = args.steps + args.warmup
+    Wwork = {l.name: [W0[l.name].clone() for _ in range(rounds)] for l in wl.layers}
+    HA = {iid: (torch.empty((n, n), device=dev), torch.empty((n, n), device=dev)) for iid, n in inputs.items()}
+    nmax, mmax = max(inputs.values()), max(l.m for l in wl.layers)
+    ws_acc = B.workspace(B.gptaq_accumulate_workspace_bytes(args.chunk, nmax))
+    ws_prep = B.workspace(B.gptaq_prepare_workspace_bytes(nmax))
+    ws_q = B.workspace(B.gptaq_quantize_workspace_bytes(mmax, nmax))
+    outs = {l.name: (torch.empty((l.m, l.n), dtype=torch.uint8, device=dev),
+                     torch.empty((l.m, max(1, l.n // wl.group) if wl.group > 0 else 1), device=dev),
+                     torch.empty((l.m, max(1, l.n // wl.group) if wl.group > 0 else 1), device=dev))
+            for l in wl.layers}
+    info = {iid: torch.zeros(2, dtype=torch.int32, device=dev) for iid in inputs}
+    dead = {iid: torch.zeros(n, dtype=torch.uint8, device=dev) for iid, n in inputs.items()}
+    stage_ms = {"accumulate": 0.0, "prepare": 0.0, "quantize": 0.0}
+
+    def step(r: int, ev=None):
+        for iid, n in inputs.items():
+            X, Xt = acts[iid]
+            H, A = HA[iid]
+            if ev: ev[0].record()
+            H.zero_(); A.zero_()
+            for t0 in range(0, wl.tokens, args.chunk):
+                t1 = min(wl.tokens, t0 + args.chunk)
+                B.gptaq_accumulate(X[t0:t1], Xt[t0:t1], H, A, ws_acc)
+            if ev: ev[1].record()
+            B.gptaq_prepare(H, A, wl.damp, ws_prep, dead=dead[iid], info=info[iid])
+            if ev: ev[2].record()
+            for l in wl.layers:
+                if l.input_id != iid:
+                    continue
+                c, s, z = outs[l.name]
+                B.gptaq_quantize_layer(Wwork[l.name][r], H, A, wl.bits, wl.group, wl.sym, wl.blocksize, ws_q,
+                                       dead=dead[iid], codes=c, scales=s, zeros=z)
+            if ev:
+                ev[3].record(); ev[3].synchronize()
+                stage_ms["accumulate"] += ev[0].elapsed_time(ev[1])
+                stage_ms["prepare"] += ev[1].elapsed_time(ev[2])
+                stage_ms["quantize"] += ev[2].elapsed_time(ev[3])
+
+    for r in range(args.warmup):
+        step(r)
+    torch.cuda.synchronize()
+    B.gptaq_profile_enable(1 << 0)            # only the dominant kernel is bracketed in the timed region
+    t_start = time.perf_counter()
+    for r in range(args.warmup, rounds):
+        step(r)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    launches, gemm_ms = B.gptaq_profile_read(0)
+    B.gptaq_profile_enable(0)
+    for iid in inputs:
+        assert info[iid].cpu().tolist()[0] == 0, "factorisation reported a non-positive pivot"
+
+    # stage and kernel split: one extra, untimed pass with every kernel bracketed
+    Wwork = {l.name: [W0[l.name].clone()] for l in wl.layers}
+    B.gptaq_profile_enable((1 << len(B.PROFILE_TAGS)) - 1)
+    step(0, ev=[torch.cuda.Event(enable_timing=True) for _ in range(4)])
+    torch.cuda.synchronize()
+    prof = {name: B.gptaq_profile_read(i) for i, name in enumerate(B.PROFILE_TAGS)}
+    B.gptaq_profile_enable(0)
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    n_layers = len(wl.layers)
+    # dominant kernel: the accumulate MFMA GEMM.  Algorithmic flop per launch = n(n+1)c [H, upper half]
+    # + 2 n^2 c [dXXT] for a pass over c tokens of an n-wide input.
+    flops = 0.0
+    for iid, n in inputs.items():
+        flops += (n * (n + 1) + 2 * n * n) * float(wl.tokens)
+    flops *= args.steps
+    achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    out = {
+        "metric": "ms_per_layer_solve", "value": ms_per_step / n_layers, "unit": "ms/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 MFMA -> fp32 (fp64 factor)",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: " + ", ".join(f"{l.name} {l.m}x{l.n}" for l in wl.layers) +
+                               f"; {wl.tokens} tokens; W{wl.bits} g{wl.group} {'sym' if wl.sym else 'asym'} "
+                               f"B{wl.blocksize}; accumulate chunk {args.chunk}",
+                   "layers_per_step": n_layers},
+        "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel<256> (accumulate: H and dXXT)",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "launches": launches, "avg_launch_ms": gemm_ms / max(1, launches)},
+        "stages_ms_per_step": stage_ms,
+        "kernels_ms_per_step": {k: v[1] for k, v in prof.items()},
+        "kernel_launches_per_step": {k: v[0] for k, v in prof.items()},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -115,6 +115,21 @@ int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
                          uint8_t* codes, float* scales, float* zeros,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* ---------------------------------------------------------------------------------------
+ * Measurement aid (not part of the method).  While enabled, the library brackets its kernels
+ * with HIP events on the caller's stream, grouped by tag:
+ *   0 accumulate MFMA GEMM (H and dXXT, one launch per pass)   1 accumulate split/transpose pass
+ *   2 factorisation + triangular inverse sweep (whole sweep)    3 the two Theorem-4.2 GEMMs
+ *   4 column-loop kernel (one per block)                        5 trailing-update GEMM (one per block)
+ *   6 trailing operand split/transpose
+ * gptaq_profile_enable(mask) clears the records and records the tags whose bit (1 << tag) is set
+ * in `mask`; 0 stops recording.
+ * gptaq_profile_read waits for the recorded events and returns the number of bracketed
+ * launches of `tag` and their summed duration in milliseconds.  Not thread-safe.
+ */
+int gptaq_profile_enable(int mask);
+int gptaq_profile_read(int tag, int64_t* launches, double* total_ms);
+
 #ifdef __cplusplus
 }
 #endif

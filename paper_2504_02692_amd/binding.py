@@ -32,8 +32,12 @@ _SIGS = {
                                         _c.c_int64, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                         _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                         _c.c_void_p]),
+    "gptaq_profile_enable": (_c.c_int, [_c.c_int]),
+    "gptaq_profile_read": (_c.c_int, [_c.c_int, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_double)]),
 }
 EXPORTS = tuple(_SIGS)
+PROFILE_TAGS = ("accumulate_gemm", "accumulate_split", "factor_sweep", "p_gemm", "column_loop", "trailing_gemm",
+                "trailing_split")
 
 
 class GptaqError(RuntimeError):
@@ -146,3 +150,15 @@ def gptaq_quantize_layer(W: torch.Tensor, U: torch.Tensor, P: torch.Tensor, bits
                                        _ptr(scales), _ptr(zeros), _ptr(ws), ws.numel(), _stream()),
            "gptaq_quantize_layer")
     return codes, scales, zeros
+
+
+def gptaq_profile_enable(mask: int) -> None:
+    """Record the kernels whose tag bit (1 << tag) is set in `mask`; 0 switches recording off."""
+    _check(load().gptaq_profile_enable(int(mask)), "gptaq_profile_enable")
+
+
+def gptaq_profile_read(tag: int):
+    """(launches, total milliseconds) of the kernels bracketed under `tag` since profiling was enabled."""
+    n, ms = _c.c_int64(0), _c.c_double(0.0)
+    _check(load().gptaq_profile_read(int(tag), _c.byref(n), _c.byref(ms)), "gptaq_profile_read")
+    return n.value, ms.value

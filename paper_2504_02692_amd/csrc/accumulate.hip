@@ -103,9 +103,12 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
     uint16_t* oX = (uint16_t*)ws;
     uint16_t* oHi = oX + np * cp;
     uint16_t* oLo = oHi + np * cp;
-    hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)),
-                       dim3(256), 0, s, X + t0 * ldx, Xtilde + t0 * ldx, ldx, (int)c, (int)n,
-                       oX, oHi, oLo, cp);
+    {
+      ProfScope ps(kProfAccumSplit, s);
+      hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)),
+                         dim3(256), 0, s, X + t0 * ldx, Xtilde + t0 * ldx, ldx, (int)c, (int)n,
+                         oX, oHi, oLo, cp);
+    }
     GPTAQ_LAUNCH_CHECK();
     GemmBatch b;
     b.nprob = 2;
@@ -120,7 +123,11 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
     h = a;
     h.C = H; h.nseg = 1; h.tile_mode = 1;
     h.seg[0] = {oX, oX, cp, cp};
-    hipError_t e = launch_gemm(b, s);
+    hipError_t e;
+    {
+      ProfScope ps(kProfAccumGemm, s);
+      e = launch_gemm(b, s);
+    }
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   }
   return GPTAQ_OK;

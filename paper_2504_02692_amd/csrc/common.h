@@ -51,6 +51,17 @@ inline int gemm_tile_for(int64_t M, int64_t N) { return (M >= 1024 && N >= 1024)
 
 void set_last_hip_error(hipError_t e);
 
+// Optional per-kernel timing with HIP events (gptaq_profile_* in the public header).
+enum ProfTag { kProfAccumGemm = 0, kProfAccumSplit = 1, kProfFactor = 2, kProfPGemm = 3, kProfColumnLoop = 4,
+               kProfTrailGemm = 5, kProfTrailSplit = 6, kProfTags = 7 };
+bool prof_enabled(int tag);
+void prof_mark(int tag, hipStream_t s, bool begin);
+struct ProfScope {
+  int tag; hipStream_t s; bool on;
+  ProfScope(int t, hipStream_t st) : tag(t), s(st), on(prof_enabled(t)) { if (on) prof_mark(tag, s, true); }
+  ~ProfScope() { if (on) prof_mark(tag, s, false); }
+};
+
 #define GPTAQ_LAUNCH_CHECK()                                   \
   do {                                                         \
     hipError_t e__ = hipGetLastError();                        \

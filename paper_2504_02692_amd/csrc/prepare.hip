@@ -365,6 +365,8 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
                      lam, F, n);
   GPTAQ_LAUNCH_CHECK();
 
+  {
+  ProfScope sweep_scope(kProfFactor, s);
   Sweep a;
   a.F = F; a.ldf = n; a.n = ni; a.nblk = (int)((n + NB - 1) / NB); a.Dinv = Dinv; a.info = info;
   for (int kb = a.nblk - 1; kb >= 0; --kb) {
@@ -385,6 +387,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
     }
   }
 
+  }
   // U -> H (fp32) and the bf16 splits; dXXT (dead rows zeroed) split.
   const int64_t np = L.np;
   uint16_t *Uh = bb[0], *Ul = bb[1], *Uth = bb[2], *Utl = bb[3], *Ah = bb[4], *Al = bb[5];
@@ -406,7 +409,11 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   g.seg[0] = {Ah, Uh, np, np};
   g.seg[1] = {Ah, Ul, np, np};
   g.seg[2] = {Al, Uh, np, np};
-  hipError_t e = launch_gemm(b, s);
+  hipError_t e;
+  {
+    ProfScope ps(kProfPGemm, s);
+    e = launch_gemm(b, s);
+  }
   if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   // split O (reuses the dXXT split buffers), then P = O U: P[i][j] = sum_{i < a <= j} O[i][a] U[a][j]
   hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)np), dim3(256), 0, s, Obuf, np,
@@ -416,7 +423,10 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   g.seg[0] = {Ah, Uth, np, np};
   g.seg[1] = {Ah, Utl, np, np};
   g.seg[2] = {Al, Uth, np, np};
-  e = launch_gemm(b, s);
+  {
+    ProfScope ps(kProfPGemm, s);
+    e = launch_gemm(b, s);
+  }
   if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   return GPTAQ_OK;
 }

@@ -289,17 +289,23 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
     const int bw = (int)(n - i0 < blocksize ? n - i0 : blocksize);
     const int64_t i2 = i0 + bw;
     a.i0 = (int)i0; a.bw = bw;
-    if (m <= 1024) launch_quant<1>(a, s);
-    else if (m <= 2048) launch_quant<2>(a, s);
-    else if (m <= 8192) launch_quant<4>(a, s);
-    else launch_quant<8>(a, s);
+    {
+      ProfScope ps(kProfColumnLoop, s);
+      if (m <= 1024) launch_quant<1>(a, s);
+      else if (m <= 2048) launch_quant<2>(a, s);
+      else if (m <= 8192) launch_quant<4>(a, s);
+      else launch_quant<8>(a, s);
+    }
     GPTAQ_LAUNCH_CHECK();
     if (i2 >= n) break;
     const int64_t nt = n - i2;
     const int tile = gemm_tile_for(m, nt);
     const int64_t ntp = round_up(nt, tile);
-    hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(ntp / 64), 2), dim3(256), 0, s, U, P, ldh, (int)n,
-                       (int)i0, bw, (int)i2, Uth, Utl, Pth, Ptl);
+    {
+      ProfScope ps(kProfTrailSplit, s);
+      hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(ntp / 64), 2), dim3(256), 0, s, U, P, ldh,
+                         (int)n, (int)i0, bw, (int)i2, Uth, Utl, Pth, Ptl);
+    }
     GPTAQ_LAUNCH_CHECK();
     GemmBatch b;
     b.nprob = 1; b.tile = tile;
@@ -313,7 +319,11 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
     g.seg[3] = {a.Vh, Pth, QB, QB};
     g.seg[4] = {a.Vh, Ptl, QB, QB};
     g.seg[5] = {a.Vl, Pth, QB, QB};
-    hipError_t e = launch_gemm(b, s);
+    hipError_t e;
+    {
+      ProfScope ps(kProfTrailGemm, s);
+      e = launch_gemm(b, s);
+    }
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   }
   return GPTAQ_OK;
