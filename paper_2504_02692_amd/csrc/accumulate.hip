@@ -2,8 +2,9 @@
 //
 // Two steps per chunk.  (1) A bandwidth-bound pass reads the token-major bf16 X and X~,
 // forms dX = X~ - X in fp32, splits it exactly into two bf16 terms (hi = rne(dX),
-// lo = dX - hi) and writes X, hi, lo transposed, i.e. neuron-major with tokens contiguous,
-// which is the operand layout the MFMA GEMM wants (K-contiguous rows on both sides).
+// lo = dX - hi) and writes X, hi, lo transposed in k-tile-major order: [token tile of 64]
+// [neuron][64 tokens], the operand layout the MFMA GEMM wants (tokens are its K dimension and
+// a block of neurons x one token tile is a single contiguous run).
 // (2) One launch of the MFMA GEMM computes dXXT += hi X^T + lo X^T on all tiles and
 // H += X X^T on the tiles that touch the upper triangle.
 #include "common.h"
@@ -21,7 +22,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 __global__ __launch_bounds__(256) void split_transpose_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xt, int64_t ldx,
     int tokens, int n, uint16_t* __restrict__ oX, uint16_t* __restrict__ oHi,
-    uint16_t* __restrict__ oLo, int64_t ldo) {
+    uint16_t* __restrict__ oLo, int64_t ldo /* padded rows */) {
   constexpr int LS = 72;                                  // padded LDS row, 144 bytes
   __shared__ __attribute__((aligned(16))) uint16_t sx[64 * LS], sh[64 * LS], sl[64 * LS];
   const int n0 = blockIdx.x * 64, t0 = blockIdx.y * 64;
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(256) void split_transpose_kernel(
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     const int nl = r + 32 * p;
-    const int64_t g = (int64_t)(n0 + nl) * ldo + t0 + c * 8;
+    const int64_t g = ((int64_t)blockIdx.y * ldo + n0 + nl) * 64 + c * 8;      // k-tile-major
     *reinterpret_cast<u32x4*>(oX + g) = *reinterpret_cast<const u32x4*>(sx + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oHi + g) = *reinterpret_cast<const u32x4*>(sh + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oLo + g) = *reinterpret_cast<const u32x4*>(sl + nl * LS + c * 8);
@@ -107,7 +108,7 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
       ProfScope ps(kProfAccumSplit, s);
       hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)),
                          dim3(256), 0, s, X + t0 * ldx, Xtilde + t0 * ldx, ldx, (int)c, (int)n,
-                         oX, oHi, oLo, cp);
+                         oX, oHi, oLo, np);
     }
     GPTAQ_LAUNCH_CHECK();
     GemmBatch b;
@@ -117,12 +118,12 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
     a.C = dXXT; a.ldc = ldh; a.M = (int)n; a.N = (int)n; a.K = (int)cp;
     a.tiles_m = a.tiles_n = (int)(np / tile);
     a.nseg = 2; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
-    a.seg[0] = {oHi, oX, cp, cp};
-    a.seg[1] = {oLo, oX, cp, cp};
+    a.seg[0] = {oHi, oX, 64, 64, np * 64, np * 64};
+    a.seg[1] = {oLo, oX, 64, 64, np * 64, np * 64};
     GemmProblem& h = b.p[1];
     h = a;
-    h.C = H; h.nseg = 1; h.tile_mode = 1;
-    h.seg[0] = {oX, oX, cp, cp};
+    h.C = H; h.nseg = 1; h.tile_mode = 2;
+    h.seg[0] = {oX, oX, 64, 64, np * 64, np * 64};
     hipError_t e;
     {
       ProfScope ps(kProfAccumGemm, s);

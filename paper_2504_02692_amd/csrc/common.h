@@ -16,11 +16,16 @@ constexpr int kMaxSeg = 6;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
-// One K-segment of a split GEMM: rows of L and R are K-contiguous bf16.
+// One K-segment of a split GEMM.  Element (row, k) of an operand sits at
+// base + row * ld + (k / 64) * kt + k % 64:  ld = K, kt = 64 for a plain row-major K-contiguous
+// matrix;  ld = 64, kt = rows * 64 for the k-tile-major layout, in which the 64-wide k-tile of a
+// block of rows is one contiguous run (no power-of-two row stride, so the tile's lines spread
+// over all memory channels).
 struct GemmSeg {
   const uint16_t* L;
   const uint16_t* R;
   int64_t ldl, ldr;
+  int64_t ktl, ktr;
 };
 
 // C (+)= sum_s L_s R_s^T.  Operand buffers are zero-padded to whole tiles in rows and to a
@@ -32,7 +37,8 @@ struct GemmProblem {
   int32_t M, N, K;       // K per segment (multiple of kGemmBK)
   int32_t tiles_m, tiles_n;
   int32_t nseg;
-  int32_t tile_mode;     // 0: all tiles; 1: tiles lying entirely below the diagonal are skipped
+  int32_t tile_mode;     // 0: all tiles; 1: tiles entirely below the diagonal do no work (but store);
+                         // 2: square problem, only tiles with tile column >= tile row are scheduled
   int32_t k_mode;        // 0: all k; 1: k >= first column of the tile; 2: tile row0 <= k < tile col end
   int32_t store_mode;    // 0: C += acc; 1: C = acc; 2: C = acc where col > row, else 0
   GemmSeg seg[kMaxSeg];
@@ -41,6 +47,8 @@ struct GemmProblem {
 struct GemmBatch {
   int32_t nprob;
   int32_t tile;          // 128 or 256 (square block tile)
+  int32_t debug;         // experiment switches (0 in production)
+  int32_t ntiles[2];     // filled by launch_gemm
   GemmProblem p[2];
 };
 

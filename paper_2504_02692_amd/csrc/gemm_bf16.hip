@@ -13,10 +13,11 @@
 // Two LDS stages, one barrier per k-tile; the next k-tile is in flight in registers while
 // the current one is multiplied.
 #include "common.h"
+#include <cstdlib>
 
 namespace gptaq {
 
-template <int BT>
+template <int BT, int DBG = 0>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int WT = BT / 2;             // wave tile edge
@@ -24,21 +25,26 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
   constexpr int NP = BT / 32;            // 32-row passes of the global->LDS copy
   constexpr int OPB = BT * 128;          // bytes of one operand k-tile
 
-  // ---- which tile: spread consecutive tiles over one XCD so they share operands in its L2
-  const int total = gridDim.x;
+  // ---- which tile.  Workgroups are dealt round-robin to the 8 XCDs; inside each problem, give every
+  // XCD one contiguous run of tiles so that they share operand tiles in that XCD's L2, and so that
+  // every XCD gets the same share of each problem (the problems differ in K).
   int id = blockIdx.x;
-  {
-    const int per = total >> 3, rem = total & 7, xcd = id & 7, loc = id >> 3;
-    id = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
-  }
   int pi = 0;
+  int ntile = b.ntiles[0];
+  if (id >= ntile) { pi = 1; id -= ntile; ntile = b.ntiles[1]; }
   {
-    const int t0 = b.p[0].tiles_m * b.p[0].tiles_n;
-    if (id >= t0) { pi = 1; id -= t0; }
+    const int per = ntile >> 3, rem = ntile & 7, xcd = id & 7, loc = id >> 3;
+    id = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
   }
   const GemmProblem& P = b.p[pi];
   int tm, tn;
-  {
+  if (P.tile_mode == 2) {
+    // only the tiles with tn >= tm exist, numbered row by row
+    tm = 0;
+    int rowlen = P.tiles_n;
+    while (id >= rowlen) { id -= rowlen; --rowlen; ++tm; }
+    tn = tm + id;
+  } else {
     constexpr int GROUP = 4;
     const int width = GROUP * P.tiles_n;
     const int g = id / width, first = g * GROUP;
@@ -77,8 +83,9 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
     const int s = it / nk;
     const int k = klo + (it - s * nk) * kGemmBK;
     const GemmSeg& sg = P.seg[s];
-    const uint16_t* lp = sg.L + (int64_t)(m0 + crow) * sg.ldl + k + cchunk * 8;
-    const uint16_t* rp = sg.R + (int64_t)(n0 + crow) * sg.ldr + k + cchunk * 8;
+    const int64_t kt = k / kGemmBK;
+    const uint16_t* lp = sg.L + (int64_t)(m0 + crow) * sg.ldl + kt * sg.ktl + cchunk * 8;
+    const uint16_t* rp = sg.R + (int64_t)(n0 + crow) * sg.ldr + kt * sg.ktr + cchunk * 8;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       pl[p] = *reinterpret_cast<const u32x4*>(lp + (int64_t)p * 32 * sg.ldl);
@@ -95,61 +102,109 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
     }
   };
 
+  // Fragment reads are software-pipelined by hand: while the 16 (or 4) MFMAs of k-step kk run, the
+  // ds_read_b128 of k-step kk+1 are already in flight into the other register set; the LDS writes of
+  // the next k-tile are issued under the MFMAs of the last k-step.  sched_barrier keeps the compiler
+  // from re-serialising the phases.
+  bf16x8 af[2][FR], bfr[2][FR];
+  auto read_frags = [&](int buf, int kk, int set) {
+    if ((DBG & 16) && !(buf == 0 && kk == 0)) return;
+    const unsigned char* lb = smem + buf * 2 * OPB + (wm * WT + rl) * 128;
+    const unsigned char* rb = smem + buf * 2 * OPB + OPB + (wn * WT + rl) * 128;
+    const int off = ((kk * 2 + half) ^ sw) << 4;
+#pragma unroll
+    for (int i = 0; i < FR; ++i) {
+      af[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lb + i * 32 * 128 + off));
+      bfr[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + i * 32 * 128 + off));
+    }
+  };
+  auto mfma_step = [&](int set) {
+#pragma unroll
+    for (int i = 0; i < FR; ++i)
+#pragma unroll
+      for (int j = 0; j < FR; ++j)
+        if (!(DBG & 2) || (i == 0 && j == 0))
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+  };
+
   if (total_it > 0) {
     load_global(0);
     store_lds(0);
     __syncthreads();
+    read_frags(0, 0, 0);
     for (int it = 0; it < total_it; ++it) {
       const bool more = it + 1 < total_it;
-      if (more) load_global(it + 1);
-      const unsigned char* lb = smem + (it & 1) * 2 * OPB + (wm * WT + rl) * 128;
-      const unsigned char* rb = smem + (it & 1) * 2 * OPB + OPB + (wn * WT + rl) * 128;
-#pragma unroll
-      for (int kk = 0; kk < kGemmBK / 16; ++kk) {
-        const int off = ((kk * 2 + half) ^ sw) << 4;
-        bf16x8 af[FR], bfr[FR];
-#pragma unroll
-        for (int i = 0; i < FR; ++i) {
-          af[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lb + i * 32 * 128 + off));
-          bfr[i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + i * 32 * 128 + off));
-        }
-#pragma unroll
-        for (int i = 0; i < FR; ++i)
-#pragma unroll
-          for (int j = 0; j < FR; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
-      }
-      if (more) store_lds((it + 1) & 1);
-      __syncthreads();
+      const int buf = it & 1;
+      if (more && !(DBG & 1)) load_global(it + 1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(buf, 1, 1);
+      mfma_step(0);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(buf, 2, 0);
+      mfma_step(1);
+      __builtin_amdgcn_sched_barrier(0);
+      read_frags(buf, 3, 1);
+      mfma_step(0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (more && !(DBG & 4)) store_lds(buf ^ 1);
+      mfma_step(1);
+      __builtin_amdgcn_sched_barrier(0);
+      if (!(DBG & 8)) __syncthreads();
+      if (more) read_frags(buf ^ 1, 0, 0);
     }
   }
 
   // ---- epilogue.  MFMA 32x32 result: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4,
   // column lane%32 of the block.
+  // For C += acc all 64 loads of a row of blocks are issued before the first store, so the
+  // read-modify-write costs a few memory round trips per tile instead of one per element.
   if (skipped && P.store_mode == 0) return;
+  const int rbase = m0 + wm * WT + 4 * half, cbase = n0 + wn * WT + rl;
+  if (P.store_mode == 0) {
 #pragma unroll
-  for (int i = 0; i < FR; ++i)
+    for (int i = 0; i < FR; ++i) {
+      float old[FR][16];
 #pragma unroll
-    for (int j = 0; j < FR; ++j)
+      for (int j = 0; j < FR; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * WT + i * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        const int col = n0 + wn * WT + j * 32 + rl;
-        if (row < P.M && col < P.N) {
-          float* c = P.C + (int64_t)row * P.ldc + col;
-          const float a = acc[i][j][v];
-          if (P.store_mode == 0) *c += a;
-          else if (P.store_mode == 1) *c = a;
-          else *c = col > row ? a : 0.f;
+        for (int v = 0; v < 16; ++v) {
+          const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3), col = cbase + j * 32;
+          old[j][v] = (row < P.M && col < P.N) ? P.C[(int64_t)row * P.ldc + col] : 0.f;
         }
-      }
+#pragma unroll
+      for (int j = 0; j < FR; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3), col = cbase + j * 32;
+          if (row < P.M && col < P.N) P.C[(int64_t)row * P.ldc + col] = old[j][v] + acc[i][j][v];
+        }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < FR; ++i)
+#pragma unroll
+      for (int j = 0; j < FR; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = rbase + i * 32 + 8 * (v >> 2) + (v & 3), col = cbase + j * 32;
+          if (row < P.M && col < P.N) {
+            const float a = acc[i][j][v];
+            P.C[(int64_t)row * P.ldc + col] = (P.store_mode == 1 || col > row) ? a : 0.f;
+          }
+        }
+  }
 }
 
 static bool g_attr_set = false;
 
 hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
+  GemmBatch bb = b;
   int total = 0;
-  for (int i = 0; i < b.nprob; ++i) total += b.p[i].tiles_m * b.p[i].tiles_n;
+  for (int i = 0; i < 2; ++i) {
+    const GemmProblem& q = bb.p[i];
+    bb.ntiles[i] = i >= bb.nprob ? 0 : q.tile_mode == 2 ? q.tiles_m * (q.tiles_m + 1) / 2 : q.tiles_m * q.tiles_n;
+    total += bb.ntiles[i];
+  }
   if (total == 0) return hipSuccess;
   if (!g_attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<256>),
@@ -160,9 +215,22 @@ hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
     if (e != hipSuccess) return e;
     g_attr_set = true;
   }
-  GemmBatch bb = b;
-  if (bb.nprob == 1) { bb.p[1].tiles_m = 0; bb.p[1].tiles_n = 0; }
-  if (b.tile == 256)
+  static int dbg = getenv("GPTAQ_GEMM_DEBUG") ? atoi(getenv("GPTAQ_GEMM_DEBUG")) : 0;
+  bb.debug = dbg;
+  if (b.tile == 256 && dbg) {
+    void (*k)(GemmBatch) = nullptr;
+    switch (dbg) {
+      case 5: k = gemm_nt_kernel<256, 5>; break;
+      case 13: k = gemm_nt_kernel<256, 13>; break;
+      case 29: k = gemm_nt_kernel<256, 29>; break;
+      case 21: k = gemm_nt_kernel<256, 21>; break;
+      case 4: k = gemm_nt_kernel<256, 4>; break;
+      case 1: k = gemm_nt_kernel<256, 1>; break;
+      default: return hipErrorInvalidValue;
+    }
+    hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 256 * 128);
+    hipLaunchKernelGGL(k, dim3(total), dim3(256), 4 * 256 * 128, s, bb);
+  } else if (b.tile == 256)
     hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3(total), dim3(256), 4 * 256 * 128, s, bb);
   else
     hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3(total), dim3(256), 4 * 128 * 128, s, bb);
