@@ -2,8 +2,8 @@
 //
 // Two steps per chunk.  (1) A bandwidth-bound pass reads the token-major bf16 X and X~,
 // forms dX = X~ - X in fp32, splits it exactly into two bf16 terms (hi = rne(dX),
-// lo = dX - hi) and writes X, hi, lo transposed in k-tile-major order: [token tile of 64]
-// [neuron][64 tokens], the operand layout the MFMA GEMM wants (tokens are its K dimension and
+// lo = dX - hi) and writes X, hi, lo transposed in k-tile-major order: [token tile of 32]
+// [neuron][32 tokens], the operand layout the MFMA GEMM wants (tokens are its K dimension and
 // a block of neurons x one token tile is a single contiguous run).
 // (2) One launch of the MFMA GEMM computes dXXT += hi X^T + lo X^T on all tiles and
 // H += X X^T on the tiles that touch the upper triangle.
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void split_transpose_kernel(
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     const int nl = r + 32 * p;
-    const int64_t g = ((int64_t)blockIdx.y * ldo + n0 + nl) * 64 + c * 8;      // k-tile-major
+    const int64_t g = (((int64_t)blockIdx.y * 2 + (c >> 2)) * ldo + n0 + nl) * 32 + (c & 3) * 8;   // k-tile-major
     *reinterpret_cast<u32x4*>(oX + g) = *reinterpret_cast<const u32x4*>(sx + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oHi + g) = *reinterpret_cast<const u32x4*>(sh + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oLo + g) = *reinterpret_cast<const u32x4*>(sl + nl * LS + c * 8);
@@ -78,7 +78,7 @@ using namespace gptaq;
 
 extern "C" size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n) {
   if (tokens <= 0 || n <= 0) return 0;
-  const int64_t c = round_up(tokens < 16384 ? tokens : 16384, kGemmBK);
+  const int64_t c = round_up(tokens < 16384 ? tokens : 16384, 64);
   return (size_t)(3 * padded_n(n) * c * 2);
 }
 
@@ -95,12 +95,12 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
   hipStream_t s = (hipStream_t)stream;
   const int tile = gemm_tile_for(n, n);
   const int64_t np = padded_n(n);
-  int64_t cmax = (int64_t)(ws_bytes / (size_t)(6 * np)) / kGemmBK * kGemmBK;
-  if (cmax < kGemmBK) return GPTAQ_EWORKSPACE;
+  int64_t cmax = (int64_t)(ws_bytes / (size_t)(6 * np)) / 64 * 64;
+  if (cmax < 64) return GPTAQ_EWORKSPACE;
   if (cmax > 32768) cmax = 32768;    // keeps one fp32 running sum short (accuracy), and K in int32
   for (int64_t t0 = 0; t0 < tokens; t0 += cmax) {
     const int64_t c = tokens - t0 < cmax ? tokens - t0 : cmax;
-    const int64_t cp = round_up(c, kGemmBK);
+    const int64_t cp = round_up(c, 64);
     uint16_t* oX = (uint16_t*)ws;
     uint16_t* oHi = oX + np * cp;
     uint16_t* oLo = oHi + np * cp;
@@ -118,12 +118,12 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
     a.C = dXXT; a.ldc = ldh; a.M = (int)n; a.N = (int)n; a.K = (int)cp;
     a.tiles_m = a.tiles_n = (int)(np / tile);
     a.nseg = 2; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
-    a.seg[0] = {oHi, oX, 64, 64, np * 64, np * 64};
-    a.seg[1] = {oLo, oX, 64, 64, np * 64, np * 64};
+    a.seg[0] = {oHi, oX, 32, 32, np * 32, np * 32};
+    a.seg[1] = {oLo, oX, 32, 32, np * 32, np * 32};
     GemmProblem& h = b.p[1];
     h = a;
     h.C = H; h.nseg = 1; h.tile_mode = 2;
-    h.seg[0] = {oX, oX, 64, 64, np * 64, np * 64};
+    h.seg[0] = {oX, oX, 32, 32, np * 32, np * 32};
     hipError_t e;
     {
       ProfScope ps(kProfAccumGemm, s);

@@ -11,14 +11,14 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
-constexpr int kGemmBK = 64;          // bf16 elements per k-tile of the MFMA GEMM
+constexpr int kGemmBK = 32;          // bf16 elements per k-tile of the MFMA GEMM
 constexpr int kMaxSeg = 6;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 // One K-segment of a split GEMM.  Element (row, k) of an operand sits at
-// base + row * ld + (k / 64) * kt + k % 64:  ld = K, kt = 64 for a plain row-major K-contiguous
-// matrix;  ld = 64, kt = rows * 64 for the k-tile-major layout, in which the 64-wide k-tile of a
+// base + row * ld + (k / 32) * kt + k % 32:  ld = K, kt = 32 for a plain row-major K-contiguous
+// matrix;  ld = 32, kt = rows * 32 for the k-tile-major layout, in which the 32-wide k-tile of a
 // block of rows is one contiguous run (no power-of-two row stride, so the tile's lines spread
 // over all memory channels).
 struct GemmSeg {
@@ -47,7 +47,6 @@ struct GemmProblem {
 struct GemmBatch {
   int32_t nprob;
   int32_t tile;          // 128 or 256 (square block tile)
-  int32_t debug;         // experiment switches (0 in production)
   int32_t ntiles[2];     // filled by launch_gemm
   GemmProblem p[2];
 };

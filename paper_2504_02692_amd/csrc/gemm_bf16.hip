@@ -7,23 +7,23 @@
 //
 // Tiling: a 256-thread workgroup owns a BT x BT tile of C (BT = 256 or 128); its four
 // wavefronts sit 2 x 2 and each accumulates a (BT/2)^2 sub-tile with
-// v_mfma_f32_32x32x16_bf16.  Operand k-tiles (BT rows x 64 bf16) are staged through LDS in
-// 16-byte chunks whose position inside a 128-byte row is XOR-ed with the row number, which
-// makes both the global->LDS writes and the ds_read_b128 fragment reads bank-conflict free.
-// Two LDS stages, one barrier per k-tile; the next k-tile is in flight in registers while
-// the current one is multiplied.
+// v_mfma_f32_32x32x16_bf16 (accumulators in AGPRs).  Operand k-tiles (BT rows x 32 bf16) go
+// from global memory straight into LDS (global_load_lds_dwordx4, no VGPR staging) through a
+// ring of four LDS stages, three k-tiles ahead of the multiply; fragment reads are
+// ds_read_b128 on an XOR-swizzled layout and run one k-step ahead of the MFMAs.
 #include "common.h"
-#include <cstdlib>
 
 namespace gptaq {
 
-template <int BT, int DBG = 0>
+template <int BT>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int WT = BT / 2;             // wave tile edge
   constexpr int FR = WT / 32;            // 32x32 MFMA blocks per wave tile edge
-  constexpr int NP = BT / 32;            // 32-row passes of the global->LDS copy
-  constexpr int OPB = BT * 128;          // bytes of one operand k-tile
+  constexpr int OPB = BT * 64;           // bytes of one operand k-tile (BT rows x 32 bf16)
+  constexpr int STAGE_BYTES = 2 * OPB;
+  constexpr int NSTAGE = 4;
+  constexpr int LPW = BT / 64;           // 1 KB wave-loads per operand per wave per k-tile
 
   // ---- which tile.  Workgroups are dealt round-robin to the 8 XCDs; inside each problem, give every
   // XCD one contiguous run of tiles so that they share operand tiles in that XCD's L2, and so that
@@ -72,50 +72,47 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // global -> LDS copy roles
-  const int crow = tid >> 3, cchunk = tid & 7;
-  const int cst = crow * 128 + ((cchunk ^ (crow & 7)) << 4);
-  // fragment read roles
-  const int rl = lane & 31, half = lane >> 5, sw = lane & 7;
-
-  u32x4 pl[NP], pr[NP];
-  auto load_global = [&](int it) {
+  // ---- LDS tile format.  An operand k-tile is BT rows x 32 bf16 (64 B per row).  The LDS of gfx950
+  // has 64 banks (256 B per clock), and a ds_read_b128 serves 16 lanes per clock, so 16 consecutive
+  // fragment rows of one 16-byte chunk column must land in 16 different 16-byte slots of a 256-byte
+  // line.  Four rows share a line; slot = (row & 3) * 4 + (chunk ^ (line & 3)): the four lines that
+  // 16 consecutive rows touch use four different XOR values, i.e. disjoint slot sets.
+  // Loads go global -> LDS directly (global_load_lds_dwordx4): lane l of a wave writes the 16 bytes at
+  // LDS base + 16 l, so a wave fills 4 consecutive lines (16 rows) and each lane fetches the
+  // (row, chunk) that belongs in its slot.
+  const int ld_line = lane >> 4;                            // line inside the wave's 4 lines
+  const int ld_row = ld_line * 4 + ((lane & 15) >> 2);      // row inside the wave's 16 rows
+  const int ld_chunk = (lane & 3) ^ ld_line;                // undo the XOR (line & 3 == ld_line)
+  auto issue_loads = [&](int it) {
     const int s = it / nk;
-    const int k = klo + (it - s * nk) * kGemmBK;
+    const int64_t kt = (klo / kGemmBK) + (it - s * nk);
     const GemmSeg& sg = P.seg[s];
-    const int64_t kt = k / kGemmBK;
-    const uint16_t* lp = sg.L + (int64_t)(m0 + crow) * sg.ldl + kt * sg.ktl + cchunk * 8;
-    const uint16_t* rp = sg.R + (int64_t)(n0 + crow) * sg.ldr + kt * sg.ktr + cchunk * 8;
+    const int stage = it % NSTAGE;
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      pl[p] = *reinterpret_cast<const u32x4*>(lp + (int64_t)p * 32 * sg.ldl);
-      pr[p] = *reinterpret_cast<const u32x4*>(rp + (int64_t)p * 32 * sg.ldr);
-    }
-  };
-  auto store_lds = [&](int buf) {
-    unsigned char* lb = smem + buf * 2 * OPB;
-    unsigned char* rb = lb + OPB;
-#pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      *reinterpret_cast<u32x4*>(lb + cst + p * 32 * 128) = pl[p];
-      *reinterpret_cast<u32x4*>(rb + cst + p * 32 * 128) = pr[p];
+    for (int j = 0; j < LPW; ++j) {
+      const int r = (wave * LPW + j) * 16 + ld_row;
+      const uint16_t* lp = sg.L + (int64_t)(m0 + r) * sg.ldl + kt * sg.ktl + ld_chunk * 8;
+      const uint16_t* rp = sg.R + (int64_t)(n0 + r) * sg.ldr + kt * sg.ktr + ld_chunk * 8;
+      unsigned char* dl = smem + stage * STAGE_BYTES + (wave * LPW + j) * 1024;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)lp,
+                                       (__attribute__((address_space(3))) void*)dl, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)rp,
+                                       (__attribute__((address_space(3))) void*)(dl + OPB), 16, 0, 0);
     }
   };
 
-  // Fragment reads are software-pipelined by hand: while the 16 (or 4) MFMAs of k-step kk run, the
-  // ds_read_b128 of k-step kk+1 are already in flight into the other register set; the LDS writes of
-  // the next k-tile are issued under the MFMAs of the last k-step.  sched_barrier keeps the compiler
-  // from re-serialising the phases.
+  // fragment reads: lane -> row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5)
+  const int rl = lane & 31, half = lane >> 5;
+  const int fr_line = rl >> 2, fr_x = fr_line & 3, fr_hi = (rl & 3) << 2;
   bf16x8 af[2][FR], bfr[2][FR];
-  auto read_frags = [&](int buf, int kk, int set) {
-    if ((DBG & 16) && !(buf == 0 && kk == 0)) return;
-    const unsigned char* lb = smem + buf * 2 * OPB + (wm * WT + rl) * 128;
-    const unsigned char* rb = smem + buf * 2 * OPB + OPB + (wn * WT + rl) * 128;
-    const int off = ((kk * 2 + half) ^ sw) << 4;
+  auto read_frags = [&](int stage, int kk, int set) {
+    const unsigned char* lb = smem + stage * STAGE_BYTES + (wm * (WT / 4) + fr_line) * 256;
+    const unsigned char* rb = smem + stage * STAGE_BYTES + OPB + (wn * (WT / 4) + fr_line) * 256;
+    const int off = (fr_hi | ((kk * 2 + half) ^ fr_x)) << 4;
 #pragma unroll
     for (int i = 0; i < FR; ++i) {
-      af[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lb + i * 32 * 128 + off));
-      bfr[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + i * 32 * 128 + off));
+      af[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lb + i * 8 * 256 + off));
+      bfr[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + i * 8 * 256 + off));
     }
   };
   auto mfma_step = [&](int set) {
@@ -123,34 +120,38 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
     for (int i = 0; i < FR; ++i)
 #pragma unroll
       for (int j = 0; j < FR; ++j)
-        if (!(DBG & 2) || (i == 0 && j == 0))
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
+  };
+  // wait until at most `tiles` k-tiles of this wave's own loads are still in flight (loads return in
+  // order), and all LDS reads have returned
+  auto wait_tiles = [&](int tiles) {
+    constexpr int T1 = 2 * LPW, T2 = 4 * LPW;
+    if (tiles >= 2) __builtin_amdgcn_s_waitcnt(((T2 & 15) | ((T2 >> 4) << 14)) | (7 << 4));
+    else if (tiles == 1) __builtin_amdgcn_s_waitcnt(((T1 & 15) | ((T1 >> 4) << 14)) | (7 << 4));
+    else __builtin_amdgcn_s_waitcnt(7 << 4);
   };
 
+  // Pipeline: k-tile `it` is multiplied from stage it % 4 while tiles it+1 .. it+3 are in flight or
+  // landed.  One barrier per k-tile: it publishes tile it+1 (every wave waited for its own loads) and
+  // retires stage (it - 1) % 4, which the loads issued at the top of the next iteration overwrite.
   if (total_it > 0) {
-    load_global(0);
-    store_lds(0);
+    for (int t = 0; t < NSTAGE - 1 && t < total_it; ++t) issue_loads(t);
+    wait_tiles(min(total_it, NSTAGE - 1) - 1);
     __syncthreads();
     read_frags(0, 0, 0);
     for (int it = 0; it < total_it; ++it) {
-      const bool more = it + 1 < total_it;
-      const int buf = it & 1;
-      if (more && !(DBG & 1)) load_global(it + 1);
+      const int stage = it % NSTAGE;
+      if (it + NSTAGE - 1 < total_it) issue_loads(it + NSTAGE - 1);
       __builtin_amdgcn_sched_barrier(0);
-      read_frags(buf, 1, 1);
+      read_frags(stage, 1, 1);
       mfma_step(0);
       __builtin_amdgcn_sched_barrier(0);
-      read_frags(buf, 2, 0);
+      wait_tiles(min(total_it - 1, it + NSTAGE - 1) - (it + 1));
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
       mfma_step(1);
       __builtin_amdgcn_sched_barrier(0);
-      read_frags(buf, 3, 1);
-      mfma_step(0);
-      __builtin_amdgcn_sched_barrier(0);
-      if (more && !(DBG & 4)) store_lds(buf ^ 1);
-      mfma_step(1);
-      __builtin_amdgcn_sched_barrier(0);
-      if (!(DBG & 8)) __syncthreads();
-      if (more) read_frags(buf ^ 1, 0, 0);
     }
   }
 
@@ -208,32 +209,17 @@ hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
   if (total == 0) return hipSuccess;
   if (!g_attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<256>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 256 * 128);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2 * 256 * 64);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 128 * 128);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2 * 128 * 64);
     if (e != hipSuccess) return e;
     g_attr_set = true;
   }
-  static int dbg = getenv("GPTAQ_GEMM_DEBUG") ? atoi(getenv("GPTAQ_GEMM_DEBUG")) : 0;
-  bb.debug = dbg;
-  if (b.tile == 256 && dbg) {
-    void (*k)(GemmBatch) = nullptr;
-    switch (dbg) {
-      case 5: k = gemm_nt_kernel<256, 5>; break;
-      case 13: k = gemm_nt_kernel<256, 13>; break;
-      case 29: k = gemm_nt_kernel<256, 29>; break;
-      case 21: k = gemm_nt_kernel<256, 21>; break;
-      case 4: k = gemm_nt_kernel<256, 4>; break;
-      case 1: k = gemm_nt_kernel<256, 1>; break;
-      default: return hipErrorInvalidValue;
-    }
-    hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 256 * 128);
-    hipLaunchKernelGGL(k, dim3(total), dim3(256), 4 * 256 * 128, s, bb);
-  } else if (b.tile == 256)
-    hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3(total), dim3(256), 4 * 256 * 128, s, bb);
+  if (b.tile == 256)
+    hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3(total), dim3(256), 4 * 2 * 256 * 64, s, bb);
   else
-    hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3(total), dim3(256), 4 * 128 * 128, s, bb);
+    hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3(total), dim3(256), 4 * 2 * 128 * 64, s, bb);
   return hipGetLastError();
 }
 

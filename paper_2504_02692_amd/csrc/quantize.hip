@@ -313,12 +313,12 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
     g.C = W + i2; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = QB;
     g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(ntp / tile);
     g.nseg = 6; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
-    g.seg[0] = {a.Eh, Uth, QB, QB, 64, 64};
-    g.seg[1] = {a.Eh, Utl, QB, QB, 64, 64};
-    g.seg[2] = {a.El, Uth, QB, QB, 64, 64};
-    g.seg[3] = {a.Vh, Pth, QB, QB, 64, 64};
-    g.seg[4] = {a.Vh, Ptl, QB, QB, 64, 64};
-    g.seg[5] = {a.Vl, Pth, QB, QB, 64, 64};
+    g.seg[0] = {a.Eh, Uth, QB, QB, 32, 32};
+    g.seg[1] = {a.Eh, Utl, QB, QB, 32, 32};
+    g.seg[2] = {a.El, Uth, QB, QB, 32, 32};
+    g.seg[3] = {a.Vh, Pth, QB, QB, 32, 32};
+    g.seg[4] = {a.Vh, Ptl, QB, QB, 32, 32};
+    g.seg[5] = {a.Vl, Pth, QB, QB, 32, 32};
     hipError_t e;
     {
       ProfScope ps(kProfTrailGemm, s);
