@@ -36,7 +36,7 @@ def cpu_baseline(wl, budget_s: float = 20.0):
         cores = max(i["num_threads"] for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else cores
     except Exception:
         pass
-    n_s, tok_s, m_s = 1024, 8192, 64
+    n_s, tok_s, m_s = 4096, 16384, 128
     Xb, Xtb = synth.make_activations(tok_s, n_s, wl.seed, "cpu", wl.n_outliers, wl.outlier_scale, wl.noise,
                                      empirical_sigma=False)
     W = synth.make_weights(m_s, n_s, wl.seed, "cpu")
@@ -153,6 +153,10 @@ def main() -> int:
         flops += (n * (n + 1) + 2 * n * n) * float(wl.tokens)
     flops *= args.steps
     achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"{wl.name}_block_hbm_traffic.json")
+    if os.path.exists(tpath):          # HBM bytes per launch from the separate rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
+        traffic = json.load(open(tpath)).get("bytes_per_launch_avg")
     out = {
         "metric": "ms_per_layer_solve", "value": ms_per_step / n_layers, "unit": "ms/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -164,7 +168,7 @@ def main() -> int:
                    "layers_per_step": n_layers},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel<256> (accumulate: H and dXXT)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "launches": launches, "avg_launch_ms": gemm_ms / max(1, launches)},
         "stages_ms_per_step": stage_ms,
         "kernels_ms_per_step": {k: v[1] for k, v in prof.items()},

@@ -1,0 +1,146 @@
+"""Parity at the full benchmark sizes (Llama-2-7B block shapes, 262144 tokens), in the launch
+configuration bench.py times (16384-token accumulate chunks, W4 g128, B = 128).
+
+The full fp64 oracle does not fit these sizes everywhere, so each stage is checked on what the
+oracle can compute exactly:
+  accumulate : fp64 sums over ALL tokens for sampled sets of neurons (sub-blocks of H and dXXT are
+               independent sums);
+  prepare    : n = 4096: the whole fp64 oracle prepare from the GPU's H, dXXT; n = 11008: sampled
+               columns of U^T U against (H + lam I)^-1 and sampled rows of P against Eq. 16, both from
+               one fp64 library Cholesky solve;
+  quantize   : the oracle's column loop on sampled rows (rows are independent, Step 1), near-tie
+               protocol, dequantised weights, and the Eq. 4 objective on a token subsample.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import gptaq_oracle as O
+from paper_2504_02692_amd import binding as B
+from paper_2504_02692_amd import synth
+from tests import parity_util as PU
+
+pytestmark = pytest.mark.gpu
+CHUNK = 16384
+
+
+def bits_of(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def accumulate_full(wl, iid, n):
+    X, Xt = synth.make_activations_device(wl.tokens, n, wl.seed, iid, "cuda", wl.n_outliers, wl.outlier_scale, wl.noise)
+    H = torch.zeros((n, n), device="cuda"); A = torch.zeros_like(H)
+    ws = B.workspace(B.gptaq_accumulate_workspace_bytes(CHUNK, n))
+    for t0 in range(0, wl.tokens, CHUNK):
+        B.gptaq_accumulate(X[t0:t0 + CHUNK], Xt[t0:t0 + CHUNK], H, A, ws)
+    torch.cuda.synchronize()
+    return X, Xt, H, A
+
+
+def check_sampled_blocks(wl, iid, n, X, Xt, H, A):
+    rng = np.random.default_rng(11)
+    out = synth.outlier_channels(n, wl.n_outliers, wl.seed, iid)
+    S = np.unique(np.concatenate([out, [0, 1, 255, 256, n - 1], rng.choice(n, 96, replace=False)]))
+    T = np.unique(np.concatenate([out[:2], [n - 2, 300], rng.choice(n, 60, replace=False)]))
+    idxS, idxT = torch.as_tensor(S, device="cuda"), torch.as_tensor(T, device="cuda")
+    XS, XtS = bits_of(X[:, idxS]), bits_of(Xt[:, idxS])
+    XT = bits_of(X[:, idxT])
+    xs, xts, xt_ = O.bf16_bits_to_f64(XS), O.bf16_bits_to_f64(XtS), O.bf16_bits_to_f64(XT)
+    Hss = xs.T @ xs                      # H restricted to S x S
+    Ast = (xts - xs).T @ xt_             # dXXT rows S, columns T
+    Hg = H.cpu().numpy().astype(np.float64)
+    Hg = np.triu(Hg) + np.triu(Hg, 1).T
+    Ag = A.cpu().numpy().astype(np.float64)
+    eh = PU.rel_fro(Hg[np.ix_(S, S)], Hss)
+    ea = PU.rel_fro(Ag[np.ix_(S, T)], Ast)
+    print(f"[{iid} n={n}] sampled H block {len(S)}x{len(S)}: {eh:.3e}; sampled dXXT block {len(S)}x{len(T)}: {ea:.3e}")
+    assert eh <= 1e-5 and ea <= 1e-5
+    return Hg, Ag
+
+
+def quantize_rows_check(wl, layer, Wd0, Ud, Pd, U64, P64, X, Xt, label):
+    m, n = layer.m, layer.n
+    Wd = Wd0.clone()
+    ws = B.workspace(B.gptaq_quantize_workspace_bytes(m, n))
+    codes, scales, zeros = B.gptaq_quantize_layer(Wd, Ud, Pd, wl.bits, wl.group, wl.sym, wl.blocksize, ws)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    rows = np.unique(np.concatenate([[0, 1, m - 1], rng.choice(m, 45, replace=False)]))
+    ridx = torch.as_tensor(rows, device="cuda")
+    got = dict(What=Wd[ridx].cpu().numpy(), codes=codes[ridx].cpu().numpy(), scales=scales[ridx].cpu().numpy(),
+               zeros=zeros[ridx].cpu().numpy())
+    tok = torch.arange(0, wl.tokens, wl.tokens // 4096, device="cuda")[:4096]
+    PU.check_against_oracle(Wd0[ridx].cpu().numpy(), U64, P64, got, wl.bits, wl.group, wl.sym,
+                            Xb=bits_of(X[tok]), Xtb=bits_of(Xt[tok]), label=label)
+    # whole-matrix properties that hold at any size
+    c = codes.cpu().numpy()
+    assert c.max() <= 2 ** wl.bits - 1
+    z = zeros.cpu().numpy(); s = scales.cpu().numpy()
+    assert np.all(z == np.rint(z)) and np.all(s > 0)
+    G = n // wl.group
+    rec = (s[:, :, None] * (c.reshape(m, G, wl.group).astype(np.float32) - z[:, :, None])).reshape(m, n)
+    assert np.allclose(rec, Wd.cpu().numpy(), rtol=1e-6, atol=1e-9)
+
+
+def test_llama7b_attention_input_4096():
+    wl = synth.workload("llama7b")
+    n, iid = 4096, "attn_in"
+    X, Xt, H, A = accumulate_full(wl, iid, n)
+    Hg, Ag = check_sampled_blocks(wl, iid, n, X, Xt, H, A)
+    # prepare: the whole oracle, fed with the GPU's sums
+    U64, P64, dead = O.prepare(Hg, Ag, wl.damp)
+    wsp = B.workspace(B.gptaq_prepare_workspace_bytes(n))
+    dd, info = B.gptaq_prepare(H, A, wl.damp, wsp)
+    torch.cuda.synchronize()
+    assert info.cpu().tolist() == [0, 0]
+    eu, ep = PU.rel_fro(H.cpu().numpy(), U64), PU.rel_fro(A.cpu().numpy(), P64)
+    print(f"[{iid}] U rel. Frobenius {eu:.3e}; P rel. Frobenius {ep:.3e}")
+    assert eu <= 1e-6 and ep <= 5e-5
+    layer = [l for l in wl.layers if l.name == "q_proj"][0]
+    W0 = synth.make_weights_device(layer.m, layer.n, wl.seed, layer.name, "cuda")
+    quantize_rows_check(wl, layer, W0, H, A, U64, P64, X, Xt, "q_proj 4096x4096, oracle factors")
+
+
+def test_llama7b_mlp_down_input_11008():
+    wl = synth.workload("llama7b")
+    n, iid = 11008, "mlp_mid"
+    X, Xt, H, A = accumulate_full(wl, iid, n)
+    Hg, Ag = check_sampled_blocks(wl, iid, n, X, Xt, H, A)
+    lam = wl.damp * np.trace(Hg) / n
+    Hl = Hg + lam * np.eye(n)
+    wsp = B.workspace(B.gptaq_prepare_workspace_bytes(n))
+    dd, info = B.gptaq_prepare(H, A, wl.damp, wsp)
+    torch.cuda.synchronize()
+    assert info.cpu().tolist() == [0, 0]
+    U = H.cpu().numpy().astype(np.float64)
+    P = A.cpu().numpy().astype(np.float64)
+    assert np.all(np.diag(U) > 0)
+    assert not np.any(np.tril(U, -1)) and not np.any(np.tril(P))
+    import scipy.linalg as sla
+    chol = sla.cho_factor(Hl, lower=True)             # one fp64 factorisation as the reference for both checks
+    rng = np.random.default_rng(3)
+    cols = np.unique(np.concatenate([[0, n - 1], synth.outlier_channels(n, wl.n_outliers, wl.seed, iid)[:2],
+                                     rng.choice(n, 6, replace=False)]))
+    for j in cols:                                   # column j of (H + lam I)^-1 = L L^T = U^T U   (Step 3)
+        e = np.zeros(n); e[j] = 1.0
+        ref = sla.cho_solve(chol, e)
+        got = U.T @ U[:, j]
+        err = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+        assert err <= 1e-5, (j, err)
+    # Eq. 16 for row 0: P[0, 1:] = dXXT[0, 1:] (H_lam[1:, 1:])^-1, the reduced inverse written with Eq. 3
+    e0 = np.zeros(n); e0[0] = 1.0
+    h0 = sla.cho_solve(chol, e0)
+    a = Ag[0].copy(); a[0] = 0.0
+    z = sla.cho_solve(chol, a)
+    ref = z[1:] - z[0] * h0[1:] / h0[0]
+    err = np.linalg.norm(P[0, 1:] - ref) / np.linalg.norm(ref)
+    print(f"[{iid}] P row 0 vs Eq. 16: {err:.3e}")
+    assert err <= 1e-4
+    for q in (n - 2, n - 300, n - 1500):              # and for late rows by a direct solve
+        ref = np.linalg.solve(Hl[q + 1:, q + 1:], Ag[q, q + 1:])
+        err = np.linalg.norm(P[q, q + 1:] - ref) / np.linalg.norm(ref)
+        assert err <= 1e-4, (q, err)
+    layer = [l for l in wl.layers if l.name == "down_proj"][0]
+    W0 = synth.make_weights_device(layer.m, layer.n, wl.seed, layer.name, "cuda")
+    quantize_rows_check(wl, layer, W0, H, A, U, P, X, Xt, "down_proj 4096x11008, GPU factors upcast")
