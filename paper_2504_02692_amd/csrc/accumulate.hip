@@ -117,13 +117,12 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
     GemmProblem& a = b.p[0];
     a.C = dXXT; a.ldc = ldh; a.M = (int)n; a.N = (int)n; a.K = (int)cp;
     a.tiles_m = a.tiles_n = (int)(np / tile);
-    a.nseg = 2; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
-    a.seg[0] = {oHi, oX, 32, 32, np * 32, np * 32};
-    a.seg[1] = {oLo, oX, 32, 32, np * 32, np * 32};
+    a.kind = 1; a.nterm = 1; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
+    a.term[0] = {{oHi, oLo}, {oX, oX}, 32, 32, np * 32, np * 32};
     GemmProblem& h = b.p[1];
     h = a;
-    h.C = H; h.nseg = 1; h.tile_mode = 2;
-    h.seg[0] = {oX, oX, 32, 32, np * 32, np * 32};
+    h.C = H; h.kind = 0; h.tile_mode = 2;
+    h.term[0] = {{oX, oX}, {oX, oX}, 32, 32, np * 32, np * 32};
     hipError_t e;
     {
       ProfScope ps(kProfAccumGemm, s);

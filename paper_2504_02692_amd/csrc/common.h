@@ -12,36 +12,36 @@ typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 constexpr int kGemmBK = 32;          // bf16 elements per k-tile of the MFMA GEMM
-constexpr int kMaxSeg = 6;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
-// One K-segment of a split GEMM.  Element (row, k) of an operand sits at
-// base + row * ld + (k / 32) * kt + k % 32:  ld = K, kt = 32 for a plain row-major K-contiguous
-// matrix;  ld = 32, kt = rows * 32 for the k-tile-major layout, in which the 32-wide k-tile of a
-// block of rows is one contiguous run (no power-of-two row stride, so the tile's lines spread
-// over all memory channels).
-struct GemmSeg {
-  const uint16_t* L;
-  const uint16_t* R;
+// One term of a GEMM: up to two left and two right bf16 operands (hi, lo) sharing one layout.
+// Element (row, k) of an operand sits at base + row * ld + (k / 32) * kt + k % 32:  ld = K, kt = 32
+// for a plain row-major K-contiguous matrix;  ld = 32, kt = rows * 32 for the k-tile-major layout, in
+// which the 32-wide k-tile of a block of rows is one contiguous run (no power-of-two row stride, so a
+// tile's lines spread over all memory channels).
+struct GemmTerm {
+  const uint16_t* L[2];
+  const uint16_t* R[2];
   int64_t ldl, ldr;
   int64_t ktl, ktr;
 };
 
-// C (+)= sum_s L_s R_s^T.  Operand buffers are zero-padded to whole tiles in rows and to a
-// multiple of kGemmBK in K, so the main loop needs no bounds checks; stores are bounded by
-// M and N.
+// C (+)= sum_t sum_pairs L R^T.  kind 0: L0 R0.  kind 1: L0 R0 + L1 R0 (two left operands share the
+// right one).  kind 2: L0 R0 + L0 R1 + L1 R0 (hi/lo split of both sides, lo*lo dropped).
+// Operand buffers are zero-padded to whole tiles in rows and to a multiple of kGemmBK in K, so the
+// main loop needs no bounds checks; stores are bounded by M and N.
 struct GemmProblem {
   float* C;
   int64_t ldc;
-  int32_t M, N, K;       // K per segment (multiple of kGemmBK)
+  int32_t M, N, K;       // K per term (multiple of kGemmBK)
   int32_t tiles_m, tiles_n;
-  int32_t nseg;
+  int32_t kind, nterm;
   int32_t tile_mode;     // 0: all tiles; 1: tiles entirely below the diagonal do no work (but store);
                          // 2: square problem, only tiles with tile column >= tile row are scheduled
   int32_t k_mode;        // 0: all k; 1: k >= first column of the tile; 2: tile row0 <= k < tile col end
   int32_t store_mode;    // 0: C += acc; 1: C = acc; 2: C = acc where col > row, else 0
-  GemmSeg seg[kMaxSeg];
+  GemmTerm term[2];
 };
 
 struct GemmBatch {

@@ -1,29 +1,152 @@
-// bf16 x bf16 -> fp32 MFMA GEMM for gfx950:  C (+)= sum_s L_s R_s^T.
+// bf16 x bf16 -> fp32 MFMA GEMM for gfx950:  C (+)= sum over terms of (sum of cross products) L R^T.
 //
 // Every dense contraction of the solve goes through this kernel (Algorithm 1 line 2: H and
 // dXXT; line 4: the two products of Theorem 4.2; lines 11-12: the lazy trailing update of
 // Eq. 18).  fp32-accurate products are obtained by splitting an fp32 operand into bf16
-// terms and listing the cross products as K-segments.
+// hi + lo and summing the cross products hi*hi + hi*lo + lo*hi.
 //
 // Tiling: a 256-thread workgroup owns a BT x BT tile of C (BT = 256 or 128); its four
 // wavefronts sit 2 x 2 and each accumulates a (BT/2)^2 sub-tile with
 // v_mfma_f32_32x32x16_bf16 (accumulators in AGPRs).  Operand k-tiles (BT rows x 32 bf16) go
 // from global memory straight into LDS (global_load_lds_dwordx4, no VGPR staging) through a
-// ring of four LDS stages, three k-tiles ahead of the multiply; fragment reads are
-// ds_read_b128 on an XOR-swizzled layout and run one k-step ahead of the MFMAs.
+// ring of LDS stages, ahead of the multiply; fragment reads are ds_read_b128 on an
+// XOR-swizzled layout and run one k-step ahead of the MFMAs.
+//
+// The traffic from L2 into LDS is what bounds this kernel (a CU sustains only about 13 bytes per
+// clock of L2 reads), so operand tiles are shared between cross products: per k-tile a term
+// loads its NL left and NR right operand tiles once and multiplies all listed (left, right)
+// pairs from them - dXXT's hi and lo halves share the X tile, and the three products of a
+// split term need four tiles instead of six.
 #include "common.h"
 
 namespace gptaq {
+
+template <int KIND> struct KindTraits;
+template <> struct KindTraits<0> { static constexpr int NL = 1, NR = 1, NPAIR = 1, NSTAGE = 4; };
+template <> struct KindTraits<1> { static constexpr int NL = 2, NR = 1, NPAIR = 2, NSTAGE = 3; };
+template <> struct KindTraits<2> { static constexpr int NL = 2, NR = 2, NPAIR = 3, NSTAGE = 2; };
+// pair p of a kind: (left index, right index)
+__device__ __forceinline__ constexpr int pair_l(int kind, int p) { return kind == 0 ? 0 : kind == 1 ? p : (p == 2 ? 1 : 0); }
+__device__ __forceinline__ constexpr int pair_r(int kind, int p) { return kind == 2 ? (p == 1 ? 1 : 0) : 0; }
+
+template <int N> __device__ __forceinline__ void wait_vm_and_lds() {
+  // vmcnt <= N (vmcnt is split over bits 3:0 and 15:14), lgkmcnt == 0, expcnt untouched
+  __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
+}
+
+template <int BT, int KIND>
+__device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* smem, int m0, int n0, int klo, int nk,
+                                          f32x16 (&acc)[BT / 64][BT / 64]) {
+  using T = KindTraits<KIND>;
+  constexpr int NL = T::NL, NR = T::NR, NOP = NL + NR, NSTAGE = T::NSTAGE;
+  constexpr int WT = BT / 2, FR = WT / 32;
+  constexpr int OPB = BT * 64;           // bytes of one operand k-tile (BT rows x 32 bf16)
+  constexpr int STAGE_BYTES = NOP * OPB;
+  constexpr int LPW = BT / 64;           // 1 KB wave-loads per operand per wave per k-tile
+  constexpr int TL = NOP * LPW;          // loads per k-tile per wave
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int total_it = nk * P.nterm;
+
+  // ---- LDS tile format.  An operand k-tile is BT rows x 32 bf16 (64 B per row).  The LDS of gfx950
+  // has 64 banks (256 B per clock), and a ds_read_b128 serves 16 lanes per clock, so 16 consecutive
+  // fragment rows of one 16-byte chunk column must land in 16 different 16-byte slots of a 256-byte
+  // line.  Four rows share a line; slot = (row & 3) * 4 + (chunk ^ (line & 3)): the four lines that
+  // 16 consecutive rows touch use four different XOR values, i.e. disjoint slot sets.
+  // Loads go global -> LDS directly: lane l of a wave writes the 16 bytes at LDS base + 16 l, so a
+  // wave fills 4 consecutive lines (16 rows) and each lane fetches the (row, chunk) of its slot.
+  const int ld_line = lane >> 4;
+  const int ld_row = ld_line * 4 + ((lane & 15) >> 2);
+  const int ld_chunk = (lane & 3) ^ ld_line;
+  auto issue_loads = [&](int it) {
+    const int t = it / nk;
+    const int64_t kt = (klo / kGemmBK) + (it - t * nk);
+    const GemmTerm& tm = P.term[t];
+    unsigned char* st = smem + (it % NSTAGE) * STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < LPW; ++j) {
+      const int r = (wave * LPW + j) * 16 + ld_row;
+      const int64_t lo = (int64_t)(m0 + r) * tm.ldl + kt * tm.ktl + ld_chunk * 8;
+      const int64_t ro = (int64_t)(n0 + r) * tm.ldr + kt * tm.ktr + ld_chunk * 8;
+      unsigned char* d = st + (wave * LPW + j) * 1024;
+#pragma unroll
+      for (int o = 0; o < NL; ++o)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tm.L[o] + lo),
+                                         (__attribute__((address_space(3))) void*)(d + o * OPB), 16, 0, 0);
+#pragma unroll
+      for (int o = 0; o < NR; ++o)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tm.R[o] + ro),
+                                         (__attribute__((address_space(3))) void*)(d + (NL + o) * OPB), 16, 0, 0);
+    }
+  };
+
+  // fragment reads: lane -> row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5)
+  const int rl = lane & 31, half = lane >> 5;
+  const int fr_line = rl >> 2, fr_x = fr_line & 3, fr_hi = (rl & 3) << 2;
+  bf16x8 af[2][NL][FR], bfr[2][NR][FR];
+  auto read_frags = [&](int stage, int kk, int set) {
+    const unsigned char* lb = smem + stage * STAGE_BYTES + (wm * (WT / 4) + fr_line) * 256;
+    const unsigned char* rb = smem + stage * STAGE_BYTES + NL * OPB + (wn * (WT / 4) + fr_line) * 256;
+    const int off = (fr_hi | ((kk * 2 + half) ^ fr_x)) << 4;
+#pragma unroll
+    for (int o = 0; o < NL; ++o)
+#pragma unroll
+      for (int i = 0; i < FR; ++i)
+        af[set][o][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lb + o * OPB + i * 8 * 256 + off));
+#pragma unroll
+    for (int o = 0; o < NR; ++o)
+#pragma unroll
+      for (int i = 0; i < FR; ++i)
+        bfr[set][o][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + o * OPB + i * 8 * 256 + off));
+  };
+  auto mfma_step = [&](int set) {
+#pragma unroll
+    for (int p = 0; p < T::NPAIR; ++p)
+#pragma unroll
+      for (int i = 0; i < FR; ++i)
+#pragma unroll
+        for (int j = 0; j < FR; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][pair_l(KIND, p)][i], bfr[set][pair_r(KIND, p)][j],
+                                                              acc[i][j], 0, 0, 0);
+  };
+  // wait until at most `tiles` k-tiles of this wave's own loads are still in flight (loads return in
+  // order) and all of its LDS reads have returned
+  auto wait_tiles = [&](int tiles) {
+    if (NSTAGE >= 4 && tiles >= 2) wait_vm_and_lds<2 * TL>();
+    else if (NSTAGE >= 3 && tiles >= 1) wait_vm_and_lds<TL>();
+    else wait_vm_and_lds<0>();
+  };
+
+  // Pipeline: k-tile `it` is multiplied from stage it % NSTAGE while the next NSTAGE - 1 tiles are in
+  // flight or landed.  One barrier per k-tile: it publishes tile it+1 (every wave waited for its own
+  // loads) and retires stage (it - 1) % NSTAGE, which the loads issued at the top of the next
+  // iteration overwrite.
+  if (total_it <= 0) return;
+  for (int t = 0; t < NSTAGE - 1 && t < total_it; ++t) issue_loads(t);
+  wait_tiles(min(total_it, NSTAGE - 1) - 1);
+  __syncthreads();
+  read_frags(0, 0, 0);
+  for (int it = 0; it < total_it; ++it) {
+    const int stage = it % NSTAGE;
+    if (it + NSTAGE - 1 < total_it) issue_loads(it + NSTAGE - 1);
+    __builtin_amdgcn_sched_barrier(0);
+    read_frags(stage, 1, 1);
+    mfma_step(0);
+    __builtin_amdgcn_sched_barrier(0);
+    wait_tiles(min(total_it - 1, it + NSTAGE - 1) - (it + 1));
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+    if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
+    mfma_step(1);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
 
 template <int BT>
 __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int WT = BT / 2;             // wave tile edge
   constexpr int FR = WT / 32;            // 32x32 MFMA blocks per wave tile edge
-  constexpr int OPB = BT * 64;           // bytes of one operand k-tile (BT rows x 32 bf16)
-  constexpr int STAGE_BYTES = 2 * OPB;
-  constexpr int NSTAGE = 4;
-  constexpr int LPW = BT / 64;           // 1 KB wave-loads per operand per wave per k-tile
 
   // ---- which tile.  Workgroups are dealt round-robin to the 8 XCDs; inside each problem, give every
   // XCD one contiguous run of tiles so that they share operand tiles in that XCD's L2, and so that
@@ -54,15 +177,15 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
     tn = r / gsz;
   }
   const int m0 = tm * BT, n0 = tn * BT;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int wm = wave >> 1, wn = wave & 1;
+  const int rl = lane & 31, half = lane >> 5;
 
   const bool skipped = P.tile_mode == 1 && n0 + BT <= m0;
   int klo = 0, khi = P.K;
   if (P.k_mode == 1) klo = min(n0, P.K);
   if (P.k_mode == 2) { klo = min(m0, P.K); khi = min(P.K, n0 + BT); }
   const int nk = (skipped || khi <= klo) ? 0 : (khi - klo) / kGemmBK;
-  const int total_it = nk * P.nseg;
 
   f32x16 acc[FR][FR];
 #pragma unroll
@@ -72,88 +195,9 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  // ---- LDS tile format.  An operand k-tile is BT rows x 32 bf16 (64 B per row).  The LDS of gfx950
-  // has 64 banks (256 B per clock), and a ds_read_b128 serves 16 lanes per clock, so 16 consecutive
-  // fragment rows of one 16-byte chunk column must land in 16 different 16-byte slots of a 256-byte
-  // line.  Four rows share a line; slot = (row & 3) * 4 + (chunk ^ (line & 3)): the four lines that
-  // 16 consecutive rows touch use four different XOR values, i.e. disjoint slot sets.
-  // Loads go global -> LDS directly (global_load_lds_dwordx4): lane l of a wave writes the 16 bytes at
-  // LDS base + 16 l, so a wave fills 4 consecutive lines (16 rows) and each lane fetches the
-  // (row, chunk) that belongs in its slot.
-  const int ld_line = lane >> 4;                            // line inside the wave's 4 lines
-  const int ld_row = ld_line * 4 + ((lane & 15) >> 2);      // row inside the wave's 16 rows
-  const int ld_chunk = (lane & 3) ^ ld_line;                // undo the XOR (line & 3 == ld_line)
-  auto issue_loads = [&](int it) {
-    const int s = it / nk;
-    const int64_t kt = (klo / kGemmBK) + (it - s * nk);
-    const GemmSeg& sg = P.seg[s];
-    const int stage = it % NSTAGE;
-#pragma unroll
-    for (int j = 0; j < LPW; ++j) {
-      const int r = (wave * LPW + j) * 16 + ld_row;
-      const uint16_t* lp = sg.L + (int64_t)(m0 + r) * sg.ldl + kt * sg.ktl + ld_chunk * 8;
-      const uint16_t* rp = sg.R + (int64_t)(n0 + r) * sg.ldr + kt * sg.ktr + ld_chunk * 8;
-      unsigned char* dl = smem + stage * STAGE_BYTES + (wave * LPW + j) * 1024;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)lp,
-                                       (__attribute__((address_space(3))) void*)dl, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)rp,
-                                       (__attribute__((address_space(3))) void*)(dl + OPB), 16, 0, 0);
-    }
-  };
-
-  // fragment reads: lane -> row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5)
-  const int rl = lane & 31, half = lane >> 5;
-  const int fr_line = rl >> 2, fr_x = fr_line & 3, fr_hi = (rl & 3) << 2;
-  bf16x8 af[2][FR], bfr[2][FR];
-  auto read_frags = [&](int stage, int kk, int set) {
-    const unsigned char* lb = smem + stage * STAGE_BYTES + (wm * (WT / 4) + fr_line) * 256;
-    const unsigned char* rb = smem + stage * STAGE_BYTES + OPB + (wn * (WT / 4) + fr_line) * 256;
-    const int off = (fr_hi | ((kk * 2 + half) ^ fr_x)) << 4;
-#pragma unroll
-    for (int i = 0; i < FR; ++i) {
-      af[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lb + i * 8 * 256 + off));
-      bfr[set][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + i * 8 * 256 + off));
-    }
-  };
-  auto mfma_step = [&](int set) {
-#pragma unroll
-    for (int i = 0; i < FR; ++i)
-#pragma unroll
-      for (int j = 0; j < FR; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][i], bfr[set][j], acc[i][j], 0, 0, 0);
-  };
-  // wait until at most `tiles` k-tiles of this wave's own loads are still in flight (loads return in
-  // order), and all LDS reads have returned
-  auto wait_tiles = [&](int tiles) {
-    constexpr int T1 = 2 * LPW, T2 = 4 * LPW;
-    if (tiles >= 2) __builtin_amdgcn_s_waitcnt(((T2 & 15) | ((T2 >> 4) << 14)) | (7 << 4));
-    else if (tiles == 1) __builtin_amdgcn_s_waitcnt(((T1 & 15) | ((T1 >> 4) << 14)) | (7 << 4));
-    else __builtin_amdgcn_s_waitcnt(7 << 4);
-  };
-
-  // Pipeline: k-tile `it` is multiplied from stage it % 4 while tiles it+1 .. it+3 are in flight or
-  // landed.  One barrier per k-tile: it publishes tile it+1 (every wave waited for its own loads) and
-  // retires stage (it - 1) % 4, which the loads issued at the top of the next iteration overwrite.
-  if (total_it > 0) {
-    for (int t = 0; t < NSTAGE - 1 && t < total_it; ++t) issue_loads(t);
-    wait_tiles(min(total_it, NSTAGE - 1) - 1);
-    __syncthreads();
-    read_frags(0, 0, 0);
-    for (int it = 0; it < total_it; ++it) {
-      const int stage = it % NSTAGE;
-      if (it + NSTAGE - 1 < total_it) issue_loads(it + NSTAGE - 1);
-      __builtin_amdgcn_sched_barrier(0);
-      read_frags(stage, 1, 1);
-      mfma_step(0);
-      __builtin_amdgcn_sched_barrier(0);
-      wait_tiles(min(total_it - 1, it + NSTAGE - 1) - (it + 1));
-      __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);
-      if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
-      mfma_step(1);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
+  if (P.kind == 0) tile_loop<BT, 0>(P, smem, m0, n0, klo, nk, acc);
+  else if (P.kind == 1) tile_loop<BT, 1>(P, smem, m0, n0, klo, nk, acc);
+  else tile_loop<BT, 2>(P, smem, m0, n0, klo, nk, acc);
 
   // ---- epilogue.  MFMA 32x32 result: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4,
   // column lane%32 of the block.
@@ -197,6 +241,8 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
 }
 
 static bool g_attr_set = false;
+constexpr int kLds256 = 3 * 3 * 256 * 64;     // largest ring: 3 stages x 3 operand tiles (2 x 4 tiles is smaller)
+constexpr int kLds128 = 3 * 3 * 128 * 64;
 
 hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
   GemmBatch bb = b;
@@ -209,17 +255,17 @@ hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
   if (total == 0) return hipSuccess;
   if (!g_attr_set) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<256>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2 * 256 * 64);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds256);
     if (e != hipSuccess) return e;
     e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, 4 * 2 * 128 * 64);
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds128);
     if (e != hipSuccess) return e;
     g_attr_set = true;
   }
   if (b.tile == 256)
-    hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3(total), dim3(256), 4 * 2 * 256 * 64, s, bb);
+    hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3(total), dim3(256), kLds256, s, bb);
   else
-    hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3(total), dim3(256), 4 * 2 * 128 * 64, s, bb);
+    hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3(total), dim3(256), kLds128, s, bb);
   return hipGetLastError();
 }
 

@@ -405,10 +405,8 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   // O = triu(dXXT U^T, 1): O[i][a] = sum_{b >= a} dXXT[i][b] U[a][b]
   g.C = Obuf; g.ldc = np; g.M = ni; g.N = ni; g.K = (int)np;
   g.tiles_m = g.tiles_n = (int)(np / tile);
-  g.nseg = 3; g.tile_mode = 1; g.k_mode = 1; g.store_mode = 2;
-  g.seg[0] = {Ah, Uh, np, np, 32, 32};
-  g.seg[1] = {Ah, Ul, np, np, 32, 32};
-  g.seg[2] = {Al, Uh, np, np, 32, 32};
+  g.kind = 2; g.nterm = 1; g.tile_mode = 1; g.k_mode = 1; g.store_mode = 2;
+  g.term[0] = {{Ah, Al}, {Uh, Ul}, np, np, 32, 32};
   hipError_t e;
   {
     ProfScope ps(kProfPGemm, s);
@@ -420,9 +418,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
                      ni, (const uint8_t*)nullptr, Ah, Al, np);
   GPTAQ_LAUNCH_CHECK();
   g.C = dXXT; g.ldc = ldh; g.k_mode = 2;
-  g.seg[0] = {Ah, Uth, np, np, 32, 32};
-  g.seg[1] = {Ah, Utl, np, np, 32, 32};
-  g.seg[2] = {Al, Uth, np, np, 32, 32};
+  g.term[0] = {{Ah, Al}, {Uth, Utl}, np, np, 32, 32};
   {
     ProfScope ps(kProfPGemm, s);
     e = launch_gemm(b, s);

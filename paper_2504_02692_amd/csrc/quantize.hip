@@ -312,13 +312,9 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
     GemmProblem& g = b.p[0];
     g.C = W + i2; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = QB;
     g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(ntp / tile);
-    g.nseg = 6; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
-    g.seg[0] = {a.Eh, Uth, QB, QB, 32, 32};
-    g.seg[1] = {a.Eh, Utl, QB, QB, 32, 32};
-    g.seg[2] = {a.El, Uth, QB, QB, 32, 32};
-    g.seg[3] = {a.Vh, Pth, QB, QB, 32, 32};
-    g.seg[4] = {a.Vh, Ptl, QB, QB, 32, 32};
-    g.seg[5] = {a.Vl, Pth, QB, QB, 32, 32};
+    g.kind = 2; g.nterm = 2; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
+    g.term[0] = {{a.Eh, a.El}, {Uth, Utl}, QB, QB, 32, 32};
+    g.term[1] = {{a.Vh, a.Vl}, {Pth, Ptl}, QB, QB, 32, 32};
     hipError_t e;
     {
       ProfScope ps(kProfTrailGemm, s);
