@@ -3,22 +3,24 @@
 // Step 3 of the paper needs L with (H + lambda I)^-1 = L L^T.  Instead of inverting and then
 // factoring, factor  H + lambda I = V V^T  with V UPPER triangular (a Cholesky factorisation
 // run from the last row/column towards the first); then U = L^T = V^-1 (the factor is unique
-// for a positive diagonal).  Both the factorisation and the triangular inverse are swept
-// from the bottom-right block to the top-left block in one pass, in fp64, 64 columns at a
-// time, inside one n x n fp64 array F:
+// for a positive diagonal).  Factorisation and triangular inverse are swept together from the
+// bottom-right to the top-left, in fp64, inside one n x n fp64 array F whose strictly-upper
+// region holds Schur-complement data until its block column is factored and the running
+// right-hand side R of the solve V U = I afterwards.  Two block levels:
 //
-//   for K = last block .. first block                       (I: blocks above K, J: other blocks)
-//     diag   : F_KK = V_KK V_KK^T,  Winv = V_KK^-1,  U_KK = Winv
-//     panel  : V_IK = F_IK Winv^T            (rows above)   } one launch
-//     rowblk : U_KJ = Winv R_KJ              (J right of K) }
-//     update : F_IJ -= V_IK V_JK^T  (I <= J < K, Schur complement)
-//              R_IJ -= V_IK U_KJ    (J > K, right-looking solve of V U = I)
-//     close  : R_IK  = -V_IK U_KK
+//   for every outer block OB of 256 columns, last to first      (I: rows above OB, J: columns right of OB)
+//     for every inner block K of 64 columns in OB, last to first
+//       diag   : F_KK = V_KK V_KK^T,  Winv_K = V_KK^-1                       (one workgroup, LDS)
+//       panel  : V_iK = F_iK Winv_K^T  for all rows i above K
+//       inner  : F_ij -= V_iK V_jK^T   for the column blocks j of OB left of K (rank 64)
+//     syrk   : F_II  -= V_I,OB V_I,OB^T                (rank 256, fp64 MFMA)  } the n^3 * 2/3 bulk
+//     trinv  : U_OB,OB = V_OB,OB^-1  from the Winv_K and the V_kj inside OB
+//     rowblk : U_OB,J  = U_OB,OB R_OB,J
+//     rupd   : R_I,J  -= V_I,OB U_OB,J                 (rank 256, fp64 MFMA)  }
+//     close  : R_I,OB  = -V_I,OB U_OB,OB
 //
-// The strictly-upper region of F holds Schur-complement data until its block column is
-// factored and the running right-hand side R of the triangular solve afterwards, so no
-// second n x n array is needed.  Theorem 4.2's two products then run on the MFMA GEMM with
-// fp32 operands split into bf16 hi+lo (three cross products per term).
+// Theorem 4.2's two products then run on the bf16 MFMA GEMM with fp32 operands split into
+// bf16 hi+lo (three cross products per term).
 #include "common.h"
 
 namespace gptaq {
@@ -27,12 +29,17 @@ constexpr int NB = 64;
 constexpr int LDT = 65;                       // padded LDS row (doubles)
 constexpr int MM_LDS = 2 * NB * LDT * 8;      // bytes for two staged tiles
 
+constexpr int NBO = 256;                      // outer block (columns per rank-256 update)
+typedef __attribute__((ext_vector_type(4))) double f64x4;
+
 struct Sweep {
   double* F;
   int64_t ldf;
   int n, kb, nblk;
   double* Dinv;      // nblk tiles of 64 x 64: V_KK^-1
   int32_t* info;
+  int o0, o1, jlo;   // current outer block [o0, o1); first inner block of it
+  double* Uob;       // 256 x 256 scratch: U_OB,OB
 };
 
 // ----------------------------------------------------------------------------- statistics
@@ -111,81 +118,149 @@ __device__ __forceinline__ void stage_tile(double* dst, const double* src, int64
   }
 }
 
+// fast fp64 reciprocal: hardware estimate + two Newton steps (about 1 ulp; no correctly rounded divide needed here)
+__device__ __forceinline__ double fast_rcp(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = fma(fma(-x, r, 1.0), r, r);
+  r = fma(fma(-x, r, 1.0), r, r);
+  return r;
+}
+// sum over the four neighbouring lanes of a quad (DPP quad permutes, no LDS traffic)
+template <int CTRL> __device__ __forceinline__ double dpp_quad(double v) {
+  const long long b = __builtin_bit_cast(long long, v);
+  int lo = (int)b, hi = (int)(b >> 32);
+  lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
+  hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
+  return __builtin_bit_cast(double, ((long long)hi << 32) | (unsigned int)lo);
+}
+__device__ __forceinline__ double quad_sum(double v) {
+  v += dpp_quad<0xB1>(v);      // lanes 1,0,3,2
+  v += dpp_quad<0x4E>(v);      // lanes 2,3,0,1
+  return v;
+}
+
 // ------------------------------------------------------------------------------- diag
+// One workgroup: reverse Cholesky of the 64 x 64 diagonal block and the inverse of its factor.
+// Thread (ti, tl) keeps the 16 entries S[ti + 16p][tl + 16q] in registers.  At step j the pivot
+// column is published through LDS (two alternating buffers, one barrier per step) and every thread
+// applies the rank-1 downdate with the unscaled column (column j is final when step j starts and
+// is never touched again); columns are scaled at the end.
 __global__ __launch_bounds__(256) void diag_kernel(Sweep a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   double* S = reinterpret_cast<double*>(smem_raw);        // S[r*LDT + c]
   double* Wi = S + NB * LDT;
+  __shared__ double col[2][NB];
   const int tid = threadIdx.x;
   const int k0 = a.kb * NB, w = min(NB, a.n - k0);
-  // load the upper triangle, mirror it, identity in the padding
-  for (int idx = tid; idx < NB * NB; idx += 256) {
-    const int r = idx >> 6, c = idx & 63;
-    double v;
-    if (r < w && c < w) {
-      const int rr = min(r, c), cc = max(r, c);
-      v = a.F[(int64_t)(k0 + rr) * a.ldf + k0 + cc];
-    } else {
-      v = r == c ? 1.0 : 0.0;
-    }
-    S[r * LDT + c] = v;
-    Wi[r * LDT + c] = 0.0;
-  }
   const int ti = tid >> 4, tl = tid & 15;
+  double s[4][4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {                          // upper triangle mirrored, identity in the padding
+      const int r = ti + 16 * p, c = tl + 16 * q;
+      double v;
+      if (r < w && c < w) {
+        const int rr = min(r, c), cc = max(r, c);
+        v = a.F[(int64_t)(k0 + rr) * a.ldf + k0 + cc];
+      } else {
+        v = r == c ? 1.0 : 0.0;
+      }
+      s[p][q] = v;
+    }
   for (int j = NB - 1; j >= 0; --j) {
+    double* cb = col[j & 1];
+    if (tl == (j & 15)) {                                  // owners of column j publish it
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        double v = s[p][0];
+#pragma unroll
+        for (int q = 1; q < 4; ++q) v = (j >> 4) == q ? s[p][q] : v;
+        cb[ti + 16 * p] = v;
+      }
+    }
     __syncthreads();
-    const double sjj = S[j * LDT + j];
+    const double sjj = cb[j];
     const bool bad = !(sjj > 0.0);
-    const double d = bad ? 1.0 : sqrt(sjj);
     if (bad && tid == 0) atomicCAS(a.info, 0, k0 + j + 1);
-    __syncthreads();
-    if (tid < j) S[tid * LDT + j] = S[tid * LDT + j] / d;
-    if (tid == j) S[j * LDT + j] = d;
-    __syncthreads();
-    for (int i = ti; i < j; i += 16)
-      for (int l = tl; l < j; l += 16) S[i * LDT + l] -= S[i * LDT + j] * S[l * LDT + j];
+    const double rinv = bad ? 0.0 : fast_rcp(sjj);
+    double ci[4], cl[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) { ci[p] = cb[ti + 16 * p] * rinv; cl[p] = cb[tl + 16 * p]; }
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        if (ti + 16 * p < j && tl + 16 * q < j) s[p][q] = fma(-ci[p], cl[q], s[p][q]);
+  }
+  // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j, zero below the diagonal
+  __syncthreads();
+  if (ti == tl) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) { const double d = s[p][p]; col[0][ti + 16 * p] = d > 0.0 ? 1.0 / sqrt(d) : 1.0; }
   }
   __syncthreads();
-  // Wi = V^-1 (V = upper part of S), one column per thread by back substitution
-  if (tid < NB) {
-    const int c = tid;
-    Wi[c * LDT + c] = 1.0 / S[c * LDT + c];
+#pragma unroll
+  for (int p = 0; p < 4; ++p)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r = ti + 16 * p, c = tl + 16 * q;
+      S[r * LDT + c] = r <= c ? s[p][q] * col[0][c] : 0.0;
+      Wi[r * LDT + c] = 0.0;
+    }
+  __syncthreads();
+  // Wi = V^-1 by back substitution, row by row from the bottom.  The four threads that share a column
+  // are neighbouring lanes of one wavefront and columns are independent, so no barrier is needed inside.
+  {
+    const int c = tid >> 2, part = tid & 3;
+    if (part == 0) {
+      const double rd = 1.0 / S[c * LDT + c];
+      Wi[c * LDT + c] = rd;
+      col[1][c] = rd;                                       // reciprocal diagonal of V
+    }
+    __syncthreads();
     for (int i = c - 1; i >= 0; --i) {
-      double s = 0.0;
-      for (int l = i + 1; l <= c; ++l) s = fma(S[i * LDT + l], Wi[l * LDT + c], s);
-      Wi[i * LDT + c] = -s / S[i * LDT + i];
+      // thread `part` sums the terms l = part, part + 4, ... inside (i, c]; all 32 LDS reads are issued
+      // before the first use so their latencies overlap, and four partial sums shorten the fma chain
+      double sv[16], wv[16];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        const int l = part + 4 * q;
+        const bool ok = l > i && l <= c;
+        sv[q] = ok ? S[i * LDT + l] : 0.0;
+        wv[q] = ok ? Wi[l * LDT + c] : 0.0;
+      }
+      const double ri = col[1][i];
+      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+#pragma unroll
+      for (int q = 0; q < 16; q += 4) {
+        s0 = fma(sv[q], wv[q], s0); s1 = fma(sv[q + 1], wv[q + 1], s1);
+        s2 = fma(sv[q + 2], wv[q + 2], s2); s3 = fma(sv[q + 3], wv[q + 3], s3);
+      }
+      const double sum = quad_sum((s0 + s1) + (s2 + s3));
+      if (part == 0) Wi[i * LDT + c] = -sum * ri;
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
     }
   }
   __syncthreads();
   double* D = a.Dinv + (int64_t)a.kb * NB * NB;
   for (int idx = tid; idx < NB * NB; idx += 256) {
     const int r = idx >> 6, c = idx & 63;
-    const double v = Wi[r * LDT + c];
-    D[idx] = v;
-    if (r < w && c < w && c >= r) a.F[(int64_t)(k0 + r) * a.ldf + k0 + c] = v;   // U_KK
+    D[idx] = Wi[r * LDT + c];
   }
 }
 
-// ------------------------------------------------------------------ panel + row block
-// blockIdx.x <  kb : row tile I = blockIdx.x,            V_IK = F_IK Winv^T   (in place)
-// blockIdx.x >= kb : column tile J = blockIdx.x + 1,     U_KJ = Winv R_KJ     (in place)
+// ------------------------------------------------------------------------------ panel
+// V_iK = F_iK Winv_K^T for every row tile i above K (in place).  grid: kb workgroups.
 __global__ __launch_bounds__(256) void panel_kernel(Sweep a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   double* As = reinterpret_cast<double*>(smem_raw);
   double* Bs = As + NB * LDT;
-  const int k0 = a.kb * NB;
+  const int k0 = a.kb * NB, r0 = blockIdx.x * NB;
   const double* D = a.Dinv + (int64_t)a.kb * NB * NB;
-  const bool is_panel = (int)blockIdx.x < a.kb;
-  int r0, c0;
-  if (is_panel) {
-    r0 = blockIdx.x * NB; c0 = k0;
-    stage_tile(As, a.F, a.ldf, r0, c0, a.n, a.n, false);          // A[i][l] = F[r0+i][k0+l]
-    stage_tile(Bs, D, NB, 0, 0, NB, NB, false);                   // B[l][c] = Winv[c][l]
-  } else {
-    r0 = k0; c0 = (blockIdx.x + 1) * NB;
-    stage_tile(As, D, NB, 0, 0, NB, NB, false);                   // A[r][l] = Winv[r][l]
-    stage_tile(Bs, a.F, a.ldf, r0, c0, a.n, a.n, true);           // B[l][c] = F[k0+l][c0+c]
-  }
+  stage_tile(As, a.F, a.ldf, r0, k0, a.n, a.n, false);            // A[i][l] = F[r0+i][k0+l]
+  stage_tile(Bs, D, NB, 0, 0, NB, NB, false);                     // B[l][c] = Winv[c][l]
   __syncthreads();
   double acc[4][4];
   mm64(As, Bs, acc);
@@ -194,27 +269,23 @@ __global__ __launch_bounds__(256) void panel_kernel(Sweep a) {
   for (int p = 0; p < 4; ++p)
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
-      const int r = r0 + 4 * ty + p, c = c0 + tx + 16 * q;
+      const int r = r0 + 4 * ty + p, c = k0 + tx + 16 * q;
       if (r < a.n && c < a.n) a.F[(int64_t)r * a.ldf + c] = acc[p][q];
     }
 }
 
-// ----------------------------------------------------------------------------- update
-// grid (nblk - 1, kb): blockIdx.y = row tile I (< K); column tile J = blockIdx.x, shifted past K.
-//   J <  K : F_IJ -= V_IK V_JK^T   (only J >= I)
-//   J >  K : F_IJ -= V_IK U_KJ
-__global__ __launch_bounds__(256) void update_kernel(Sweep a) {
+// ------------------------------------------------------------------------------ inner
+// F_ij -= V_iK V_jK^T for the column blocks j in [jlo, kb) of the current outer block and the row
+// tiles i <= j.  grid (kb - jlo, kb).
+__global__ __launch_bounds__(256) void inner_update_kernel(Sweep a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   double* As = reinterpret_cast<double*>(smem_raw);
   double* Bs = As + NB * LDT;
-  const int I = blockIdx.y;
-  int J = blockIdx.x;
-  if (J >= a.kb) ++J;
-  if (J < I) return;
+  const int I = blockIdx.y, J = a.jlo + blockIdx.x;
+  if (I > J) return;
   const int k0 = a.kb * NB, r0 = I * NB, c0 = J * NB;
   stage_tile(As, a.F, a.ldf, r0, k0, a.n, a.n, false);            // A[i][l] = V[r0+i][k0+l]
-  if (J < a.kb) stage_tile(Bs, a.F, a.ldf, c0, k0, a.n, a.n, false);   // B[l][c] = V[c0+c][k0+l]
-  else stage_tile(Bs, a.F, a.ldf, k0, c0, a.n, a.n, true);             // B[l][c] = U[k0+l][c0+c]
+  stage_tile(Bs, a.F, a.ldf, c0, k0, a.n, a.n, false);            // B[l][c] = V[c0+c][k0+l]
   __syncthreads();
   double acc[4][4];
   mm64(As, Bs, acc);
@@ -228,27 +299,187 @@ __global__ __launch_bounds__(256) void update_kernel(Sweep a) {
     }
 }
 
-// ------------------------------------------------------------------------------ close
-// R_IK = -V_IK U_KK for every row tile I above K (in place over V_IK).
-__global__ __launch_bounds__(256) void close_kernel(Sweep a) {
+// ------------------------------------------------------------------------------ trinv
+// U_OB,OB = V_OB,OB^-1 from the inner blocks: U_ll = Winv_l and, for k < l,
+// U_kl = -Winv_k sum_{k < j <= l} V_kj U_jl.  One workgroup per block column l; results go to the
+// dense scratch Uob (ld 256, zeros below the diagonal), from which they are copied into F afterwards
+// (the V_kj of F are still being read by the other workgroups).
+__global__ __launch_bounds__(256) void trinv_kernel(Sweep a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   double* As = reinterpret_cast<double*>(smem_raw);
   double* Bs = As + NB * LDT;
-  const int k0 = a.kb * NB, r0 = blockIdx.x * NB;
-  const double* D = a.Dinv + (int64_t)a.kb * NB * NB;
-  stage_tile(As, a.F, a.ldf, r0, k0, a.n, a.n, false);
-  stage_tile(Bs, D, NB, 0, 0, NB, NB, true);                      // B[l][c] = Winv[l][c]
-  __syncthreads();
-  double acc[4][4];
-  mm64(As, Bs, acc);
+  const int l = blockIdx.x, kb0 = a.o0 / NB, wo = a.o1 - a.o0;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const int nbi = (wo + NB - 1) / NB;
+  // blocks below the diagonal of this block column are zero
+  for (int k = l + 1; k < nbi; ++k)
+    for (int idx = threadIdx.x; idx < NB * NB; idx += 256) a.Uob[(int64_t)(k * NB + (idx >> 6)) * 256 + l * NB + (idx & 63)] = 0.0;
+  for (int k = l; k >= 0; --k) {
+    double acc[4][4];
+    if (k == l) {
+      const double* D = a.Dinv + (int64_t)(kb0 + l) * NB * NB;
 #pragma unroll
-  for (int p = 0; p < 4; ++p)
+      for (int p = 0; p < 4; ++p)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = r0 + 4 * ty + p, c = k0 + tx + 16 * q;
-      if (r < a.n && c < a.n) a.F[(int64_t)r * a.ldf + c] = -acc[p][q];
+        for (int q = 0; q < 4; ++q) acc[p][q] = D[(4 * ty + p) * NB + tx + 16 * q];
+    } else {
+      double sum[4][4];
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sum[p][q] = 0.0;
+      for (int j = k + 1; j <= l; ++j) {
+        __syncthreads();
+        stage_tile(As, a.F, a.ldf, a.o0 + k * NB, a.o0 + j * NB, a.n, a.n, false);   // A[i][m] = V_kj[i][m]
+        stage_tile(Bs, a.Uob, 256, j * NB, l * NB, 256, 256, true);                  // B[m][c] = U_jl[m][c]
+        __syncthreads();
+        mm64(As, Bs, acc);
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) sum[p][q] += acc[p][q];
+      }
+      __syncthreads();
+      stage_tile(As, a.Dinv + (int64_t)(kb0 + k) * NB * NB, NB, 0, 0, NB, NB, false);  // A[i][m] = Winv_k[i][m]
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) Bs[(4 * ty + p) * LDT + tx + 16 * q] = -sum[p][q];  // B[m][c] = -S[m][c]
+      __syncthreads();
+      mm64(As, Bs, acc);
     }
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) a.Uob[(int64_t)(k * NB + 4 * ty + p) * 256 + l * NB + tx + 16 * q] = acc[p][q];
+    __threadfence();          // the next k of this workgroup reads these values back from memory
+  }
+}
+
+// dst[r][c] = src[r][c] for an (rows x cols) block of doubles; `upper`: only c >= r is copied.
+__global__ void copy_block_kernel(const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols,
+                                  int upper) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x, r = blockIdx.y;
+  if (c >= cols || r >= rows || (upper && c < r)) return;
+  dst[(int64_t)r * ldd + c] = src[(int64_t)r * lds_ + c];
+}
+
+// dst[c][r] = src[r][c] for an (rows x cols) block of doubles (LDS tile transpose).  grid (ceil(cols/64), ceil(rows/64)).
+__global__ __launch_bounds__(256) void transpose_block_kernel(const double* src, int64_t lds_, double* dst, int64_t ldd,
+                                                              int rows, int cols) {
+  __shared__ double t[64][65];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+  for (int p = 0; p < 16; ++p) {
+    const int r = r0 + y + 4 * p, c = c0 + x;
+    t[y + 4 * p][x] = (r < rows && c < cols) ? src[(int64_t)r * lds_ + c] : 0.0;
+  }
+  __syncthreads();
+  for (int p = 0; p < 16; ++p) {
+    const int c = c0 + y + 4 * p, r = r0 + x;
+    if (r < rows && c < cols) dst[(int64_t)c * ldd + r] = t[x][y + 4 * p];
+  }
+}
+
+// ------------------------------------------------------------------- rank-256 updates: fp64 MFMA
+// C = beta C + alpha At^T B with both operands k-major: At is K x M, B is K x N, row-major, rows
+// 16-byte aligned.  128 x 128 tile per workgroup, four wavefronts 2 x 2, each 4 x 4 blocks of
+// v_mfma_f64_16x16x4_f64 (A: lane l holds row l%16, k l/16; B: column l%16, k l/16; D: register v
+// holds row 4v + l/16, column l%16).  k-tiles of 16 are copied to LDS as they are (16-byte chunks,
+// coalesced, conflict-free); the LDS row stride of 144 doubles puts the k and k+1 rows that a fragment
+// read touches into different bank halves.
+struct DGemm {
+  const double* At; int64_t lda;
+  const double* B; int64_t ldb;
+  double* C; int64_t ldc;
+  int M, N, K, beta, upper_only;
+  double alpha;
+};
+constexpr int DG_LS = 144, DG_BK = 16;
+constexpr int DG_LDS = 2 * 2 * DG_BK * DG_LS * 8;
+typedef __attribute__((ext_vector_type(2))) double f64x2;
+
+__global__ __launch_bounds__(256) void dgemm_bulk_kernel(DGemm g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  double* As = reinterpret_cast<double*>(smem_raw);              // [buf][k][DG_LS]
+  double* Bs = As + 2 * DG_BK * DG_LS;
+  const int i0 = blockIdx.y * 128, j0 = blockIdx.x * 128;
+  if (g.upper_only && j0 + 128 <= i0) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  f64x4 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+  // chunk id = tid + 256 p: k row = id >> 6, 16-byte chunk = id & 63 (two doubles)
+  // loads stay in flight while the current k-tile is multiplied: nothing touches the loaded registers
+  // until store(), which also zeroes the odd element of a chunk that straddles the edge
+  f64x2 ra[4], rb[4];
+  auto load = [&](int k0) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int id = tid + 256 * p, k = k0 + (id >> 6), c = (id & 63) * 2;
+      ra[p] = f64x2{0.0, 0.0};
+      rb[p] = f64x2{0.0, 0.0};
+      if (k < g.K && i0 + c < g.M) ra[p] = *reinterpret_cast<const f64x2*>(g.At + (int64_t)k * g.lda + i0 + c);
+      if (k < g.K && j0 + c < g.N) rb[p] = *reinterpret_cast<const f64x2*>(g.B + (int64_t)k * g.ldb + j0 + c);
+    }
+  };
+  auto store = [&](int buf) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int id = tid + 256 * p, kk = id >> 6, c = (id & 63) * 2;
+      f64x2 va = ra[p], vb = rb[p];
+      if (i0 + c + 1 >= g.M) va[1] = 0.0;
+      if (j0 + c + 1 >= g.N) vb[1] = 0.0;
+      *reinterpret_cast<f64x2*>(As + (buf * DG_BK + kk) * DG_LS + c) = va;
+      *reinterpret_cast<f64x2*>(Bs + (buf * DG_BK + kk) * DG_LS + c) = vb;
+    }
+  };
+  const int nkt = (g.K + DG_BK - 1) / DG_BK;
+  load(0);
+  store(0);
+  __syncthreads();
+  for (int kt = 0; kt < nkt; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nkt) load((kt + 1) * DG_BK);
+    const double* a = As + buf * DG_BK * DG_LS + wm * 64 + (lane & 15);
+    const double* b = Bs + buf * DG_BK * DG_LS + wn * 64 + (lane & 15);
+#pragma unroll
+    for (int ks = 0; ks < DG_BK / 4; ++ks) {
+      const int kk = ks * 4 + (lane >> 4);
+      double fa[4], fb[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { fa[i] = a[kk * DG_LS + i * 16]; fb[i] = b[kk * DG_LS + i * 16]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nkt) store(buf ^ 1);
+    __syncthreads();
+  }
+  // epilogue: all loads of a row of blocks are issued before the first store of it
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    double old[4][4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = i0 + wm * 64 + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * 64 + j * 16 + (lane & 15);
+        old[j][v] = (g.beta && r < g.M && c < g.N) ? g.C[(int64_t)r * g.ldc + c] : 0.0;
+      }
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int r = i0 + wm * 64 + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * 64 + j * 16 + (lane & 15);
+        if (r < g.M && c < g.N) g.C[(int64_t)r * g.ldc + c] = fma(g.alpha, acc[i][j][v], old[j][v]);
+      }
+  }
 }
 
 // --------------------------------------------------------------- extraction and splits
@@ -307,7 +538,7 @@ using namespace gptaq;
 namespace {
 struct PrepLayout {
   int64_t np;
-  size_t off_F, off_Dinv, off_lam, off_dead, off_O, off_b[6], total;
+  size_t off_F, off_Dinv, off_lam, off_dead, off_O, off_b[6], off_T1, off_T2, off_Uob, total;
 };
 PrepLayout prep_layout(int64_t n) {
   PrepLayout L;
@@ -316,11 +547,14 @@ PrepLayout prep_layout(int64_t n) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t r = o; o += (bytes + 255) / 256 * 256; return r; };
   L.off_lam = take(256);
-  L.off_F = take((size_t)n * n * 8);
+  L.off_F = take((size_t)n * round_up(n, 16) * 8);
   L.off_Dinv = take((size_t)round_up(n, NB) * NB * 8);
   L.off_dead = take((size_t)n);
   L.off_O = take((size_t)L.np * L.np * 4);
   for (int i = 0; i < 6; ++i) L.off_b[i] = take((size_t)L.np * L.np * 2);
+  L.off_T1 = take((size_t)NBO * round_up(n, 16) * 8);
+  L.off_T2 = take((size_t)NBO * round_up(n, 16) * 8);
+  L.off_Uob = take((size_t)2 * NBO * NBO * 8);
   L.total = o;
   return L;
 }
@@ -341,12 +575,15 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   if (!g_prep_attr) {
-    const void* fns[4] = {(const void*)&diag_kernel, (const void*)&panel_kernel, (const void*)&update_kernel,
-                          (const void*)&close_kernel};
+    const void* fns[4] = {(const void*)&diag_kernel, (const void*)&panel_kernel, (const void*)&inner_update_kernel,
+                          (const void*)&trinv_kernel};
     for (const void* f : fns) {
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, MM_LDS);
       if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
     }
+    hipError_t e2 = hipFuncSetAttribute((const void*)&dgemm_bulk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        DG_LDS);
+    if (e2 != hipSuccess) { set_last_hip_error(e2); return GPTAQ_ELAUNCH; }
     g_prep_attr = true;
   }
   unsigned char* base = (unsigned char*)ws;
@@ -355,6 +592,10 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   double* Dinv = (double*)(base + L.off_Dinv);
   uint8_t* deadbuf = dead ? dead : (uint8_t*)(base + L.off_dead);
   float* Obuf = (float*)(base + L.off_O);
+  double* T1 = (double*)(base + L.off_T1);
+  double* T2t = (double*)(base + L.off_T2);
+  const int64_t ldf = round_up(n, 16);
+  double* Uob = (double*)(base + L.off_Uob);
   uint16_t* bb[6];
   for (int i = 0; i < 6; ++i) bb[i] = (uint16_t*)(base + L.off_b[i]);
   const int ni = (int)n;
@@ -362,36 +603,71 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   hipLaunchKernelGGL(diag_stats_kernel, dim3(1), dim3(1024), 0, s, H, ldh, ni, damp, deadbuf, lam, info);
   GPTAQ_LAUNCH_CHECK();
   hipLaunchKernelGGL(build_F_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)n), dim3(256), 0, s, H, ldh, ni,
-                     lam, F, n);
+                     lam, F, ldf);
   GPTAQ_LAUNCH_CHECK();
 
   {
-  ProfScope sweep_scope(kProfFactor, s);
-  Sweep a;
-  a.F = F; a.ldf = n; a.n = ni; a.nblk = (int)((n + NB - 1) / NB); a.Dinv = Dinv; a.info = info;
-  for (int kb = a.nblk - 1; kb >= 0; --kb) {
-    a.kb = kb;
-    hipLaunchKernelGGL(diag_kernel, dim3(1), dim3(256), MM_LDS, s, a);
-    GPTAQ_LAUNCH_CHECK();
-    if (a.nblk > 1) {
-      hipLaunchKernelGGL(panel_kernel, dim3(a.nblk - 1), dim3(256), MM_LDS, s, a);
-      GPTAQ_LAUNCH_CHECK();
-    }
-    if (kb > 0) {
-      if (a.nblk > 1) {
-        hipLaunchKernelGGL(update_kernel, dim3(a.nblk - 1, kb), dim3(256), MM_LDS, s, a);
+    ProfScope sweep_scope(kProfFactor, s);
+    Sweep a;
+    a.F = F; a.ldf = ldf; a.n = ni; a.nblk = (int)((n + NB - 1) / NB); a.Dinv = Dinv; a.info = info; a.Uob = Uob;
+    double* Uobt = Uob + NBO * NBO;
+    auto dgemm = [&](const double* At, int64_t lda, const double* Bm, int64_t ldb, double* C, int64_t ldc, int M, int N,
+                     int K, double alpha, int beta, int upper_only) {
+      if (M <= 0 || N <= 0 || K <= 0) return;
+      DGemm g{At, lda, Bm, ldb, C, ldc, M, N, K, beta, upper_only, alpha};
+      hipLaunchKernelGGL(dgemm_bulk_kernel, dim3((N + 127) / 128, (M + 127) / 128), dim3(256), DG_LDS, s, g);
+    };
+    auto copy = [&](const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols, int upper) {
+      if (rows <= 0 || cols <= 0) return;
+      hipLaunchKernelGGL(copy_block_kernel, dim3((cols + 255) / 256, rows), dim3(256), 0, s, src, lds_, dst, ldd, rows,
+                         cols, upper);
+    };
+    auto transpose = [&](const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols) {
+      if (rows <= 0 || cols <= 0) return;
+      hipLaunchKernelGGL(transpose_block_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, s, src, lds_,
+                         dst, ldd, rows, cols);
+    };
+    const int nob = (int)((n + NBO - 1) / NBO);
+    for (int ob = nob - 1; ob >= 0; --ob) {
+      const int o0 = ob * NBO, o1 = (int)(n < o0 + NBO ? n : o0 + NBO), wo = o1 - o0;
+      a.o0 = o0; a.o1 = o1; a.jlo = o0 / NB;
+      const int kb_hi = (o1 + NB - 1) / NB - 1;
+      for (int kb = kb_hi; kb >= a.jlo; --kb) {
+        a.kb = kb;
+        hipLaunchKernelGGL(diag_kernel, dim3(1), dim3(256), MM_LDS, s, a);
         GPTAQ_LAUNCH_CHECK();
+        if (kb > 0) {
+          hipLaunchKernelGGL(panel_kernel, dim3(kb), dim3(256), MM_LDS, s, a);
+          GPTAQ_LAUNCH_CHECK();
+        }
+        if (kb > a.jlo) {
+          hipLaunchKernelGGL(inner_update_kernel, dim3(kb - a.jlo, kb), dim3(256), MM_LDS, s, a);
+          GPTAQ_LAUNCH_CHECK();
+        }
       }
-      hipLaunchKernelGGL(close_kernel, dim3(kb), dim3(256), MM_LDS, s, a);
+      // T2t = V_I,OB^T (k-major operand of the three rank-256 products); T1 = R_OB,J
+      transpose(F + o0, ldf, T2t, ldf, o0, wo);
+      copy(F + (int64_t)o0 * ldf + o1, ldf, T1, ldf, wo, ni - o1, 0);
+      GPTAQ_LAUNCH_CHECK();
+      // Schur complement of everything above/left of the outer block: F_II -= V_I,OB V_I,OB^T (upper tiles)
+      dgemm(T2t, ldf, T2t, ldf, F, ldf, o0, o0, wo, -1.0, 1, 1);
+      GPTAQ_LAUNCH_CHECK();
+      // triangular inverse of the outer diagonal block, then the right-looking solve V U = I
+      hipLaunchKernelGGL(trinv_kernel, dim3((wo + NB - 1) / NB), dim3(256), MM_LDS, s, a);
+      GPTAQ_LAUNCH_CHECK();
+      copy(Uob, 256, F + (int64_t)o0 * ldf + o0, ldf, wo, wo, 1);             // U_OB,OB into F
+      transpose(Uob, 256, Uobt, 256, wo, wo);
+      GPTAQ_LAUNCH_CHECK();
+      dgemm(Uobt, 256, T1, ldf, F + (int64_t)o0 * ldf + o1, ldf, wo, ni - o1, wo, 1.0, 0, 0);       // U_OB,J = U_OB,OB R_OB,J
+      dgemm(T2t, ldf, F + (int64_t)o0 * ldf + o1, ldf, F + o1, ldf, o0, ni - o1, wo, -1.0, 1, 0);  // R_I,J -= V_I,OB U_OB,J
+      dgemm(T2t, ldf, Uob, 256, F + o0, ldf, o0, wo, wo, -1.0, 0, 0);                              // R_I,OB = -V_I,OB U_OB,OB
       GPTAQ_LAUNCH_CHECK();
     }
-  }
-
   }
   // U -> H (fp32) and the bf16 splits; dXXT (dead rows zeroed) split.
   const int64_t np = L.np;
   uint16_t *Uh = bb[0], *Ul = bb[1], *Uth = bb[2], *Utl = bb[3], *Ah = bb[4], *Al = bb[5];
-  hipLaunchKernelGGL(extract_U_kernel, dim3((unsigned)(np / 64), (unsigned)(np / 64)), dim3(256), 0, s, F, n, ni, H,
+  hipLaunchKernelGGL(extract_U_kernel, dim3((unsigned)(np / 64), (unsigned)(np / 64)), dim3(256), 0, s, F, ldf, ni, H,
                      ldh, Uh, Ul, Uth, Utl, np);
   GPTAQ_LAUNCH_CHECK();
   hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)np), dim3(256), 0, s, dXXT, ldh,
