@@ -54,7 +54,12 @@ struct GemmBatch {
 // Enqueue the batch; problems are scheduled in order (put the heavier one first).
 hipError_t launch_gemm(const GemmBatch& b, hipStream_t s);
 // Row padding the GEMM expects from an operand with `rows` logical rows.
-inline int gemm_tile_for(int64_t M, int64_t N) { return (M >= 1024 && N >= 1024) ? 256 : 128; }
+inline int gemm_tile_for(int64_t M, int64_t N) {
+  // 256 x 256 tiles move the fewest bytes per flop but one workgroup fills a CU; use them only when they
+  // still give every CU a tile, otherwise 128 x 128 tiles (two workgroups per CU).
+  const int64_t t256 = ((M + 255) / 256) * ((N + 255) / 256);
+  return (M >= 1024 && N >= 1024 && t256 >= 224) ? 256 : 128;
+}
 
 void set_last_hip_error(hipError_t e);
 

@@ -98,7 +98,11 @@ __global__ __launch_bounds__(256) void quant_block_kernel(QuantArgs a) {
   if (tid < QB) dinv[tid] = tid < bw ? 1.f / a.U[(int64_t)(i0 + tid) * a.ldh + i0 + tid] : 0.f;
 
   const int row0 = (blockIdx.x * 4 + wave) * R;
-  float w0[R], w1[R], c0[R], c1[R], e0[R], e1[R], v0[R], v1[R], sc[R], zr[R], isc[R];
+  // w: the row's current values of the lane's two columns; v: the value each column had just before it
+  // was quantised; (sc, zr): the current group's grid (wave-uniform); (ms, mz): the grid of the group
+  // the lane's own columns belong to.  Codes and -E are recomputed per lane after the loop from
+  // (v, ms, mz), with the same fp32 operations the loop used, so nothing else has to be captured.
+  float w0[R], w1[R], v0[R], v1[R], sc[R], zr[R], isc[R], ms0[R], mz0[R], ms1[R], mz1[R];
   const bool col0 = lane < bw && !(a.dead && a.dead[i0 + lane]);
   const bool col1 = lane + 64 < bw && !(a.dead && a.dead[i0 + 64 + lane]);
 #pragma unroll
@@ -107,72 +111,95 @@ __global__ __launch_bounds__(256) void quant_block_kernel(QuantArgs a) {
     const bool ok = row < a.m;
     w0[r] = ok && col0 ? a.W[(int64_t)row * a.ldw + i0 + lane] : 0.f;
     w1[r] = ok && col1 ? a.W[(int64_t)row * a.ldw + i0 + 64 + lane] : 0.f;
-    c0[r] = c1[r] = e0[r] = e1[r] = v0[r] = v1[r] = 0.f;
+    v0[r] = v1[r] = 0.f;
     sc[r] = 1.f; zr[r] = 0.f;
     if (a.group <= 0 && ok) { sc[r] = a.scales[row]; zr[r] = a.zeros[row]; }
     isc[r] = 1.f / sc[r];
+    ms0[r] = ms1[r] = sc[r];
+    mz0[r] = mz1[r] = zr[r];
   }
   __syncthreads();
 
-  for (int j = 0; j < bw; ++j) {
-    const int jl = j & 63;
-    const bool second = j >= 64;
-    if (a.group > 0 && (i0 + j) % a.group == 0) {
-      const int jend = j + a.group;
-      const bool in0 = lane >= j && lane < jend, in1 = lane + 64 >= j && lane + 64 < jend;
+  int next_group = a.group > 0 ? 0 : bw;                  // i0 is a multiple of the group size
+  auto group_start = [&](int j) {
+    const int jend = j + a.group;
+    const bool in0 = lane >= j && lane < jend, in1 = lane + 64 >= j && lane + 64 < jend;
 #pragma unroll
-      for (int r = 0; r < R; ++r) {
-        float mn = fminf(in0 ? w0[r] : 0.f, in1 ? w1[r] : 0.f);
-        float mx = fmaxf(in0 ? w0[r] : 0.f, in1 ? w1[r] : 0.f);
-        mn = wave_min(mn);
-        mx = wave_max(mx);
-        grid_params(mn, mx, a.maxq, a.sym, sc[r], zr[r]);
-        isc[r] = 1.f / sc[r];
-        const int row = row0 + r;
-        if (lane == 0 && row < a.m) {
-          const int64_t o = (int64_t)row * a.G + (i0 + j) / a.group;
-          a.scales[o] = sc[r];
-          a.zeros[o] = zr[r];
-        }
+    for (int r = 0; r < R; ++r) {
+      float mn = fminf(in0 ? w0[r] : 0.f, in1 ? w1[r] : 0.f);
+      float mx = fmaxf(in0 ? w0[r] : 0.f, in1 ? w1[r] : 0.f);
+      mn = wave_min(mn);
+      mx = wave_max(mx);
+      grid_params(mn, mx, a.maxq, a.sym, sc[r], zr[r]);
+      isc[r] = 1.f / sc[r];
+      if (in0) { ms0[r] = sc[r]; mz0[r] = zr[r]; }
+      if (in1) { ms1[r] = sc[r]; mz1[r] = zr[r]; }
+      const int row = row0 + r;
+      if (lane == 0 && row < a.m) {
+        const int64_t o = (int64_t)row * a.G + (i0 + j) / a.group;
+        a.scales[o] = sc[r];
+        a.zeros[o] = zr[r];
       }
     }
+    next_group += a.group;
+  };
+
+  const int h1 = bw < 64 ? bw : 64;
+  for (int j = 0; j < h1; ++j) {                           // columns held in w0
+    if (j == next_group) group_start(j);
     const float u0 = Us[j * QB + lane], u1 = Us[j * QB + 64 + lane];
     const float p0 = Ps[j * QB + lane], p1 = Ps[j * QB + 64 + lane];
     const float dj = dinv[j];
-    const bool mine = lane == jl;
+    const bool mine = lane == j;
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-      const float src = second ? w1[r] : w0[r];
-      const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(src), jl));
-      const float t = v * isc[r];
-      const float q = fminf(fmaxf(rintf(t) + zr[r], 0.f), a.maxq);
+      const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w0[r]), j));
+      const float q = fminf(fmaxf(rintf(v * isc[r]) + zr[r], 0.f), a.maxq);
       const float wh = sc[r] * (q - zr[r]);
-      const float ne = (wh - v) * dj;                   // -E_j
-      if (!second) {
-        w0[r] = fmaf(v, p0, fmaf(ne, u0, w0[r]));
-        if (mine) { w0[r] = wh; c0[r] = q; e0[r] = ne; v0[r] = v; }
-      }
+      const float ne = (wh - v) * dj;                     // -E_j
+      const float n0 = fmaf(v, p0, fmaf(ne, u0, w0[r]));
       w1[r] = fmaf(v, p1, fmaf(ne, u1, w1[r]));
-      if (second && mine) { w1[r] = wh; c1[r] = q; e1[r] = ne; v1[r] = v; }
+      w0[r] = mine ? wh : n0;
+      v0[r] = mine ? v : v0[r];
+    }
+  }
+  for (int j = 64; j < bw; ++j) {                          // columns held in w1; w0 is final
+    if (j == next_group) group_start(j);
+    const float u1 = Us[j * QB + 64 + lane], p1 = Ps[j * QB + 64 + lane];
+    const float dj = dinv[j];
+    const bool mine = lane == j - 64;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(w1[r]), j - 64));
+      const float q = fminf(fmaxf(rintf(v * isc[r]) + zr[r], 0.f), a.maxq);
+      const float wh = sc[r] * (q - zr[r]);
+      const float ne = (wh - v) * dj;
+      const float n1 = fmaf(v, p1, fmaf(ne, u1, w1[r]));
+      w1[r] = mine ? wh : n1;
+      v1[r] = mine ? v : v1[r];
     }
   }
 
+  const float d0 = dinv[lane], d1 = dinv[64 + lane];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int row = row0 + r;
     if (row >= a.m) continue;
+    const float q0 = fminf(fmaxf(rintf(v0[r] * (1.f / ms0[r])) + mz0[r], 0.f), a.maxq);
+    const float q1 = fminf(fmaxf(rintf(v1[r] * (1.f / ms1[r])) + mz1[r], 0.f), a.maxq);
+    const float e0 = (w0[r] - v0[r]) * d0, e1 = (w1[r] - v1[r]) * d1;       // -E; 0 in the padding
     if (lane < bw) {
       a.W[(int64_t)row * a.ldw + i0 + lane] = w0[r];
-      a.codes[(int64_t)row * a.n + i0 + lane] = (uint8_t)c0[r];
+      a.codes[(int64_t)row * a.n + i0 + lane] = (uint8_t)q0;
     }
     if (lane + 64 < bw) {
       a.W[(int64_t)row * a.ldw + i0 + 64 + lane] = w1[r];
-      a.codes[(int64_t)row * a.n + i0 + 64 + lane] = (uint8_t)c1[r];
+      a.codes[(int64_t)row * a.n + i0 + 64 + lane] = (uint8_t)q1;
     }
     const int64_t o = (int64_t)row * QB + lane;
     uint16_t h;
-    h = q_bf16_rne(e0[r]); a.Eh[o] = h; a.El[o] = q_bf16_rne(e0[r] - q_bf16_f32(h));
-    h = q_bf16_rne(e1[r]); a.Eh[o + 64] = h; a.El[o + 64] = q_bf16_rne(e1[r] - q_bf16_f32(h));
+    h = q_bf16_rne(e0); a.Eh[o] = h; a.El[o] = q_bf16_rne(e0 - q_bf16_f32(h));
+    h = q_bf16_rne(e1); a.Eh[o + 64] = h; a.El[o + 64] = q_bf16_rne(e1 - q_bf16_f32(h));
     h = q_bf16_rne(v0[r]); a.Vh[o] = h; a.Vl[o] = q_bf16_rne(v0[r] - q_bf16_f32(h));
     h = q_bf16_rne(v1[r]); a.Vh[o + 64] = h; a.Vl[o + 64] = q_bf16_rne(v1[r] - q_bf16_f32(h));
   }
