@@ -75,8 +75,8 @@ struct QuantArgs {
   uint16_t *Eh, *El, *Vh, *Vl;          // (rows x 128) bf16, -E and V split hi/lo
 };
 
-template <int R>
-__global__ __launch_bounds__(256) void quant_block_kernel(QuantArgs a) {
+template <int R, int NW>
+__global__ __launch_bounds__(64 * NW) void quant_block_kernel(QuantArgs a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   float* Us = reinterpret_cast<float*>(smem_raw);
   float* Ps = Us + QB * QB;
@@ -84,7 +84,7 @@ __global__ __launch_bounds__(256) void quant_block_kernel(QuantArgs a) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int i0 = a.i0, bw = a.bw;
 
-  for (int idx = tid; idx < QB * QB; idx += 256) {
+  for (int idx = tid; idx < QB * QB; idx += 64 * NW) {
     const int r = idx >> 7, c = idx & 127;
     float u = 0.f, p = 0.f;
     if (r < bw && c < bw && c >= r) {
@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void quant_block_kernel(QuantArgs a) {
   }
   if (tid < QB) dinv[tid] = tid < bw ? 1.f / a.U[(int64_t)(i0 + tid) * a.ldh + i0 + tid] : 0.f;
 
-  const int row0 = (blockIdx.x * 4 + wave) * R;
+  const int row0 = (blockIdx.x * NW + wave) * R;
   // w: the row's current values of the lane's two columns; v: the value each column had just before it
   // was quantised; (sc, zr): the current group's grid (wave-uniform); (ms, mz): the grid of the group
   // the lane's own columns belong to.  Codes and -E are recomputed per lane after the loop from
@@ -259,12 +259,32 @@ QLayout q_layout(int64_t m, int64_t n) {
   L.total = o;
   return L;
 }
-bool g_q_attr = false;
 
-template <int R>
-void launch_quant(const QuantArgs& a, hipStream_t s) {
-  const int rows_per_wg = 4 * R;
-  hipLaunchKernelGGL(quant_block_kernel<R>, dim3((a.m + rows_per_wg - 1) / rows_per_wg), dim3(256), Q_LDS, s, a);
+template <int R, int NW>
+hipError_t launch_quant(const QuantArgs& a, hipStream_t s) {
+  static bool attr = false;                      // per instantiation
+  if (!attr) {
+    hipError_t e = hipFuncSetAttribute((const void*)&quant_block_kernel<R, NW>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, Q_LDS);
+    if (e != hipSuccess) return e;
+    attr = true;
+  }
+  const int rows_per_wg = NW * R;
+  hipLaunchKernelGGL((quant_block_kernel<R, NW>), dim3((a.m + rows_per_wg - 1) / rows_per_wg), dim3(64 * NW), Q_LDS, s, a);
+  return hipGetLastError();
+}
+// Rows are spread over the 256 CUs with two wavefronts per SIMD where m allows it (the loop is a
+// dependency chain; the second wavefront hides its latencies).
+hipError_t launch_quant_for(const QuantArgs& a, hipStream_t s) {
+  const int m = a.m;
+  if (m <= 1024) return launch_quant<1, 4>(a, s);
+  const int r = (m + 2047) / 2048;
+  if (r <= 1) return launch_quant<1, 8>(a, s);
+  if (r <= 2) return launch_quant<2, 8>(a, s);
+  if (r <= 3) return launch_quant<3, 8>(a, s);
+  if (r <= 4) return launch_quant<4, 8>(a, s);
+  if (r <= 6) return launch_quant<6, 8>(a, s);
+  return launch_quant<8, 8>(a, s);
 }
 }  // namespace
 
@@ -285,15 +305,6 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
   const QLayout L = q_layout(m, n);
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
-  if (!g_q_attr) {
-    const void* fns[4] = {(const void*)&quant_block_kernel<1>, (const void*)&quant_block_kernel<2>,
-                          (const void*)&quant_block_kernel<4>, (const void*)&quant_block_kernel<8>};
-    for (const void* f : fns) {
-      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, Q_LDS);
-      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
-    }
-    g_q_attr = true;
-  }
   unsigned char* base = (unsigned char*)ws;
   uint16_t* buf[8];
   for (int i = 0; i < 8; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
@@ -318,12 +329,9 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
     a.i0 = (int)i0; a.bw = bw;
     {
       ProfScope ps(kProfColumnLoop, s);
-      if (m <= 1024) launch_quant<1>(a, s);
-      else if (m <= 2048) launch_quant<2>(a, s);
-      else if (m <= 8192) launch_quant<4>(a, s);
-      else launch_quant<8>(a, s);
+      hipError_t e = launch_quant_for(a, s);
+      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
     }
-    GPTAQ_LAUNCH_CHECK();
     if (i2 >= n) break;
     const int64_t nt = n - i2;
     const int tile = gemm_tile_for(m, nt);

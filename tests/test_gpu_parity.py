@@ -137,9 +137,12 @@ def test_whole_path_c1(c1):
     (4, 0, True, 128, 512, 512),         # per-channel symmetric
     (4, 32, False, 96, 200, 480),        # block not a power of two, ragged last block
     (4, 0, False, 50, 64, 130),          # tiny, ragged everything
-    (8, 16, False, 16, 1100, 256),       # two rows per wavefront
-    (4, 128, False, 128, 2500, 384),     # four rows per wavefront
-    (4, 64, False, 64, 8200, 256),       # eight rows per wavefront
+    (8, 16, False, 16, 1100, 256),       # one row per wavefront, eight wavefronts per workgroup
+    (4, 128, False, 128, 2500, 384),     # two rows per wavefront
+    (4, 128, False, 128, 5100, 256),     # three
+    (3, 0, False, 128, 7000, 128),       # four
+    (4, 64, False, 64, 8200, 256),       # six
+    (4, 0, False, 128, 16500, 128),      # eight, more than one round of workgroups
 ])
 def test_quantize_variants(c1, bits, group, sym, blocksize, m, n):
     Hn = c1["H"][:n, :n]; An = c1["A"][:n, :n]
