@@ -72,7 +72,8 @@ struct QuantArgs {
   const uint8_t* dead;
   float maxq; int group, sym, G;
   float* scales; float* zeros; uint8_t* codes;
-  uint16_t *Eh, *El, *Vh, *Vl;          // (rows x 128) bf16, -E and V split hi/lo
+  uint16_t *Eh, *El, *Vh, *Vl;          // bf16 hi/lo of -E and V: row stride ldev, this block's 128 slots at evoff
+  int64_t ldev; int evoff;
 };
 
 template <int R, int NW>
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(64 * NW) void quant_block_kernel(QuantArgs a) {
       a.W[(int64_t)row * a.ldw + i0 + 64 + lane] = w1[r];
       a.codes[(int64_t)row * a.n + i0 + 64 + lane] = (uint8_t)q1;
     }
-    const int64_t o = (int64_t)row * QB + lane;
+    const int64_t o = (int64_t)row * a.ldev + a.evoff + lane;
     uint16_t h;
     h = q_bf16_rne(e0); a.Eh[o] = h; a.El[o] = q_bf16_rne(e0 - q_bf16_f32(h));
     h = q_bf16_rne(e1); a.Eh[o + 64] = h; a.El[o + 64] = q_bf16_rne(e1 - q_bf16_f32(h));
@@ -205,23 +206,28 @@ __global__ __launch_bounds__(64 * NW) void quant_block_kernel(QuantArgs a) {
   }
 }
 
-// Right operands of the trailing GEMM: rows i0..i0+bw of U and P restricted to the columns
-// after the block, transposed to (column x 128) and split into bf16 hi+lo.
-// grid (ceil(ntrail_padded / 64), 2): blockIdx.y = 0 for U, 1 for P.
+// Right operands of a trailing GEMM: for each of the `gridDim.z` column blocks (chunk c covers the rows
+// sb0 + c * blocksize .. of U and P), the entries in the columns [c_begin, c_end), transposed to
+// (column x K) with the chunk's rows at K offsets 128 c .. 128 c + 127 (zero padded), split into bf16 hi+lo.
+// grid (ceil(padded columns / 64), 2, chunks): blockIdx.y = 0 for U, 1 for P.
 __global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* U, const float* P, int64_t ldh, int n,
-                                                                   int i0, int bw, int i2, uint16_t* Uth, uint16_t* Utl,
-                                                                   uint16_t* Pth, uint16_t* Ptl) {
+                                                                   int sb0, int blocksize, int c_begin, int c_end,
+                                                                   uint16_t* Uth, uint16_t* Utl, uint16_t* Pth,
+                                                                   uint16_t* Ptl, int64_t ldo) {
   __shared__ uint16_t th[64][QB + 2], tl[64][QB + 2];
   const float* S = blockIdx.y ? P : U;
   uint16_t* oh = blockIdx.y ? Pth : Uth;
   uint16_t* ol = blockIdx.y ? Ptl : Utl;
+  const int chunk = blockIdx.z;
+  const int i0 = sb0 + chunk * blocksize;
+  const int bw = min(blocksize, n - i0);
   const int j0 = blockIdx.x * 64;
   const int c = threadIdx.x & 63, kq = threadIdx.x >> 6;
-  const int col = i2 + j0 + c;
+  const int col = c_begin + j0 + c;
   for (int p = 0; p < QB / 4; ++p) {
     const int kk = kq + 4 * p;
     float v = 0.f;
-    if (kk < bw && col < n) v = S[(int64_t)(i0 + kk) * ldh + col];
+    if (kk < bw && col < c_end) v = S[(int64_t)(i0 + kk) * ldh + col];
     const uint16_t h = q_bf16_rne(v);
     th[c][kk] = h;
     tl[c][kk] = q_bf16_rne(v - q_bf16_f32(h));
@@ -233,8 +239,8 @@ __global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* 
     const int r = (threadIdx.x >> 6) + 4 * p;
     const uint32_t vh = (uint32_t)th[r][2 * d] | ((uint32_t)th[r][2 * d + 1] << 16);
     const uint32_t vl = (uint32_t)tl[r][2 * d] | ((uint32_t)tl[r][2 * d + 1] << 16);
-    reinterpret_cast<uint32_t*>(oh + (int64_t)(j0 + r) * QB)[d] = vh;
-    reinterpret_cast<uint32_t*>(ol + (int64_t)(j0 + r) * QB)[d] = vl;
+    reinterpret_cast<uint32_t*>(oh + (int64_t)(j0 + r) * ldo + chunk * QB)[d] = vh;
+    reinterpret_cast<uint32_t*>(ol + (int64_t)(j0 + r) * ldo + chunk * QB)[d] = vl;
   }
 }
 
@@ -243,18 +249,21 @@ __global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* 
 using namespace gptaq;
 
 namespace {
+constexpr int SB = 4;                         // column blocks per super-block (two-level lazy batching)
+constexpr int KS = SB * QB;
 struct QLayout {
   int64_t mp, np;
-  size_t off[8], total;
+  size_t off[12], total;
 };
 QLayout q_layout(int64_t m, int64_t n) {
   QLayout L;
   L.mp = round_up(m, 256);
   L.np = round_up(n, 256);
   size_t o = 0;
-  for (int i = 0; i < 8; ++i) {
+  for (int i = 0; i < 12; ++i) {
     L.off[i] = o;
-    o += (size_t)((i < 4 ? L.mp : L.np) * QB * 2);
+    // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of the far update; 8-11: of a near update
+    o += (size_t)(i < 4 ? L.mp * KS * 2 : i < 8 ? L.np * KS * 2 : (int64_t)KS * QB * 2);
   }
   L.total = o;
   return L;
@@ -306,8 +315,8 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   unsigned char* base = (unsigned char*)ws;
-  uint16_t* buf[8];
-  for (int i = 0; i < 8; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
+  uint16_t* buf[12];
+  for (int i = 0; i < 12; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
 
   QuantArgs a;
   a.W = W; a.ldw = ldw; a.m = (int)m; a.n = (int)n;
@@ -315,47 +324,67 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
   a.maxq = (float)((1 << bits) - 1); a.group = group; a.sym = sym;
   a.G = group > 0 ? (int)(n / group) : 1;
   a.scales = scales; a.zeros = zeros; a.codes = codes;
-  a.Eh = buf[0]; a.El = buf[1]; a.Vh = buf[2]; a.Vl = buf[3];
-  uint16_t *Uth = buf[4], *Utl = buf[5], *Pth = buf[6], *Ptl = buf[7];
+  a.Eh = buf[0]; a.El = buf[1]; a.Vh = buf[2]; a.Vl = buf[3]; a.ldev = KS;
 
   if (group <= 0) {
     hipLaunchKernelGGL(row_params_kernel, dim3((unsigned)((m + 3) / 4)), dim3(256), 0, s, W, ldw, (int)m, (int)n, dead,
                        a.maxq, sym, scales, zeros);
     GPTAQ_LAUNCH_CHECK();
   }
-  for (int64_t i0 = 0; i0 < n; i0 += blocksize) {
-    const int bw = (int)(n - i0 < blocksize ? n - i0 : blocksize);
-    const int64_t i2 = i0 + bw;
-    a.i0 = (int)i0; a.bw = bw;
-    {
-      ProfScope ps(kProfColumnLoop, s);
-      hipError_t e = launch_quant_for(a, s);
-      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
-    }
-    if (i2 >= n) break;
-    const int64_t nt = n - i2;
+  // Two-level lazy batching (a re-association of the sums of Eq. 18): a block's update reaches the rest
+  // of its super-block at once ("near", K = one block), and the columns after the super-block once per
+  // super-block ("far", K = SB blocks), which quarters the passes over W of the flat schedule.
+  auto trailing = [&](int64_t c0, int64_t c1, const uint16_t* const* L4, int64_t ldl, uint16_t* const* R4, int64_t ldr,
+                      int K, int sb0, int nchunks) -> int {
+    const int64_t nt = c1 - c0;
     const int tile = gemm_tile_for(m, nt);
     const int64_t ntp = round_up(nt, tile);
     {
       ProfScope ps(kProfTrailSplit, s);
-      hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(ntp / 64), 2), dim3(256), 0, s, U, P, ldh,
-                         (int)n, (int)i0, bw, (int)i2, Uth, Utl, Pth, Ptl);
+      hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(ntp / 64), 2, (unsigned)nchunks), dim3(256), 0, s,
+                         U, P, ldh, (int)n, sb0, blocksize, (int)c0, (int)c1, R4[0], R4[1], R4[2], R4[3], ldr);
     }
     GPTAQ_LAUNCH_CHECK();
     GemmBatch b;
     b.nprob = 1; b.tile = tile;
     GemmProblem& g = b.p[0];
-    g.C = W + i2; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = QB;
+    g.C = W + c0; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = K;
     g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(ntp / tile);
     g.kind = 2; g.nterm = 2; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
-    g.term[0] = {{a.Eh, a.El}, {Uth, Utl}, QB, QB, 32, 32};
-    g.term[1] = {{a.Vh, a.Vl}, {Pth, Ptl}, QB, QB, 32, 32};
+    g.term[0] = {{L4[0], L4[1]}, {R4[0], R4[1]}, ldl, ldr, 32, 32};
+    g.term[1] = {{L4[2], L4[3]}, {R4[2], R4[3]}, ldl, ldr, 32, 32};
     hipError_t e;
     {
       ProfScope ps(kProfTrailGemm, s);
       e = launch_gemm(b, s);
     }
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+    return GPTAQ_OK;
+  };
+  for (int64_t sb0 = 0; sb0 < n; sb0 += (int64_t)SB * blocksize) {
+    const int64_t sb_end = n < sb0 + (int64_t)SB * blocksize ? n : sb0 + (int64_t)SB * blocksize;
+    const int nb = (int)((sb_end - sb0 + blocksize - 1) / blocksize);
+    for (int p = 0; p < nb; ++p) {
+      const int64_t i0 = sb0 + (int64_t)p * blocksize;
+      const int bw = (int)(n - i0 < blocksize ? n - i0 : blocksize);
+      const int64_t i2 = i0 + bw;
+      a.i0 = (int)i0; a.bw = bw; a.evoff = p * QB;
+      {
+        ProfScope ps(kProfColumnLoop, s);
+        hipError_t e = launch_quant_for(a, s);
+        if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+      }
+      if (i2 < sb_end) {
+        const uint16_t* L4[4] = {a.Eh + p * QB, a.El + p * QB, a.Vh + p * QB, a.Vl + p * QB};
+        const int rc = trailing(i2, sb_end, L4, KS, buf + 8, QB, QB, (int)i0, 1);
+        if (rc != GPTAQ_OK) return rc;
+      }
+    }
+    if (sb_end < n) {
+      const uint16_t* L4[4] = {a.Eh, a.El, a.Vh, a.Vl};
+      const int rc = trailing(sb_end, n, L4, KS, buf + 4, KS, nb * QB, (int)sb0, nb);
+      if (rc != GPTAQ_OK) return rc;
+    }
   }
   return GPTAQ_OK;
 }

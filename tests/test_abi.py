@@ -46,7 +46,7 @@ def test_workspace_queries(lib):
     assert lib.gptaq_accumulate_workspace_bytes(262144, 4096) == 3 * 4096 * 16384 * 2
     assert lib.gptaq_accumulate_workspace_bytes(0, 512) == 0
     assert lib.gptaq_prepare_workspace_bytes(512) > 512 * 512 * 8
-    assert lib.gptaq_quantize_workspace_bytes(512, 512) == 8 * 512 * 128 * 2
+    assert lib.gptaq_quantize_workspace_bytes(512, 512) == (4 * 512 * 512 + 4 * 512 * 512 + 4 * 512 * 128) * 2
     assert lib.gptaq_status_string(0) == b"ok"
 
 
