@@ -153,6 +153,19 @@ def main() -> int:
         flops += (n * (n + 1) + 2 * n * n) * float(wl.tokens)
     flops *= args.steps
     achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
+    # secondary kernels (from the untimed, fully bracketed pass): column loop against HBM with 17 algorithmic bytes
+    # per weight (read W 4, write W^ 4, code 1, -E and V 8), trailing update with 2 m n^2 algorithmic flop per layer
+    wbytes = 17.0 * sum(l.m * l.n for l in wl.layers)
+    tflop = 2.0 * sum(l.m * l.n * l.n for l in wl.layers)
+    other = {
+        "column_loop": {"bound": "hbm", "achieved": wbytes / (prof["column_loop"][1] * 1e-3) / 1e9, "peak": 8000.0,
+                        "unit": "GB/s", "frac": wbytes / (prof["column_loop"][1] * 1e-3) / 1e9 / 8000.0,
+                        "note": "n sequential column steps per layer bound this kernel, not bandwidth"},
+        "trailing_gemm": {"bound": "mfma", "achieved": tflop / (prof["trailing_gemm"][1] * 1e-3) / 1e12,
+                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                          "frac": tflop / (prof["trailing_gemm"][1] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+                          "note": "algorithmic 2 m n^2 flop; executed x3 (bf16 hi/lo split for fp32 accuracy)"},
+    }
     traffic = None
     tpath = os.path.join(ROOT, "profiles", f"{wl.name}_block_hbm_traffic.json")
     if os.path.exists(tpath):          # HBM bytes per launch from the separate rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
@@ -170,6 +183,7 @@ def main() -> int:
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "launches": launches, "avg_launch_ms": gemm_ms / max(1, launches)},
+        "other_kernels": other,
         "stages_ms_per_step": stage_ms,
         "kernels_ms_per_step": {k: v[1] for k, v in prof.items()},
         "kernel_launches_per_step": {k: v[0] for k, v in prof.items()},

@@ -115,6 +115,16 @@ int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
                          uint8_t* codes, float* scales, float* zeros,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* The same solve with only some of the two update terms of Eq. 15 applied (the ablation of
+ * Section 5.5): terms bit 0 = the quantisation-error term -E_j U[j, j:], bit 1 = the residual term
+ * v_j P[j, j:].  3 = GPTAQ (gptaq_quantize_layer), 1 = GPTQ (P may be NULL), 2 = the second term
+ * alone, 0 = round to nearest.  All other arguments as in gptaq_quantize_layer. */
+int gptaq_quantize_layer_terms(float* W, int64_t m, int64_t n, int64_t ldw,
+                               const float* U, const float* P, int64_t ldh, const uint8_t* dead,
+                               int bits, int group, int sym, int blocksize,
+                               uint8_t* codes, float* scales, float* zeros,
+                               void* ws, size_t ws_bytes, void* stream, int terms);
+
 /* ---------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  While enabled, the library brackets its kernels
  * with HIP events on the caller's stream, grouped by tag:

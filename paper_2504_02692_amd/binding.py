@@ -32,6 +32,10 @@ _SIGS = {
                                         _c.c_int64, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                         _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                         _c.c_void_p]),
+    "gptaq_quantize_layer_terms": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p,
+                                              _c.c_int64, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                              _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
+                                              _c.c_void_p, _c.c_int]),
     "gptaq_profile_enable": (_c.c_int, [_c.c_int]),
     "gptaq_profile_read": (_c.c_int, [_c.c_int, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_double)]),
 }
@@ -132,11 +136,16 @@ def gptaq_prepare(H: torch.Tensor, dXXT: torch.Tensor, damp: float, ws: torch.Te
 def gptaq_quantize_layer(W: torch.Tensor, U: torch.Tensor, P: torch.Tensor, bits: int, group: int, sym: bool,
                          blocksize: int, ws: torch.Tensor, dead: Optional[torch.Tensor] = None,
                          codes: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
-                         zeros: Optional[torch.Tensor] = None):
-    """In place: W -> dequantised quantised weights.  Returns (codes, scales, zeros)."""
-    _need(W, torch.float32, "W"); _need(U, torch.float32, "U"); _need(P, torch.float32, "P")
+                         zeros: Optional[torch.Tensor] = None, terms: int = 3):
+    """In place: W -> dequantised quantised weights.  Returns (codes, scales, zeros).
+    terms != 3 goes through gptaq_quantize_layer_terms (1: E term only = GPTQ, P may be None)."""
+    _need(W, torch.float32, "W"); _need(U, torch.float32, "U")
     m, n = W.shape
-    if U.shape != (n, n) or P.shape != (n, n) or U.stride(0) != P.stride(0):
+    if P is not None:
+        _need(P, torch.float32, "P")
+        if P.shape != (n, n) or U.stride(0) != P.stride(0):
+            raise GptaqError("gptaq_quantize_layer: shape mismatch")
+    if U.shape != (n, n):
         raise GptaqError("gptaq_quantize_layer: shape mismatch")
     G = max(1, n // group) if group > 0 else 1
     if codes is None:
@@ -145,11 +154,16 @@ def gptaq_quantize_layer(W: torch.Tensor, U: torch.Tensor, P: torch.Tensor, bits
         scales = torch.empty((m, G), dtype=torch.float32, device=W.device)
     if zeros is None:
         zeros = torch.empty((m, G), dtype=torch.float32, device=W.device)
-    _check(load().gptaq_quantize_layer(_ptr(W), m, n, W.stride(0), _ptr(U), _ptr(P), U.stride(0), _ptr(dead),
-                                       int(bits), int(group), int(bool(sym)), int(blocksize), _ptr(codes),
-                                       _ptr(scales), _ptr(zeros), _ptr(ws), ws.numel(), _stream()),
-           "gptaq_quantize_layer")
+    args = (_ptr(W), m, n, W.stride(0), _ptr(U), _ptr(P), U.stride(0), _ptr(dead), int(bits), int(group),
+            int(bool(sym)), int(blocksize), _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(ws), ws.numel(), _stream())
+    if terms == 3:
+        _check(load().gptaq_quantize_layer(*args), "gptaq_quantize_layer")
+    else:
+        _check(load().gptaq_quantize_layer_terms(*args, int(terms)), "gptaq_quantize_layer_terms")
     return codes, scales, zeros
+
+
+gptaq_quantize_layer_terms = gptaq_quantize_layer
 
 
 def gptaq_profile_enable(mask: int) -> None:

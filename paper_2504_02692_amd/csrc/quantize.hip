@@ -70,7 +70,7 @@ struct QuantArgs {
   float* W; int64_t ldw; int m, n, i0, bw;
   const float* U; const float* P; int64_t ldh;
   const uint8_t* dead;
-  float maxq; int group, sym, G;
+  float maxq; int group, sym, G, terms;        // terms: bit 0 = E term, bit 1 = P term of Eq. 15
   float* scales; float* zeros; uint8_t* codes;
   uint16_t *Eh, *El, *Vh, *Vl;          // bf16 hi/lo of -E and V: row stride ldev, this block's 128 slots at evoff
   int64_t ldev; int evoff;
@@ -90,8 +90,8 @@ __global__ __launch_bounds__(64 * NW) void quant_block_kernel(QuantArgs a) {
     float u = 0.f, p = 0.f;
     if (r < bw && c < bw && c >= r) {
       const int64_t o = (int64_t)(i0 + r) * a.ldh + i0 + c;
-      u = a.U[o];
-      if (c > r) p = a.P[o];
+      if (c == r || (a.terms & 1)) u = a.U[o];          // the diagonal is always needed (E divides by it)
+      if (c > r && (a.terms & 2)) p = a.P[o];
     }
     Us[idx] = u;
     Ps[idx] = p;
@@ -302,11 +302,12 @@ extern "C" size_t gptaq_quantize_workspace_bytes(int64_t m, int64_t n) {
   return q_layout(m, n).total;
 }
 
-extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
-                                    int64_t ldh, const uint8_t* dead, int bits, int group, int sym, int blocksize,
-                                    uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
-                                    void* stream) {
-  if (!W || !U || !P || !codes || !scales || !zeros || !ws) return GPTAQ_ENULL;
+static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
+                               int64_t ldh, const uint8_t* dead, int bits, int group, int sym, int blocksize,
+                               uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
+                               void* stream, int terms) {
+  if (!W || !U || (!P && (terms & 2)) || !codes || !scales || !zeros || !ws) return GPTAQ_ENULL;
+  if (terms < 0 || terms > 3) return GPTAQ_EUNSUPPORTED;
   if (m <= 0 || n <= 0 || ldw < n || ldh < n || m > (1 << 24) || n > (1 << 24)) return GPTAQ_EDIM;
   if (bits < 2 || bits > 8 || blocksize < 1 || blocksize > QB) return GPTAQ_EUNSUPPORTED;
   if (group > 0 && (n % group || blocksize % group || group > QB)) return GPTAQ_EUNSUPPORTED;
@@ -321,7 +322,7 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
   QuantArgs a;
   a.W = W; a.ldw = ldw; a.m = (int)m; a.n = (int)n;
   a.U = U; a.P = P; a.ldh = ldh; a.dead = dead;
-  a.maxq = (float)((1 << bits) - 1); a.group = group; a.sym = sym;
+  a.maxq = (float)((1 << bits) - 1); a.group = group; a.sym = sym; a.terms = terms;
   a.G = group > 0 ? (int)(n / group) : 1;
   a.scales = scales; a.zeros = zeros; a.codes = codes;
   a.Eh = buf[0]; a.El = buf[1]; a.Vh = buf[2]; a.Vl = buf[3]; a.ldev = KS;
@@ -336,13 +337,15 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
   // super-block ("far", K = SB blocks), which quarters the passes over W of the flat schedule.
   auto trailing = [&](int64_t c0, int64_t c1, const uint16_t* const* L4, int64_t ldl, uint16_t* const* R4, int64_t ldr,
                       int K, int sb0, int nchunks) -> int {
+    if (terms == 0) return GPTAQ_OK;                    // no update at all: round to nearest
     const int64_t nt = c1 - c0;
     const int tile = gemm_tile_for(m, nt);
     const int64_t ntp = round_up(nt, tile);
     {
       ProfScope ps(kProfTrailSplit, s);
       hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(ntp / 64), 2, (unsigned)nchunks), dim3(256), 0, s,
-                         U, P, ldh, (int)n, sb0, blocksize, (int)c0, (int)c1, R4[0], R4[1], R4[2], R4[3], ldr);
+                         U, (terms & 2) ? P : U, ldh, (int)n, sb0, blocksize, (int)c0, (int)c1, R4[0], R4[1], R4[2],
+                         R4[3], ldr);
     }
     GPTAQ_LAUNCH_CHECK();
     GemmBatch b;
@@ -350,9 +353,9 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
     GemmProblem& g = b.p[0];
     g.C = W + c0; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = K;
     g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(ntp / tile);
-    g.kind = 2; g.nterm = 2; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
-    g.term[0] = {{L4[0], L4[1]}, {R4[0], R4[1]}, ldl, ldr, 32, 32};
-    g.term[1] = {{L4[2], L4[3]}, {R4[2], R4[3]}, ldl, ldr, 32, 32};
+    g.kind = 2; g.nterm = 0; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
+    if (terms & 1) g.term[g.nterm++] = {{L4[0], L4[1]}, {R4[0], R4[1]}, ldl, ldr, 32, 32};
+    if (terms & 2) g.term[g.nterm++] = {{L4[2], L4[3]}, {R4[2], R4[3]}, ldl, ldr, 32, 32};
     hipError_t e;
     {
       ProfScope ps(kProfTrailGemm, s);
@@ -387,4 +390,20 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
     }
   }
   return GPTAQ_OK;
+}
+
+extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
+                                    int64_t ldh, const uint8_t* dead, int bits, int group, int sym, int blocksize,
+                                    uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
+                                    void* stream) {
+  return quantize_layer_impl(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, blocksize, codes, scales, zeros, ws,
+                             ws_bytes, stream, 3);
+}
+
+extern "C" int gptaq_quantize_layer_terms(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
+                                          int64_t ldh, const uint8_t* dead, int bits, int group, int sym,
+                                          int blocksize, uint8_t* codes, float* scales, float* zeros, void* ws,
+                                          size_t ws_bytes, void* stream, int terms) {
+  return quantize_layer_impl(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, blocksize, codes, scales, zeros, ws,
+                             ws_bytes, stream, terms);
 }

@@ -176,3 +176,14 @@ def test_quantize_with_dead_input():
     got = PU.gpu_quantize(W, Hd, Ad, 4, 0, False, 128, dead=dd)
     assert np.all(got["What"][:, 70] == 0)
     PU.check_against_oracle(W, U, P, got, 4, 0, False, dead=dead, Xb=Xb, Xtb=Xtb, label="dead input")
+
+
+@pytest.mark.parametrize("terms,name", [(1, "GPTQ: E term only"), (2, "P term only"), (0, "round to nearest")])
+def test_update_term_ablation(c1, terms, name):
+    """Section 5.5: the two terms of the update applied individually (or not at all)."""
+    wl = c1["wl"]
+    U32, P32 = c1["U"].astype(np.float32), c1["P"].astype(np.float32)
+    Pd = dev(P32) if terms & 2 else None
+    got = PU.gpu_quantize(c1["W"], dev(U32), Pd, 4, 128, False, 128, terms=terms)
+    PU.check_against_oracle(c1["W"], U32.astype(np.float64), P32.astype(np.float64), got, 4, 128, False,
+                            Xb=c1["Xb"], Xtb=c1["Xtb"], label=name, terms=terms)
