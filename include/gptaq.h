@@ -126,6 +126,32 @@ int gptaq_quantize_layer_terms(float* W, int64_t m, int64_t n, int64_t ldw,
                                void* ws, size_t ws_bytes, void* stream, int terms);
 
 /* ---------------------------------------------------------------------------------------
+ * act_order (Sections 5.2, 5.3): quantise the input channels in the order of decreasing Hessian
+ * diagonal.  The solve is unchanged; these calls permute its inputs and scatter its outputs back:
+ *
+ *   gptaq_act_order(H) -> perm;  gptaq_permute_hessian(H, dXXT, perm);  Wp = W[:, perm];
+ *   gptaq_prepare;  gptaq_quantize_layer(Wp ...);  W^[:, perm] = Wp^;  codes[:, perm] = codes_p.
+ *
+ * Groups are groups of consecutive PERMUTED columns: original column perm[i] belongs to group
+ * i / group, and scales / zeros are indexed by that group.
+ *
+ * gptaq_act_order: perm[r] = index of the input with the r-th largest H[i][i]; equal diagonals keep
+ *   their index order.  perm: n x int32 (device).
+ * gptaq_permute_hessian: in place H[i][j] <- H[perm[i]][perm[j]] (upper triangle in, upper triangle
+ *   out) and dXXT[i][j] <- dXXT[perm[i]][perm[j]];  ws: gptaq_permute_hessian_workspace_bytes(n).
+ * gptaq_permute_columns_{f32,u8}: inverse == 0: out[r][i] = in[r][perm[i]];
+ *   inverse != 0: out[r][perm[i]] = in[r][i].  in and out must not overlap.
+ */
+int gptaq_act_order(const float* H, int64_t n, int64_t ldh, int32_t* perm, void* stream);
+size_t gptaq_permute_hessian_workspace_bytes(int64_t n);
+int gptaq_permute_hessian(float* H, float* dXXT, int64_t n, int64_t ldh, const int32_t* perm,
+                          void* ws, size_t ws_bytes, void* stream);
+int gptaq_permute_columns_f32(const float* in, float* out, int64_t m, int64_t n, int64_t ldin,
+                              int64_t ldout, const int32_t* perm, int inverse, void* stream);
+int gptaq_permute_columns_u8(const uint8_t* in, uint8_t* out, int64_t m, int64_t n, int64_t ldin,
+                             int64_t ldout, const int32_t* perm, int inverse, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  While enabled, the library brackets its kernels
  * with HIP events on the caller's stream, grouped by tag:
  *   0 accumulate MFMA GEMM (H and dXXT, one launch per pass)   1 accumulate split/transpose pass

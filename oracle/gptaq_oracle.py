@@ -244,6 +244,31 @@ def quantize_layer_blocked(W, U, P, bits, group=0, sym=False, blocksize=128, dea
     return dict(codes=codes, scales=scales, zeros=zeros, What=What)
 
 
+# ------------------------------------------------ act_order (Sections 5.2 and 5.3)
+def act_order_permutation(H: np.ndarray) -> np.ndarray:
+    """Inputs in the order of decreasing Hessian diagonal (the act_order option the paper takes from
+    GPTQ); equal diagonals keep their index order."""
+    return np.argsort(-np.diag(np.asarray(H, np.float64)), kind="stable")
+
+
+def solve_with_act_order(W, H, dXXT, damp, bits, group=0, sym=False):
+    """Algorithm 1 on the permuted problem, results scattered back to the original column order.
+    scales/zeros stay indexed by groups of consecutive permuted columns."""
+    perm = act_order_permutation(H)
+    Hp = np.asarray(H, np.float64)[np.ix_(perm, perm)]
+    Ap = np.asarray(dXXT, np.float64)[np.ix_(perm, perm)]
+    U, P, dead = prepare(Hp, Ap, damp)
+    out = quantize_layer(np.asarray(W, np.float64)[:, perm], U, P, bits, group, sym, dead=dead)
+    res = dict(out)
+    for key in ("codes", "What"):
+        back = np.empty_like(out[key])
+        back[:, perm] = out[key]
+        res[key] = back
+    res["perm"] = perm
+    res["U"], res["P"] = U, P
+    return res
+
+
 # --------------------------------------------------------------- Eq. 4 objective
 def layer_output_error(W, What, X_bits, Xtilde_bits) -> float:
     """|| What X - W X~ ||_F^2 (Eq. 4), original W, undamped data."""

@@ -36,6 +36,14 @@ _SIGS = {
                                               _c.c_int64, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                               _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                               _c.c_void_p, _c.c_int]),
+    "gptaq_act_order": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p]),
+    "gptaq_permute_hessian_workspace_bytes": (_c.c_size_t, [_c.c_int64]),
+    "gptaq_permute_hessian": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p,
+                                         _c.c_size_t, _c.c_void_p]),
+    "gptaq_permute_columns_f32": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_int64,
+                                             _c.c_void_p, _c.c_int, _c.c_void_p]),
+    "gptaq_permute_columns_u8": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_int64,
+                                            _c.c_void_p, _c.c_int, _c.c_void_p]),
     "gptaq_profile_enable": (_c.c_int, [_c.c_int]),
     "gptaq_profile_read": (_c.c_int, [_c.c_int, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_double)]),
 }
@@ -176,3 +184,46 @@ def gptaq_profile_read(tag: int):
     n, ms = _c.c_int64(0), _c.c_double(0.0)
     _check(load().gptaq_profile_read(int(tag), _c.byref(n), _c.byref(ms)), "gptaq_profile_read")
     return n.value, ms.value
+
+
+def gptaq_act_order(H: torch.Tensor) -> torch.Tensor:
+    """perm (int32, device): inputs in the order of decreasing H[i][i]."""
+    _need(H, torch.float32, "H")
+    n = H.shape[0]
+    perm = torch.empty(n, dtype=torch.int32, device=H.device)
+    _check(load().gptaq_act_order(_ptr(H), n, H.stride(0), _ptr(perm), _stream()), "gptaq_act_order")
+    return perm
+
+
+def gptaq_permute_hessian_workspace_bytes(n: int) -> int:
+    return load().gptaq_permute_hessian_workspace_bytes(n)
+
+
+def gptaq_permute_hessian(H: torch.Tensor, dXXT: torch.Tensor, perm: torch.Tensor, ws: torch.Tensor) -> None:
+    _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
+    n = H.shape[0]
+    if dXXT.shape != (n, n) or H.stride(0) != dXXT.stride(0) or perm.dtype != torch.int32 or perm.numel() != n:
+        raise GptaqError("gptaq_permute_hessian: shape mismatch")
+    _check(load().gptaq_permute_hessian(_ptr(H), _ptr(dXXT), n, H.stride(0), _ptr(perm), _ptr(ws), ws.numel(),
+                                        _stream()), "gptaq_permute_hessian")
+
+
+def _permute_columns(fn, name, src: torch.Tensor, perm: torch.Tensor, inverse: bool) -> torch.Tensor:
+    if src.dim() != 2 or src.stride(1) != 1 or perm.dtype != torch.int32 or perm.numel() != src.shape[1]:
+        raise GptaqError(f"{name}: shape mismatch")
+    out = torch.empty_like(src, memory_format=torch.contiguous_format)
+    m, n = src.shape
+    _check(fn(_ptr(src), _ptr(out), m, n, src.stride(0), out.stride(0), _ptr(perm), int(bool(inverse)), _stream()), name)
+    return out
+
+
+def gptaq_permute_columns_f32(src: torch.Tensor, perm: torch.Tensor, inverse: bool = False) -> torch.Tensor:
+    if src.dtype != torch.float32:
+        raise GptaqError("gptaq_permute_columns_f32: expected float32")
+    return _permute_columns(load().gptaq_permute_columns_f32, "gptaq_permute_columns_f32", src, perm, inverse)
+
+
+def gptaq_permute_columns_u8(src: torch.Tensor, perm: torch.Tensor, inverse: bool = False) -> torch.Tensor:
+    if src.dtype != torch.uint8:
+        raise GptaqError("gptaq_permute_columns_u8: expected uint8")
+    return _permute_columns(load().gptaq_permute_columns_u8, "gptaq_permute_columns_u8", src, perm, inverse)

@@ -187,3 +187,34 @@ def test_update_term_ablation(c1, terms, name):
     got = PU.gpu_quantize(c1["W"], dev(U32), Pd, 4, 128, False, 128, terms=terms)
     PU.check_against_oracle(c1["W"], U32.astype(np.float64), P32.astype(np.float64), got, 4, 128, False,
                             Xb=c1["Xb"], Xtb=c1["Xtb"], label=name, terms=terms)
+
+
+def test_act_order_path():
+    """act_order: permutation from the Hessian diagonal, permuted solve, results scattered back."""
+    from paper_2504_02692_amd import binding as B
+    n, m, k, bits, group = 384, 200, 3000, 3, 128
+    Xb, Xtb = synth.make_activations(k, n, 12, "ao", 3, 30.0)
+    W = synth.make_weights(m, n, 12, "ao")
+    Hd, Ad = PU.gpu_accumulate(Xb, Xtb)
+    Hg = upper_to_full(Hd); Ag = Ad.cpu().numpy().astype(np.float64)
+    perm = B.gptaq_act_order(Hd)
+    ref = O.solve_with_act_order(W, Hg, Ag, 0.1, bits, group, True)     # ViT / weight-only setting: damp 10 %, symmetric
+    assert np.array_equal(perm.cpu().numpy(), ref["perm"])
+    B.gptaq_permute_hessian(Hd, Ad, perm, B.workspace(B.gptaq_permute_hessian_workspace_bytes(n)))
+    torch.cuda.synchronize()
+    hp = upper_to_full(Hd)
+    assert np.array_equal(hp, Hg[np.ix_(ref["perm"], ref["perm"])])
+    assert np.array_equal(Ad.cpu().numpy().astype(np.float64), Ag[np.ix_(ref["perm"], ref["perm"])])
+    dead, info = PU.gpu_prepare(Hd, Ad, 0.1)
+    Wp = B.gptaq_permute_columns_f32(torch.from_numpy(W).cuda(), perm)
+    assert np.array_equal(Wp.cpu().numpy(), W[:, ref["perm"]])
+    ws = B.workspace(B.gptaq_quantize_workspace_bytes(m, n))
+    codes_p, scales, zeros = B.gptaq_quantize_layer(Wp, Hd, Ad, bits, group, True, 128, ws, dead=dead)
+    What = B.gptaq_permute_columns_f32(Wp, perm, inverse=True)
+    codes = B.gptaq_permute_columns_u8(codes_p, perm, inverse=True)
+    torch.cuda.synchronize()
+    # compare in permuted order with the near-tie protocol, and the scatter exactly
+    got = dict(What=Wp.cpu().numpy(), codes=codes_p.cpu().numpy(), scales=scales.cpu().numpy(), zeros=zeros.cpu().numpy())
+    PU.check_against_oracle(W[:, ref["perm"]], ref["U"], ref["P"], got, bits, group, True, label="act_order")
+    assert np.array_equal(codes.cpu().numpy()[:, ref["perm"]], got["codes"])
+    assert np.array_equal(What.cpu().numpy()[:, ref["perm"]], got["What"])

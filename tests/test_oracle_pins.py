@@ -358,3 +358,20 @@ def test_planted_mistakes_are_caught():
     assert np.array_equal(O.quantize_layer(W, U, P, 3)["codes"], ref["codes"])
     assert not np.array_equal(O.quantize_layer(W, U, P, 3, use_E=False)["codes"], ref["codes"])
     assert not np.array_equal(O.quantize_layer(W, L, P, 3)["codes"], ref["codes"])   # L for L^T
+
+
+def test_act_order_is_the_same_solve_on_permuted_inputs():
+    """act_order only reorders the inputs: solving with the permutation equals relabelling the neurons
+    of X, X~ and the columns of W beforehand, and the order is by decreasing diagonal, ties by index."""
+    W, Xb, Xtb = tiny_problem(n=24, m=6, k=200, seed=4)
+    H, A = O.accumulate(Xb, Xtb)
+    perm = O.act_order_permutation(H)
+    d = np.diag(H)[perm]
+    assert np.all(d[:-1] >= d[1:]) and sorted(perm.tolist()) == list(range(24))
+    assert O.act_order_permutation(np.diag([3.0, 5.0, 3.0, 7.0])).tolist() == [3, 1, 0, 2]
+    out = O.solve_with_act_order(W, H, A, 0.01, 3, group=8)
+    Hp, Ap = O.accumulate(Xb[:, perm], Xtb[:, perm])          # relabelled neurons
+    U, P, _ = O.prepare(Hp, Ap, 0.01)
+    ref = O.quantize_layer(W[:, perm], U, P, 3, 8)
+    assert np.array_equal(out["codes"][:, perm], ref["codes"])
+    assert np.allclose(out["What"][:, perm], ref["What"], rtol=0, atol=1e-12)
