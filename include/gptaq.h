@@ -125,6 +125,20 @@ int gptaq_quantize_layer_terms(float* W, int64_t m, int64_t n, int64_t ldw,
                                uint8_t* codes, float* scales, float* zeros,
                                void* ws, size_t ws_bytes, void* stream, int terms);
 
+/* The same solve with the clip-range search of Section 5.1 for the weight grid ("searched by
+ * minimizing mean squared error"): whenever a (scale, zero) pair is taken from a range, the candidates
+ * p = 1 - i / mse_grid, i = 0 .. mse_steps - 1, shrink that range about its zero-point
+ * (scale_i = p * scale_0, same zero-point); the candidate with the smallest sum of squared
+ * quantisation errors over the row-group is used (the earlier one on ties).  mse_steps = 0 is the
+ * plain min-max grid; GPTQ's customary setting is mse_grid = 100, mse_steps = 80.
+ * terms as in gptaq_quantize_layer_terms (3 = both). */
+int gptaq_quantize_layer_ex(float* W, int64_t m, int64_t n, int64_t ldw,
+                            const float* U, const float* P, int64_t ldh, const uint8_t* dead,
+                            int bits, int group, int sym, int blocksize,
+                            uint8_t* codes, float* scales, float* zeros,
+                            void* ws, size_t ws_bytes, void* stream,
+                            int terms, int mse_grid, int mse_steps);
+
 /* ---------------------------------------------------------------------------------------
  * act_order (Sections 5.2, 5.3): quantise the input channels in the order of decreasing Hessian
  * diagonal.  The solve is unchanged; these calls permute its inputs and scatter its outputs back:

@@ -115,6 +115,47 @@ def quant_params(xmin: np.ndarray, xmax: np.ndarray, bits: int, sym: bool):
     return scale, zero
 
 
+def quant_params_mse(block: np.ndarray, bits: int, sym: bool, grid: int, steps: int,
+                     hint_scales=None, rel_tol=0.0):
+    """Clip-range search of Section 5.1 ("the weight clipping range is searched by minimizing mean
+    squared error"), read as: the candidates p = 1 - i/grid, i = 0..steps-1, shrink the min-max range
+    of each row of `block` about its zero-point (scale_i = fp32(p * (xmax - xmin)/maxq), zero-point of
+    the full range); the candidate with the smallest sum of squared errors wins, the earlier on ties.
+    With `hint_scales`, a hinted scale is accepted for a row if it is (to 1e-5) one of the row's
+    candidates and that candidate's error is within rel_tol of the best.  Returns scale, zero, #hints."""
+    maxq = float(2 ** bits - 1)
+    xmin = np.minimum(block.min(axis=1), 0.0)
+    xmax = np.maximum(block.max(axis=1), 0.0)
+    if sym:
+        xmax = np.maximum(np.abs(xmin), xmax)
+        xmin = -xmax
+    flat = (xmin == 0.0) & (xmax == 0.0)
+    xmin = np.where(flat, -1.0, xmin)
+    xmax = np.where(flat, 1.0, xmax)
+    base = (xmax - xmin) / maxq
+    scale0 = base.astype(np.float32).astype(np.float64)
+    zero = np.full_like(base, (maxq + 1.0) / 2.0) if sym else np.rint(-xmin / scale0)
+    cand = np.zeros((steps, block.shape[0]))
+    errs = np.zeros((steps, block.shape[0]))
+    for i in range(steps):
+        sc = ((1.0 - i / grid) * base).astype(np.float32).astype(np.float64)
+        q = np.clip(np.rint(block / sc[:, None]) + zero[:, None], 0.0, maxq)
+        d = sc[:, None] * (q - zero[:, None]) - block
+        cand[i], errs[i] = sc, np.sum(d * d, axis=1)
+    best = np.argmin(errs, axis=0)                     # first minimum = earlier candidate on ties
+    rows = np.arange(block.shape[0])
+    hints = 0
+    if hint_scales is not None:
+        hs = np.asarray(hint_scales, np.float64)
+        near = np.abs(cand - hs[None, :]) <= 1e-5 * hs[None, :]
+        ok = near & (errs <= errs[best, rows][None, :] * (1.0 + rel_tol) + 1e-300)
+        alt = np.argmax(ok, axis=0)
+        take = ok.any(axis=0) & (alt != best)
+        hints = int(take.sum())
+        best = np.where(take, alt, best)
+    return cand[best, rows], zero, hints
+
+
 def quantize_column(w: np.ndarray, scale: np.ndarray, zero: np.ndarray, bits: int):
     """quant(.) for one column.  Returns integer codes, dequantised values and
     t = w / scale (the value whose rounding decides the code)."""
@@ -127,7 +168,8 @@ def quantize_column(w: np.ndarray, scale: np.ndarray, zero: np.ndarray, bits: in
 # ------------------------------- Algorithm 1, lines 5-13 with B = 1 (no batching)
 def quantize_layer(W, U, P, bits, group=0, sym=False, dead=None,
                    identity_quantizer=False, use_E=True, use_P=True,
-                   hint_codes=None, hint_zeros=None, tau=0.0):
+                   hint_codes=None, hint_zeros=None, tau=0.0,
+                   mse_grid=0, mse_steps=0, hint_scales=None, mse_rel_tol=0.0):
     """The column loop of Algorithm 1, one column at a time (Eq. 15 with the Cholesky
     rows of Step 3): for each j
 
@@ -155,9 +197,15 @@ def quantize_layer(W, U, P, bits, group=0, sym=False, dead=None,
     zeros = np.zeros((m, G))
     hints_used = 0
     zero_hints_used = 0
+    scale_hints_used = 0
 
     def params(block, g):
-        nonlocal zero_hints_used
+        nonlocal zero_hints_used, scale_hints_used
+        if mse_steps > 0:
+            hs = None if hint_scales is None else hint_scales[:, g]
+            s, z, nh = quant_params_mse(block, bits, sym, mse_grid, mse_steps, hs, mse_rel_tol)
+            scale_hints_used += nh
+            return s, z
         s, z = quant_params(block.min(axis=1), block.max(axis=1), bits, sym)
         if hint_zeros is not None and not sym:
             xmin = np.minimum(block.min(axis=1), 0.0)
@@ -200,7 +248,7 @@ def quantize_layer(W, U, P, bits, group=0, sym=False, dead=None,
             W[:, j:] += np.outer(v, P[j, j:])
         W[:, j] = w_hat
     return dict(codes=codes, scales=scales, zeros=zeros, What=What, t=T,
-                hints_used=hints_used, zero_hints_used=zero_hints_used)
+                hints_used=hints_used, zero_hints_used=zero_hints_used, scale_hints_used=scale_hints_used)
 
 
 # ----------------------------------- Algorithm 1 as printed, block size B (Step 4)

@@ -36,6 +36,10 @@ _SIGS = {
                                               _c.c_int64, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
                                               _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                               _c.c_void_p, _c.c_int]),
+    "gptaq_quantize_layer_ex": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p,
+                                           _c.c_int64, _c.c_void_p, _c.c_int, _c.c_int, _c.c_int, _c.c_int,
+                                           _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
+                                           _c.c_void_p, _c.c_int, _c.c_int, _c.c_int]),
     "gptaq_act_order": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p]),
     "gptaq_permute_hessian_workspace_bytes": (_c.c_size_t, [_c.c_int64]),
     "gptaq_permute_hessian": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p,
@@ -144,7 +148,7 @@ def gptaq_prepare(H: torch.Tensor, dXXT: torch.Tensor, damp: float, ws: torch.Te
 def gptaq_quantize_layer(W: torch.Tensor, U: torch.Tensor, P: torch.Tensor, bits: int, group: int, sym: bool,
                          blocksize: int, ws: torch.Tensor, dead: Optional[torch.Tensor] = None,
                          codes: Optional[torch.Tensor] = None, scales: Optional[torch.Tensor] = None,
-                         zeros: Optional[torch.Tensor] = None, terms: int = 3):
+                         zeros: Optional[torch.Tensor] = None, terms: int = 3, mse_grid: int = 0, mse_steps: int = 0):
     """In place: W -> dequantised quantised weights.  Returns (codes, scales, zeros).
     terms != 3 goes through gptaq_quantize_layer_terms (1: E term only = GPTQ, P may be None)."""
     _need(W, torch.float32, "W"); _need(U, torch.float32, "U")
@@ -164,7 +168,9 @@ def gptaq_quantize_layer(W: torch.Tensor, U: torch.Tensor, P: torch.Tensor, bits
         zeros = torch.empty((m, G), dtype=torch.float32, device=W.device)
     args = (_ptr(W), m, n, W.stride(0), _ptr(U), _ptr(P), U.stride(0), _ptr(dead), int(bits), int(group),
             int(bool(sym)), int(blocksize), _ptr(codes), _ptr(scales), _ptr(zeros), _ptr(ws), ws.numel(), _stream())
-    if terms == 3:
+    if mse_steps > 0:
+        _check(load().gptaq_quantize_layer_ex(*args, int(terms), int(mse_grid), int(mse_steps)), "gptaq_quantize_layer_ex")
+    elif terms == 3:
         _check(load().gptaq_quantize_layer(*args), "gptaq_quantize_layer")
     else:
         _check(load().gptaq_quantize_layer_terms(*args, int(terms)), "gptaq_quantize_layer_terms")
@@ -172,6 +178,7 @@ def gptaq_quantize_layer(W: torch.Tensor, U: torch.Tensor, P: torch.Tensor, bits
 
 
 gptaq_quantize_layer_terms = gptaq_quantize_layer
+gptaq_quantize_layer_ex = gptaq_quantize_layer
 
 
 def gptaq_profile_enable(mask: int) -> None:

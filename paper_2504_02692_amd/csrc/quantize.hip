@@ -47,9 +47,45 @@ __device__ __forceinline__ void grid_params(float xmin, float xmax, float maxq, 
   zero = sym ? (maxq + 1.f) * 0.5f : (float)rint(-lo / (double)scale);
 }
 
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Clip-range search (Section 5.1: "the weight clipping range is searched by minimizing mean squared
+// error"): candidates shrink the min-max range by p = 1 - i / grid, i = 0 .. steps - 1, about its
+// zero-point, i.e. scale_i = fp32(p * scale_0 exact) with the zero-point of the full range; the
+// candidate with the smallest sum of squared errors over the group wins, the earlier one on ties.
+struct ClipSearch {
+  double base;      // (hi - lo) / maxq, not yet rounded
+  float zero, maxq;
+  float best_err, best_scale;
+  __device__ __forceinline__ void begin(float xmin, float xmax, float mq, int sym) {
+    double lo = fmin((double)xmin, 0.0), hi = fmax((double)xmax, 0.0);
+    if (sym) { hi = fmax(fabs(lo), hi); lo = -hi; }
+    if (lo == 0.0 && hi == 0.0) { lo = -1.0; hi = 1.0; }
+    base = (hi - lo) / (double)mq;
+    maxq = mq;
+    zero = sym ? (mq + 1.f) * 0.5f : (float)rint(-lo / (double)(float)base);
+    best_err = __builtin_inff();
+    best_scale = (float)base;
+  }
+  __device__ __forceinline__ float scale_of(int i, int grid) const { return (float)((1.0 - (double)i / (double)grid) * base); }
+  __device__ __forceinline__ float err_of(float x, float sc, float isc) const {
+    const float q = fminf(fmaxf(rintf(x * isc) + zero, 0.f), maxq);
+    const float d = sc * (q - zero) - x;
+    return d * d;
+  }
+  __device__ __forceinline__ void offer(float err, float sc) {
+    if (err < best_err) { best_err = err; best_scale = sc; }
+  }
+};
+
 // One wavefront per row: range of the whole (original) row -> one (scale, zero) per row.
 __global__ __launch_bounds__(256) void row_params_kernel(const float* W, int64_t ldw, int m, int n, const uint8_t* dead,
-                                                         float maxq, int sym, float* scales, float* zeros) {
+                                                         float maxq, int sym, int mse_grid, int mse_steps, float* scales,
+                                                         float* zeros) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (row >= m) return;
   float mn = 0.f, mx = 0.f;
@@ -63,6 +99,22 @@ __global__ __launch_bounds__(256) void row_params_kernel(const float* W, int64_t
   mx = wave_max(mx);
   float sc, zr;
   grid_params(mn, mx, maxq, sym, sc, zr);
+  if (mse_steps > 0) {
+    ClipSearch cs;
+    cs.begin(mn, mx, maxq, sym);
+    for (int i = 0; i < mse_steps; ++i) {
+      const float si = cs.scale_of(i, mse_grid), isi = 1.f / si;
+      float e = 0.f;
+      for (int c = lane; c < n; c += 64) {
+        float v = W[(int64_t)row * ldw + c];
+        if (dead && dead[c]) v = 0.f;
+        e += cs.err_of(v, si, isi);
+      }
+      cs.offer(wave_sum(e), si);
+    }
+    sc = cs.best_scale;
+    zr = cs.zero;
+  }
   if (lane == 0) { scales[row] = sc; zeros[row] = zr; }
 }
 
@@ -71,6 +123,7 @@ struct QuantArgs {
   const float* U; const float* P; int64_t ldh;
   const uint8_t* dead;
   float maxq; int group, sym, G, terms;        // terms: bit 0 = E term, bit 1 = P term of Eq. 15
+  int mse_grid, mse_steps;                     // clip-range search (0 steps: plain min-max)
   float* scales; float* zeros; uint8_t* codes;
   uint16_t *Eh, *El, *Vh, *Vl;          // bf16 hi/lo of -E and V: row stride ldev, this block's 128 slots at evoff
   int64_t ldev; int evoff;
@@ -132,6 +185,17 @@ __global__ __launch_bounds__(64 * NW) void quant_block_kernel(QuantArgs a) {
       mn = wave_min(mn);
       mx = wave_max(mx);
       grid_params(mn, mx, a.maxq, a.sym, sc[r], zr[r]);
+      if (a.mse_steps > 0) {
+        ClipSearch cs;
+        cs.begin(mn, mx, a.maxq, a.sym);
+        for (int i = 0; i < a.mse_steps; ++i) {
+          const float si = cs.scale_of(i, a.mse_grid), isi = 1.f / si;
+          const float e = (in0 ? cs.err_of(w0[r], si, isi) : 0.f) + (in1 ? cs.err_of(w1[r], si, isi) : 0.f);
+          cs.offer(wave_sum(e), si);
+        }
+        sc[r] = cs.best_scale;
+        zr[r] = cs.zero;
+      }
       isc[r] = 1.f / sc[r];
       if (in0) { ms0[r] = sc[r]; mz0[r] = zr[r]; }
       if (in1) { ms1[r] = sc[r]; mz1[r] = zr[r]; }
@@ -305,9 +369,10 @@ extern "C" size_t gptaq_quantize_workspace_bytes(int64_t m, int64_t n) {
 static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
                                int64_t ldh, const uint8_t* dead, int bits, int group, int sym, int blocksize,
                                uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
-                               void* stream, int terms) {
+                               void* stream, int terms, int mse_grid, int mse_steps) {
   if (!W || !U || (!P && (terms & 2)) || !codes || !scales || !zeros || !ws) return GPTAQ_ENULL;
-  if (terms < 0 || terms > 3) return GPTAQ_EUNSUPPORTED;
+  if (terms < 0 || terms > 3 || mse_steps < 0 || (mse_steps > 0 && (mse_grid <= 0 || mse_steps > mse_grid)))
+    return GPTAQ_EUNSUPPORTED;
   if (m <= 0 || n <= 0 || ldw < n || ldh < n || m > (1 << 24) || n > (1 << 24)) return GPTAQ_EDIM;
   if (bits < 2 || bits > 8 || blocksize < 1 || blocksize > QB) return GPTAQ_EUNSUPPORTED;
   if (group > 0 && (n % group || blocksize % group || group > QB)) return GPTAQ_EUNSUPPORTED;
@@ -322,14 +387,14 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
   QuantArgs a;
   a.W = W; a.ldw = ldw; a.m = (int)m; a.n = (int)n;
   a.U = U; a.P = P; a.ldh = ldh; a.dead = dead;
-  a.maxq = (float)((1 << bits) - 1); a.group = group; a.sym = sym; a.terms = terms;
+  a.maxq = (float)((1 << bits) - 1); a.group = group; a.sym = sym; a.terms = terms; a.mse_grid = mse_grid; a.mse_steps = mse_steps;
   a.G = group > 0 ? (int)(n / group) : 1;
   a.scales = scales; a.zeros = zeros; a.codes = codes;
   a.Eh = buf[0]; a.El = buf[1]; a.Vh = buf[2]; a.Vl = buf[3]; a.ldev = KS;
 
   if (group <= 0) {
     hipLaunchKernelGGL(row_params_kernel, dim3((unsigned)((m + 3) / 4)), dim3(256), 0, s, W, ldw, (int)m, (int)n, dead,
-                       a.maxq, sym, scales, zeros);
+                       a.maxq, sym, mse_grid, mse_steps, scales, zeros);
     GPTAQ_LAUNCH_CHECK();
   }
   // Two-level lazy batching (a re-association of the sums of Eq. 18): a block's update reaches the rest
@@ -397,7 +462,7 @@ extern "C" int gptaq_quantize_layer(float* W, int64_t m, int64_t n, int64_t ldw,
                                     uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
                                     void* stream) {
   return quantize_layer_impl(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, blocksize, codes, scales, zeros, ws,
-                             ws_bytes, stream, 3);
+                             ws_bytes, stream, 3, 0, 0);
 }
 
 extern "C" int gptaq_quantize_layer_terms(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
@@ -405,5 +470,13 @@ extern "C" int gptaq_quantize_layer_terms(float* W, int64_t m, int64_t n, int64_
                                           int blocksize, uint8_t* codes, float* scales, float* zeros, void* ws,
                                           size_t ws_bytes, void* stream, int terms) {
   return quantize_layer_impl(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, blocksize, codes, scales, zeros, ws,
-                             ws_bytes, stream, terms);
+                             ws_bytes, stream, terms, 0, 0);
+}
+
+extern "C" int gptaq_quantize_layer_ex(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
+                                       int64_t ldh, const uint8_t* dead, int bits, int group, int sym, int blocksize,
+                                       uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
+                                       void* stream, int terms, int mse_grid, int mse_steps) {
+  return quantize_layer_impl(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, blocksize, codes, scales, zeros, ws,
+                             ws_bytes, stream, terms, mse_grid, mse_steps);
 }

@@ -41,28 +41,30 @@ def gpu_prepare(H, A, damp):
     return dead, info
 
 
-def gpu_quantize(W, U, P, bits, group, sym, blocksize, dead=None, terms=3):
+def gpu_quantize(W, U, P, bits, group, sym, blocksize, dead=None, terms=3, mse=(0, 0)):
     Wd = torch.from_numpy(np.asarray(W, np.float32).copy()).cuda()
     m, n = Wd.shape
     ws = B.workspace(B.gptaq_quantize_workspace_bytes(m, n))
-    codes, scales, zeros = B.gptaq_quantize_layer(Wd, U, P, bits, group, sym, blocksize, ws, dead=dead, terms=terms)
+    codes, scales, zeros = B.gptaq_quantize_layer(Wd, U, P, bits, group, sym, blocksize, ws, dead=dead, terms=terms,
+                                                  mse_grid=mse[0], mse_steps=mse[1])
     torch.cuda.synchronize()
     return dict(What=Wd.cpu().numpy(), codes=codes.cpu().numpy(), scales=scales.cpu().numpy(),
                 zeros=zeros.cpu().numpy())
 
 
-def check_against_oracle(W, U64, P64, got, bits, group, sym, dead=None, Xb=None, Xtb=None, label="", terms=3):
+def check_against_oracle(W, U64, P64, got, bits, group, sym, dead=None, Xb=None, Xtb=None, label="", terms=3, mse=(0, 0)):
     """The parity bar: raw code mismatches reported; with near-tie hints (|frac - 1/2| < TAU, at most
     1e-4 of the entries) every code, zero and scale must agree and the dequantised weights must
     match to 1e-4 relative; the layer output error must agree to 0.5 %."""
     W = np.asarray(W, np.float64)
     m, n = W.shape
-    kw = dict(use_E=bool(terms & 1), use_P=bool(terms & 2))
+    kw = dict(use_E=bool(terms & 1), use_P=bool(terms & 2), mse_grid=mse[0], mse_steps=mse[1])
     raw = O.quantize_layer(W, U64, P64, bits, group, sym, dead=dead, **kw)
     raw_mis = float((raw["codes"] != got["codes"]).mean())
     hinted = O.quantize_layer(W, U64, P64, bits, group, sym, dead=dead,
-                              hint_codes=got["codes"], hint_zeros=got["zeros"], tau=TAU, **kw)
-    nh = hinted["hints_used"] + hinted["zero_hints_used"]
+                              hint_codes=got["codes"], hint_zeros=got["zeros"], tau=TAU,
+                              hint_scales=got["scales"] if mse[1] else None, mse_rel_tol=1e-4, **kw)
+    nh = hinted["hints_used"] + hinted["zero_hints_used"] + hinted["scale_hints_used"]
     print(f"[{label}] raw code mismatch {raw_mis:.3e}; hints used {nh} of {m * n}")
     assert nh <= max(1, MAX_HINT_FRAC * m * n), f"{nh} near-tie hints"
     assert np.array_equal(hinted["zeros"], got["zeros"].astype(np.float64)), "zero points differ"

@@ -218,3 +218,15 @@ def test_act_order_path():
     PU.check_against_oracle(W[:, ref["perm"]], ref["U"], ref["P"], got, bits, group, True, label="act_order")
     assert np.array_equal(codes.cpu().numpy()[:, ref["perm"]], got["codes"])
     assert np.array_equal(What.cpu().numpy()[:, ref["perm"]], got["What"])
+
+
+@pytest.mark.parametrize("bits,group,sym", [(4, 128, False), (3, 64, True), (4, 0, False)])
+def test_clip_range_search(c1, bits, group, sym):
+    """Section 5.1's MSE-searched clipping range (grid 100, 80 steps) against the oracle."""
+    U32, P32 = c1["U"].astype(np.float32), c1["P"].astype(np.float32)
+    W = c1["W"][:300]
+    got = PU.gpu_quantize(W, dev(U32), dev(P32), bits, group, sym, 128, mse=(100, 80))
+    plain = PU.gpu_quantize(W, dev(U32), dev(P32), bits, group, sym, 128)
+    assert np.mean(got["scales"] < plain["scales"]) > 0.5            # the search does clip
+    PU.check_against_oracle(W, U32.astype(np.float64), P32.astype(np.float64), got, bits, group, sym,
+                            Xb=c1["Xb"], Xtb=c1["Xtb"], label=f"clip search W{bits} g{group} sym{int(sym)}", mse=(100, 80))

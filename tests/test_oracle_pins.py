@@ -375,3 +375,33 @@ def test_act_order_is_the_same_solve_on_permuted_inputs():
     ref = O.quantize_layer(W[:, perm], U, P, 3, 8)
     assert np.array_equal(out["codes"][:, perm], ref["codes"])
     assert np.allclose(out["What"][:, perm], ref["What"], rtol=0, atol=1e-12)
+
+
+def test_clip_search_properties():
+    """The clip-range search: never worse than min-max, exact grids keep p = 1, an outlier row gets
+    clipped, power-of-two scaling of the weights scales the result, and the argmin is a true argmin."""
+    rng = np.random.default_rng(1)
+    bits, grid, steps = 3, 100, 80
+    w = rng.standard_normal((40, 64)) * 0.02
+    w[0] = 0.3 * rng.uniform(-1, 1, 64); w[0, 7] = 1.0              # a dense body and one outlier
+    s0, z0 = O.quant_params(w.min(1), w.max(1), bits, False)
+    s1, z1, _ = O.quant_params_mse(w, bits, False, grid, steps)
+
+    def sse(s, z):
+        q = np.clip(np.rint(w / s[:, None]) + z[:, None], 0, 2 ** bits - 1)
+        return np.sum((s[:, None] * (q - z[:, None]) - w) ** 2, axis=1)
+
+    e0, e1 = sse(s0, z0), sse(s1, z1)
+    assert np.all(e1 <= e0 * (1 + 1e-12)) and np.array_equal(z0, z1)
+    assert s1[0] < 0.95 * s0[0] and e1[0] < e0[0]                # clipping the outlier pays for the body
+    for r in (0, 5, 11):                                              # brute force over the candidate list
+        cand = [np.float64(np.float32((1 - i / grid) * (max(w[r].max(), 0) - min(w[r].min(), 0)) / 7)) for i in range(steps)]
+        errs = [sse(np.full(40, c), z1)[r] for c in cand]
+        assert s1[r] == cand[int(np.argmin(errs))]
+    grid_row = (np.arange(8) - 3)[None, :] * 0.25                     # already on a 3-bit grid: error 0 at p = 1
+    sg, zg, _ = O.quant_params_mse(grid_row, bits, False, grid, steps)
+    assert sg[0] == np.float32(0.25) and zg[0] == 3
+    s4, _, _ = O.quant_params_mse(4.0 * w, bits, False, grid, steps)
+    assert np.array_equal(s4, 4.0 * s1)
+    out = O.quantize_layer(w[:, :32], np.eye(32), np.zeros((32, 32)), bits, 16, False, mse_grid=grid, mse_steps=steps)
+    assert np.array_equal(out["scales"][:, 0], O.quant_params_mse(w[:, :16], bits, False, grid, steps)[0])
