@@ -166,6 +166,24 @@ int gptaq_permute_columns_u8(const uint8_t* in, uint8_t* out, int64_t m, int64_t
                              int64_t ldout, const int32_t* perm, int inverse, void* stream);
 
 /* ---------------------------------------------------------------------------------------
+ * Neighbours of the solve in the whole-model procedure (Algorithm 2).
+ *
+ * gptaq_fake_quant_activations: the activation quantiser of Section 5.1 (per token, asymmetric,
+ *   clipping ratio `clip`, 0.9 in the paper), used to produce X when activations are quantised before
+ *   the weights.  For every token row: range = clip * [min(0, min x), max(0, max x)],
+ *   scale = range / (2^bits - 1), zero = rint(-clip*min/scale),
+ *   y = bf16(scale * (clamp(rint(x / scale) + zero) - zero)), arithmetic in fp32.
+ *   X, Y: (tokens x n) bf16, leading dimensions ldx, ldy; Y may equal X.
+ * gptaq_pack_codes: packed row r = little-endian bit stream of the row's codes, code j in bits
+ *   [j*bits, (j+1)*bits); gptaq_packed_words_per_row(n, bits) = ceil(n*bits/32) uint32 words per row.
+ */
+int gptaq_fake_quant_activations(const uint16_t* X, uint16_t* Y, int64_t tokens, int64_t n,
+                                 int64_t ldx, int64_t ldy, int bits, float clip, void* stream);
+int64_t gptaq_packed_words_per_row(int64_t n, int bits);
+int gptaq_pack_codes(const uint8_t* codes, int64_t m, int64_t n, int64_t ldc, int bits,
+                     uint32_t* packed, void* stream);
+
+/* ---------------------------------------------------------------------------------------
  * Measurement aid (not part of the method).  While enabled, the library brackets its kernels
  * with HIP events on the caller's stream, grouped by tag:
  *   0 accumulate MFMA GEMM (H and dXXT, one launch per pass)   1 accumulate split/transpose pass

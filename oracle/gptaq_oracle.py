@@ -292,6 +292,43 @@ def quantize_layer_blocked(W, U, P, bits, group=0, sym=False, blocksize=128, dea
     return dict(codes=codes, scales=scales, zeros=zeros, What=What)
 
 
+# ------------------------------------- neighbours of the solve in Algorithm 2 (Section 5.1)
+def fake_quant_activations(X_bits: np.ndarray, bits: int, clip: float = 0.9):
+    """Per-token asymmetric activation quantiser with a clipping ratio (Section 5.1), in fp32 like the
+    library (the paper fixes no precision; the decision is taken in the kernel's).  Returns the
+    dequantised activations as bf16 bit patterns and the pre-rounding values x/scale."""
+    x = (np.ascontiguousarray(X_bits, np.uint16).astype(np.uint32) << 16).view(np.float32)
+    maxq = np.float32(2 ** bits - 1)
+    mn = np.minimum(x.min(axis=1), np.float32(0)) * np.float32(clip)
+    mx = np.maximum(x.max(axis=1), np.float32(0)) * np.float32(clip)
+    flat = (mn == 0) & (mx == 0)
+    mn = np.where(flat, np.float32(-1), mn).astype(np.float32)
+    mx = np.where(flat, np.float32(1), mx).astype(np.float32)
+    scale = ((mx - mn) / maxq).astype(np.float32)
+    zero = np.rint(-mn / scale).astype(np.float32)
+    t = (x / scale[:, None]).astype(np.float32)
+    q = np.clip(np.rint(t) + zero[:, None], 0, maxq).astype(np.float32)
+    y = (scale[:, None] * (q - zero[:, None])).astype(np.float32)
+    u = y.view(np.uint32).astype(np.uint64)
+    yb = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)      # fp32 -> bf16, round to nearest even
+    return yb, t
+
+
+def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:
+    """Row-wise little-endian bit stream: code j occupies bits [j*bits, (j+1)*bits) of its row."""
+    m, n = codes.shape
+    words = (n * bits + 31) // 32
+    out = np.zeros((m, words), np.uint64)
+    for j in range(n):
+        bit = j * bits
+        w, sh = bit // 32, bit % 32
+        v = codes[:, j].astype(np.uint64) & ((1 << bits) - 1)
+        out[:, w] |= (v << sh) & 0xFFFFFFFF
+        if sh + bits > 32:
+            out[:, w + 1] |= v >> (32 - sh)
+    return out.astype(np.uint32)
+
+
 # ------------------------------------------------ act_order (Sections 5.2 and 5.3)
 def act_order_permutation(H: np.ndarray) -> np.ndarray:
     """Inputs in the order of decreasing Hessian diagonal (the act_order option the paper takes from

@@ -48,6 +48,10 @@ _SIGS = {
                                              _c.c_void_p, _c.c_int, _c.c_void_p]),
     "gptaq_permute_columns_u8": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_int64,
                                             _c.c_void_p, _c.c_int, _c.c_void_p]),
+    "gptaq_fake_quant_activations": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_int64,
+                                                _c.c_int, _c.c_float, _c.c_void_p]),
+    "gptaq_packed_words_per_row": (_c.c_int64, [_c.c_int64, _c.c_int]),
+    "gptaq_pack_codes": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "gptaq_profile_enable": (_c.c_int, [_c.c_int]),
     "gptaq_profile_read": (_c.c_int, [_c.c_int, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_double)]),
 }
@@ -234,3 +238,28 @@ def gptaq_permute_columns_u8(src: torch.Tensor, perm: torch.Tensor, inverse: boo
     if src.dtype != torch.uint8:
         raise GptaqError("gptaq_permute_columns_u8: expected uint8")
     return _permute_columns(load().gptaq_permute_columns_u8, "gptaq_permute_columns_u8", src, perm, inverse)
+
+
+def gptaq_fake_quant_activations(X: torch.Tensor, bits: int, clip: float = 0.9) -> torch.Tensor:
+    """Per-token asymmetric fake quantisation of bf16 activations (Section 5.1); returns a new tensor."""
+    _need(X, torch.bfloat16, "X")
+    Y = torch.empty_like(X, memory_format=torch.contiguous_format)
+    tokens, n = X.shape
+    _check(load().gptaq_fake_quant_activations(_ptr(X), _ptr(Y), tokens, n, X.stride(0), Y.stride(0), int(bits),
+                                               float(clip), _stream()), "gptaq_fake_quant_activations")
+    return Y
+
+
+def gptaq_packed_words_per_row(n: int, bits: int) -> int:
+    return load().gptaq_packed_words_per_row(n, bits)
+
+
+def gptaq_pack_codes(codes: torch.Tensor, bits: int) -> torch.Tensor:
+    """(m x n) uint8 codes -> (m x ceil(n*bits/32)) int32 words, code j of a row in bits [j*bits, (j+1)*bits)."""
+    if codes.dtype != torch.uint8 or codes.dim() != 2 or codes.stride(1) != 1 or not codes.is_cuda:
+        raise GptaqError("gptaq_pack_codes: expected a 2-D row-major uint8 CUDA tensor")
+    m, n = codes.shape
+    out = torch.empty((m, gptaq_packed_words_per_row(n, bits)), dtype=torch.int32, device=codes.device)
+    _check(load().gptaq_pack_codes(_ptr(codes), m, n, codes.stride(0), int(bits), _ptr(out), _stream()),
+           "gptaq_pack_codes")
+    return out

@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgptaq.so")
-SOURCES = ["status.hip", "gemm_bf16.hip", "accumulate.hip", "prepare.hip", "quantize.hip", "act_order.hip"]
+SOURCES = ["status.hip", "gemm_bf16.hip", "accumulate.hip", "prepare.hip", "quantize.hip", "act_order.hip", "upstream.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]
@@ -35,7 +35,7 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = True) -> str:
-    with concurrent.futures.ThreadPoolExecutor(max_workers=min(6, os.cpu_count() or 1)) as ex:
+    with concurrent.futures.ThreadPoolExecutor(max_workers=min(7, os.cpu_count() or 1)) as ex:
         objs = list(ex.map(_compile, SOURCES))
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     r = subprocess.run(cmd, capture_output=True, text=True)

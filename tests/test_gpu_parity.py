@@ -230,3 +230,20 @@ def test_clip_range_search(c1, bits, group, sym):
     assert np.mean(got["scales"] < plain["scales"]) > 0.5            # the search does clip
     PU.check_against_oracle(W, U32.astype(np.float64), P32.astype(np.float64), got, bits, group, sym,
                             Xb=c1["Xb"], Xtb=c1["Xtb"], label=f"clip search W{bits} g{group} sym{int(sym)}", mse=(100, 80))
+
+
+def test_activation_quantiser_and_packing_on_gpu():
+    from paper_2504_02692_amd import binding as B
+    Xb, _ = synth.make_activations(999, 520, 9, "actq", 3, 20.0)
+    for bits, clip in ((4, 0.9), (8, 1.0)):
+        Y = B.gptaq_fake_quant_activations(PU.to_dev_bf16(Xb), bits, clip)
+        got = Y.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+        ref, t = O.fake_quant_activations(Xb, bits, clip)
+        bad = got != ref
+        # same precision on both sides: every difference must be a rounding tie of x/scale
+        assert bad.mean() <= 1e-4 and np.all(np.abs(np.abs(t[bad] - np.floor(t[bad])) - 0.5) < 1e-3)
+    rng = np.random.default_rng(2)
+    for bits, n in ((2, 512), (3, 1000), (4, 130), (8, 77)):
+        c = rng.integers(0, 2 ** bits, (300, n)).astype(np.uint8)
+        p = B.gptaq_pack_codes(torch.from_numpy(c).cuda(), bits)
+        assert np.array_equal(p.cpu().numpy().view(np.uint32), O.pack_codes(c, bits))

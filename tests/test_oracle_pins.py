@@ -405,3 +405,29 @@ def test_clip_search_properties():
     assert np.array_equal(s4, 4.0 * s1)
     out = O.quantize_layer(w[:, :32], np.eye(32), np.zeros((32, 32)), bits, 16, False, mse_grid=grid, mse_steps=steps)
     assert np.array_equal(out["scales"][:, 0], O.quant_params_mse(w[:, :16], bits, False, grid, steps)[0])
+
+
+def test_activation_quantiser_and_packing():
+    Xb, _ = synth.make_activations(50, 96, 7, "act", 2, 20.0)
+    yb, t = O.fake_quant_activations(Xb, 4, 0.9)
+    x = synth.bf16_bits_to_f32(Xb).astype(np.float64)
+    y = synth.bf16_bits_to_f32(yb).astype(np.float64)
+    for r in (0, 17, 49):                                  # per token: 16 levels, clipped range, error bound
+        assert len(np.unique(y[r])) <= 16
+        lo, hi = 0.9 * min(x[r].min(), 0), 0.9 * max(x[r].max(), 0)
+        step = (hi - lo) / 15
+        assert y[r].min() >= lo - step and y[r].max() <= hi + step
+        inside = (x[r] > lo + step) & (x[r] < hi - step)
+        assert np.all(np.abs(y[r] - x[r])[inside] <= 0.5 * step * 1.02 + 2.0 ** -8 * np.abs(x[r][inside]))
+    same, _ = O.fake_quant_activations(Xb, 16, 1.0)        # 16 bits, no clipping: (nearly) the identity
+    assert np.max(np.abs(synth.bf16_bits_to_f32(same).astype(np.float64) - x)) <= np.abs(x).max() * 2.0 ** -8
+    # packing: hand-checked 3-bit stream and a round trip
+    assert O.pack_codes(np.array([[1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 3]], np.uint8), 3).tolist() == \
+        [[1 | 2 << 3 | 3 << 6 | 4 << 9 | 5 << 12 | 6 << 15 | 7 << 18 | 0 << 21 | 1 << 24 | 2 << 27 | (3 & 3) << 30, 3 >> 2]]
+    rng = np.random.default_rng(0)
+    for bits in (2, 3, 4, 5, 8):
+        c = rng.integers(0, 2 ** bits, (5, 77)).astype(np.uint8)
+        p = O.pack_codes(c, bits)
+        stream = np.unpackbits(p.view(np.uint8), axis=1, bitorder="little")[:, :77 * bits]
+        back = (stream.reshape(5, 77, bits) * (1 << np.arange(bits))).sum(axis=2)
+        assert np.array_equal(back, c)
