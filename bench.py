@@ -36,7 +36,7 @@ def cpu_baseline(wl, budget_s: float = 20.0):
         cores = max(i["num_threads"] for i in threadpoolctl.threadpool_info()) if threadpoolctl.threadpool_info() else cores
     except Exception:
         pass
-    n_s, tok_s, m_s = 4096, 16384, 128
+    n_s, tok_s, m_s = 4096, 32768, 512
     Xb, Xtb = synth.make_activations(tok_s, n_s, wl.seed, "cpu", wl.n_outliers, wl.outlier_scale, wl.noise,
                                      empirical_sigma=False)
     W = synth.make_weights(m_s, n_s, wl.seed, "cpu")
