@@ -111,7 +111,7 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
                          oX, oHi, oLo, np);
     }
     GPTAQ_LAUNCH_CHECK();
-    GemmBatch b;
+    GemmBatch b{};
     b.nprob = 2;
     b.tile = tile;
     GemmProblem& a = b.p[0];

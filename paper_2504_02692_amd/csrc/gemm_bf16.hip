@@ -12,11 +12,14 @@
 // ring of LDS stages, ahead of the multiply; fragment reads are ds_read_b128 on an
 // XOR-swizzled layout and run one k-step ahead of the MFMAs.
 //
-// The traffic from L2 into LDS is what bounds this kernel (a CU sustains only about 13 bytes per
-// clock of L2 reads), so operand tiles are shared between cross products: per k-tile a term
-// loads its NL left and NR right operand tiles once and multiplies all listed (left, right)
-// pairs from them - dXXT's hi and lo halves share the X tile, and the three products of a
-// split term need four tiles instead of six.
+// Feeding the operands is what bounds this kernel: a CU takes at most ~22 bytes per clock from its L2
+// into LDS (measured; less when lines come from HBM), which is about what one 256 x 256 product per
+// two operand tiles needs at full MFMA rate.  So operand tiles are shared between cross products: per
+// k-tile a term loads its NL left and NR right operand tiles once and multiplies all listed
+// (left, right) pairs from them - dXXT's hi and lo halves share the X tile, and the three products of
+// a split term need four tiles instead of six.  The loads of a k-tile are issued one by one between
+// the MFMAs of an earlier k-tile, and the barriers carry no memory fence, so that loads stay in
+// flight across them (see wg_barrier).
 #include "common.h"
 
 namespace gptaq {
@@ -29,10 +32,22 @@ template <> struct KindTraits<2> { static constexpr int NL = 2, NR = 2, NPAIR = 
 __device__ __forceinline__ constexpr int pair_l(int kind, int p) { return kind == 0 ? 0 : kind == 1 ? p : (p == 2 ? 1 : 0); }
 __device__ __forceinline__ constexpr int pair_r(int kind, int p) { return kind == 2 ? (p == 1 ? 1 : 0) : 0; }
 
+// Workgroup barrier without the memory fence of __syncthreads(): that fence makes the compiler drain
+// every outstanding global -> LDS load (vmcnt(0)) at each barrier, which would cut the load pipeline
+// down to one k-tile.  The waits a barrier needs here are written out by hand before it.
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
 template <int N> __device__ __forceinline__ void wait_vm_and_lds() {
   // vmcnt <= N (vmcnt is split over bits 3:0 and 15:14), lgkmcnt == 0, expcnt untouched
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));
 }
+
+constexpr int kLds256 = 3 * 3 * 256 * 64;    // largest ring: 3 stages x 3 operand tiles (2 x 4 and 4 x 2 are smaller)
+constexpr int kLds128 = 3 * 3 * 128 * 64;
 
 template <int BT, int KIND>
 __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* smem, int m0, int n0, int klo, int nk,
@@ -58,26 +73,39 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   const int ld_line = lane >> 4;
   const int ld_row = ld_line * 4 + ((lane & 15) >> 2);
   const int ld_chunk = (lane & 3) ^ ld_line;
-  auto issue_loads = [&](int it) {
-    const int t = it / nk;
+  // The TL wave loads of a k-tile are issued one at a time, spread between the MFMAs of the k-tile
+  // before it (a wave stalls ~50 clocks per 1 KB load it hands to the memory pipeline; in a burst that
+  // is time the matrix unit idles).  Past the last k-tile the last one is fetched again into a stage
+  // nobody reads, which keeps the loop and its wait counts free of special cases.
+  struct TileSrc {
+    const uint16_t* l[NL];
+    const uint16_t* r[NR];
+    int64_t lstep, rstep;
+    unsigned char* st;
+  };
+  auto tile_src = [&](int it) {
+    it = min(it, total_it - 1);
+    const int t = it >= nk ? 1 : 0;
     const int64_t kt = (klo / kGemmBK) + (it - t * nk);
     const GemmTerm& tm = P.term[t];
-    unsigned char* st = smem + (it % NSTAGE) * STAGE_BYTES;
+    TileSrc c;
+    const int64_t lo = (int64_t)(m0 + wave * LPW * 16 + ld_row) * tm.ldl + kt * tm.ktl + ld_chunk * 8;
+    const int64_t ro = (int64_t)(n0 + wave * LPW * 16 + ld_row) * tm.ldr + kt * tm.ktr + ld_chunk * 8;
 #pragma unroll
-    for (int j = 0; j < LPW; ++j) {
-      const int r = (wave * LPW + j) * 16 + ld_row;
-      const int64_t lo = (int64_t)(m0 + r) * tm.ldl + kt * tm.ktl + ld_chunk * 8;
-      const int64_t ro = (int64_t)(n0 + r) * tm.ldr + kt * tm.ktr + ld_chunk * 8;
-      unsigned char* d = st + (wave * LPW + j) * 1024;
+    for (int o = 0; o < NL; ++o) c.l[o] = tm.L[o] + lo;
 #pragma unroll
-      for (int o = 0; o < NL; ++o)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tm.L[o] + lo),
-                                         (__attribute__((address_space(3))) void*)(d + o * OPB), 16, 0, 0);
-#pragma unroll
-      for (int o = 0; o < NR; ++o)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tm.R[o] + ro),
-                                         (__attribute__((address_space(3))) void*)(d + (NL + o) * OPB), 16, 0, 0);
-    }
+    for (int o = 0; o < NR; ++o) c.r[o] = tm.R[o] + ro;
+    c.lstep = 16 * tm.ldl;
+    c.rstep = 16 * tm.ldr;
+    c.st = smem + (it % NSTAGE) * STAGE_BYTES + wave * LPW * 1024;
+    return c;
+  };
+  // q-th load of the tile: q = j * NOP + o (16-row slab j of operand o)
+  auto load_one = [&](const TileSrc& c, int q) {
+    const int j = q / NOP, o = q % NOP;
+    const uint16_t* src = o < NL ? c.l[o < NL ? o : 0] + j * c.lstep : c.r[o < NL ? 0 : o - NL] + j * c.rstep;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                     (__attribute__((address_space(3))) void*)(c.st + j * 1024 + o * OPB), 16, 0, 0);
   };
 
   // fragment reads: lane -> row (lane & 31) of a 32-row block, chunk 2 kk + (lane >> 5)
@@ -99,47 +127,57 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
       for (int i = 0; i < FR; ++i)
         bfr[set][o][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + o * OPB + i * 8 * 256 + off));
   };
-  auto mfma_step = [&](int set) {
+  // the MFMAs of one k-step, with loads q0 .. q1-1 of tile `c` spread evenly between them
+  constexpr int NM = T::NPAIR * FR * FR;
+  static_assert(TL <= NM, "at most one load per MFMA");
+  auto mfma_step = [&](int set, const TileSrc& c, int q0, int q1) {
 #pragma unroll
     for (int p = 0; p < T::NPAIR; ++p)
 #pragma unroll
       for (int i = 0; i < FR; ++i)
 #pragma unroll
-        for (int j = 0; j < FR; ++j)
+        for (int j = 0; j < FR; ++j) {
+          const int m = (p * FR + i) * FR + j, nq = q1 - q0;
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][pair_l(KIND, p)][i], bfr[set][pair_r(KIND, p)][j],
                                                               acc[i][j], 0, 0, 0);
+          if ((m + 1) * nq / NM > m * nq / NM) {
+            __builtin_amdgcn_sched_barrier(0);
+            load_one(c, q0 + m * nq / NM);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+        }
   };
-  // wait until at most `tiles` k-tiles of this wave's own loads are still in flight (loads return in
-  // order) and all of its LDS reads have returned
-  auto wait_tiles = [&](int tiles) {
-    if (NSTAGE >= 4 && tiles >= 2) wait_vm_and_lds<2 * TL>();
-    else if (NSTAGE >= 3 && tiles >= 1) wait_vm_and_lds<TL>();
-    else wait_vm_and_lds<0>();
-  };
-
   // Pipeline: k-tile `it` is multiplied from stage it % NSTAGE while the next NSTAGE - 1 tiles are in
-  // flight or landed.  One barrier per k-tile: it publishes tile it+1 (every wave waited for its own
-  // loads) and retires stage (it - 1) % NSTAGE, which the loads issued at the top of the next
-  // iteration overwrite.
+  // flight or landed; the loads of tile it + NSTAGE - 1 go out during k-tile `it`, the first H of them
+  // before its barrier.  One barrier per k-tile: it publishes tile it+1 (every wave has waited for its own
+  // loads of it: they return in order, so "at most so many outstanding" says which have landed) and
+  // retires stage (it - 1) % NSTAGE, which the loads of the next k-tile overwrite.
+  constexpr int H = NSTAGE >= 3 ? TL / 2 : TL;             // loads issued before the barrier
+  constexpr int PENDING = (NSTAGE - 3 > 0 ? NSTAGE - 3 : 0) * TL + (NSTAGE >= 3 ? H : 0);
   if (total_it <= 0) return;
-  for (int t = 0; t < NSTAGE - 1 && t < total_it; ++t) issue_loads(t);
-  wait_tiles(min(total_it, NSTAGE - 1) - 1);
-  __syncthreads();
+  for (int t = 0; t < NSTAGE - 1; ++t) {
+    const TileSrc c = tile_src(t);
+#pragma unroll
+    for (int q = 0; q < TL; ++q) load_one(c, q);
+  }
+  wait_vm_and_lds<(NSTAGE - 2) * TL>();
+  wg_barrier();
   read_frags(0, 0, 0);
   for (int it = 0; it < total_it; ++it) {
     const int stage = it % NSTAGE;
-    if (it + NSTAGE - 1 < total_it) issue_loads(it + NSTAGE - 1);
+    const TileSrc c = tile_src(it + NSTAGE - 1);
     __builtin_amdgcn_sched_barrier(0);
     read_frags(stage, 1, 1);
-    mfma_step(0);
+    mfma_step(0, c, 0, H);
     __builtin_amdgcn_sched_barrier(0);
-    wait_tiles(min(total_it - 1, it + NSTAGE - 1) - (it + 1));
-    __syncthreads();
+    wait_vm_and_lds<PENDING>();
+    wg_barrier();
     __builtin_amdgcn_sched_barrier(0);
     if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
-    mfma_step(1);
+    mfma_step(1, c, H, TL);
     __builtin_amdgcn_sched_barrier(0);
   }
+  wait_vm_and_lds<0>();   // the surplus loads past the last k-tile
 }
 
 template <int BT>
@@ -161,14 +199,32 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
   }
   const GemmProblem& P = b.p[pi];
   int tm, tn;
+  // Tiles are numbered in groups of GROUP tile rows, column by column inside a group, so the workgroups
+  // an XCD runs side by side form a GROUP x 8 patch that shares GROUP left and 8 right operand tiles.
+  constexpr int GROUP = 4;
   if (P.tile_mode == 2) {
-    // only the tiles with tn >= tm exist, numbered row by row
-    tm = 0;
-    int rowlen = P.tiles_n;
-    while (id >= rowlen) { id -= rowlen; --rowlen; ++tm; }
-    tn = tm + id;
+    // only the tiles with tn >= tm exist: a group holds a small triangle, then full columns
+    const int T = P.tiles_n;
+    int first = 0, gs, tri;
+    for (;;) {
+      gs = min(GROUP, T - first);
+      tri = gs * (gs + 1) / 2;
+      const int cnt = tri + gs * (T - first - gs);
+      if (id < cnt) break;
+      id -= cnt;
+      first += gs;
+    }
+    if (id < tri) {
+      int c = 0;
+      while (id > c) { id -= c + 1; ++c; }
+      tm = first + id;
+      tn = first + c;
+    } else {
+      id -= tri;
+      tn = first + gs + id / gs;
+      tm = first + id % gs;
+    }
   } else {
-    constexpr int GROUP = 4;
     const int width = GROUP * P.tiles_n;
     const int g = id / width, first = g * GROUP;
     const int gsz = min(P.tiles_m - first, GROUP);
@@ -241,9 +297,6 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
 }
 
 static bool g_attr_set = false;
-constexpr int kLds256 = 3 * 3 * 256 * 64;     // largest ring: 3 stages x 3 operand tiles (2 x 4 tiles is smaller)
-constexpr int kLds128 = 3 * 3 * 128 * 64;
-
 hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
   GemmBatch bb = b;
   int total = 0;

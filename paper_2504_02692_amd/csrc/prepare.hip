@@ -675,7 +675,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   GPTAQ_LAUNCH_CHECK();
 
   const int tile = gemm_tile_for(n, n);
-  GemmBatch b;
+  GemmBatch b{};
   b.nprob = 1; b.tile = tile;
   GemmProblem& g = b.p[0];
   // O = triu(dXXT U^T, 1): O[i][a] = sum_{b >= a} dXXT[i][b] U[a][b]

@@ -413,7 +413,7 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
                          R4[3], ldr);
     }
     GPTAQ_LAUNCH_CHECK();
-    GemmBatch b;
+    GemmBatch b{};
     b.nprob = 1; b.tile = tile;
     GemmProblem& g = b.p[0];
     g.C = W + c0; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = K;
