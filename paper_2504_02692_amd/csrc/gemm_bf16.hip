@@ -75,20 +75,22 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   const int ld_chunk = (lane & 3) ^ ld_line;
   // The TL wave loads of a k-tile are issued one at a time, spread between the MFMAs of the k-tile
   // before it (a wave stalls ~50 clocks per 1 KB load it hands to the memory pipeline; in a burst that
-  // is time the matrix unit idles).  Past the last k-tile the last one is fetched again into a stage
-  // nobody reads, which keeps the loop and its wait counts free of special cases.
+  // is time the matrix unit idles).  Past the last k-tile the last one is fetched again into the stage
+  // that has just been retired, which keeps the loop and its wait counts free of special cases.
+  // The tiles are loaded in order, so the source is a cursor: per-lane pointers to the next tile, moved on
+  // by one k-tile after each (recomputed only where the second term starts).
   struct TileSrc {
     const uint16_t* l[NL];
     const uint16_t* r[NR];
-    int64_t lstep, rstep;
-    unsigned char* st;
+    int64_t lstep, rstep;     // 16 rows, in elements
+    int64_t lkt, rkt;         // one k-tile, in elements
+    unsigned char* st;        // this wave's part of the stage the tile goes to
+    int seq;                  // number of the tile in load order (not clamped)
   };
-  auto tile_src = [&](int it) {
-    it = min(it, total_it - 1);
-    const int t = it >= nk ? 1 : 0;
-    const int64_t kt = (klo / kGemmBK) + (it - t * nk);
+  const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+  auto seek_term = [&](TileSrc& c, int t) {
     const GemmTerm& tm = P.term[t];
-    TileSrc c;
+    const int64_t kt = klo / kGemmBK;
     const int64_t lo = (int64_t)(m0 + wave * LPW * 16 + ld_row) * tm.ldl + kt * tm.ktl + ld_chunk * 8;
     const int64_t ro = (int64_t)(n0 + wave * LPW * 16 + ld_row) * tm.ldr + kt * tm.ktr + ld_chunk * 8;
 #pragma unroll
@@ -97,8 +99,22 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
     for (int o = 0; o < NR; ++o) c.r[o] = tm.R[o] + ro;
     c.lstep = 16 * tm.ldl;
     c.rstep = 16 * tm.ldr;
-    c.st = smem + (it % NSTAGE) * STAGE_BYTES + wave * LPW * 1024;
-    return c;
+    c.lkt = tm.ktl;
+    c.rkt = tm.ktr;
+  };
+  auto next_tile = [&](TileSrc& c) {
+    ++c.seq;
+    c.st = smem + (c.seq % NSTAGE) * STAGE_BYTES + wave_s * LPW * 1024;
+    if (c.seq < total_it) {
+      if (c.seq == nk) {
+        seek_term(c, 1);
+      } else {
+#pragma unroll
+        for (int o = 0; o < NL; ++o) c.l[o] += c.lkt;
+#pragma unroll
+        for (int o = 0; o < NR; ++o) c.r[o] += c.rkt;
+      }
+    }
   };
   // q-th load of the tile: q = j * NOP + o (16-row slab j of operand o)
   auto load_one = [&](const TileSrc& c, int q) {
@@ -155,17 +171,20 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   constexpr int H = NSTAGE >= 3 ? TL / 2 : TL;             // loads issued before the barrier
   constexpr int PENDING = (NSTAGE - 3 > 0 ? NSTAGE - 3 : 0) * TL + (NSTAGE >= 3 ? H : 0);
   if (total_it <= 0) return;
+  TileSrc c;
+  seek_term(c, 0);
+  c.seq = 0;
+  c.st = smem + wave_s * LPW * 1024;
   for (int t = 0; t < NSTAGE - 1; ++t) {
-    const TileSrc c = tile_src(t);
 #pragma unroll
     for (int q = 0; q < TL; ++q) load_one(c, q);
+    next_tile(c);
   }
   wait_vm_and_lds<(NSTAGE - 2) * TL>();
   wg_barrier();
   read_frags(0, 0, 0);
   for (int it = 0; it < total_it; ++it) {
     const int stage = it % NSTAGE;
-    const TileSrc c = tile_src(it + NSTAGE - 1);
     __builtin_amdgcn_sched_barrier(0);
     read_frags(stage, 1, 1);
     mfma_step(0, c, 0, H);
@@ -175,6 +194,7 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
     __builtin_amdgcn_sched_barrier(0);
     if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
     mfma_step(1, c, H, TL);
+    next_tile(c);
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vm_and_lds<0>();   // the surplus loads past the last k-tile
