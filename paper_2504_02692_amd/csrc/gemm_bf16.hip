@@ -163,13 +163,14 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
           }
         }
   };
-  // Pipeline: k-tile `it` is multiplied from stage it % NSTAGE while the next NSTAGE - 1 tiles are in
-  // flight or landed; the loads of tile it + NSTAGE - 1 go out during k-tile `it`, the first H of them
-  // before its barrier.  One barrier per k-tile: it publishes tile it+1 (every wave has waited for its own
-  // loads of it: they return in order, so "at most so many outstanding" says which have landed) and
-  // retires stage (it - 1) % NSTAGE, which the loads of the next k-tile overwrite.
-  constexpr int H = NSTAGE >= 3 ? TL / 2 : TL;             // loads issued before the barrier
-  constexpr int PENDING = (NSTAGE - 3 > 0 ? NSTAGE - 3 : 0) * TL + (NSTAGE >= 3 ? H : 0);
+  // Pipeline: k-tile `it` is multiplied from stage it % NSTAGE.  One barrier per k-tile, in the middle of
+  // its MFMAs: it publishes tile it+1 (every wave has waited for its own loads of it: they return in
+  // order, so "at most so many outstanding" says which have landed) and retires stage it % NSTAGE, whose
+  // last fragments were read before it.  Tile it + NSTAGE goes into that stage: its first HF loads are
+  // issued behind the barrier, the rest before the next one, so each has at least a whole k-tile of
+  // MFMA time to arrive (half of one with two stages).
+  constexpr int HF = NSTAGE >= 3 ? TL / 2 : TL;
+  constexpr int PENDING = (NSTAGE - 2) * TL;               // loads of later tiles issued by the barrier
   if (total_it <= 0) return;
   TileSrc c;
   seek_term(c, 0);
@@ -180,21 +181,23 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
     for (int q = 0; q < TL; ++q) load_one(c, q);
     next_tile(c);
   }
-  wait_vm_and_lds<(NSTAGE - 2) * TL>();
+#pragma unroll
+  for (int q = 0; q < HF; ++q) load_one(c, q);
+  wait_vm_and_lds<PENDING + HF>();
   wg_barrier();
   read_frags(0, 0, 0);
   for (int it = 0; it < total_it; ++it) {
     const int stage = it % NSTAGE;
     __builtin_amdgcn_sched_barrier(0);
     read_frags(stage, 1, 1);
-    mfma_step(0, c, 0, H);
+    mfma_step(0, c, HF, TL);
     __builtin_amdgcn_sched_barrier(0);
     wait_vm_and_lds<PENDING>();
     wg_barrier();
     __builtin_amdgcn_sched_barrier(0);
-    if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
-    mfma_step(1, c, H, TL);
     next_tile(c);
+    if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
+    mfma_step(1, c, 0, HF);
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vm_and_lds<0>();   // the surplus loads past the last k-tile
