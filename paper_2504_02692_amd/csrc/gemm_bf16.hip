@@ -105,15 +105,14 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   auto next_tile = [&](TileSrc& c) {
     ++c.seq;
     c.st = smem + (c.seq % NSTAGE) * STAGE_BYTES + wave_s * LPW * 1024;
-    if (c.seq < total_it) {
-      if (c.seq == nk) {
-        seek_term(c, 1);
-      } else {
+    if (c.seq == nk && c.seq < total_it) {
+      seek_term(c, 1);
+    } else {
+      const int64_t ls = c.seq < total_it ? c.lkt : 0, rs = c.seq < total_it ? c.rkt : 0;
 #pragma unroll
-        for (int o = 0; o < NL; ++o) c.l[o] += c.lkt;
+      for (int o = 0; o < NL; ++o) c.l[o] += ls;
 #pragma unroll
-        for (int o = 0; o < NR; ++o) c.r[o] += c.rkt;
-      }
+      for (int o = 0; o < NR; ++o) c.r[o] += rs;
     }
   };
   // q-th load of the tile: q = j * NOP + o (16-row slab j of operand o)
@@ -128,25 +127,30 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   const int rl = lane & 31, half = lane >> 5;
   const int fr_line = rl >> 2, fr_x = fr_line & 3, fr_hi = (rl & 3) << 2;
   bf16x8 af[2][NL][FR], bfr[2][NR][FR];
-  auto read_frags = [&](int stage, int kk, int set) {
-    const unsigned char* lb = smem + stage * STAGE_BYTES + (wm * (WT / 4) + fr_line) * 256;
-    const unsigned char* rb = smem + stage * STAGE_BYTES + NL * OPB + (wn * (WT / 4) + fr_line) * 256;
+  constexpr int NFRAG = NOP * FR;      // fragments per k-step: NL * FR left, then NR * FR right
+  struct FragSrc { const unsigned char* lb; const unsigned char* rb; };
+  auto frag_src = [&](int stage, int kk) {
     const int off = (fr_hi | ((kk * 2 + half) ^ fr_x)) << 4;
-#pragma unroll
-    for (int o = 0; o < NL; ++o)
-#pragma unroll
-      for (int i = 0; i < FR; ++i)
-        af[set][o][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(lb + o * OPB + i * 8 * 256 + off));
-#pragma unroll
-    for (int o = 0; o < NR; ++o)
-#pragma unroll
-      for (int i = 0; i < FR; ++i)
-        bfr[set][o][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(rb + o * OPB + i * 8 * 256 + off));
+    FragSrc f;
+    f.lb = smem + stage * STAGE_BYTES + (wm * (WT / 4) + fr_line) * 256 + off;
+    f.rb = smem + stage * STAGE_BYTES + NL * OPB + (wn * (WT / 4) + fr_line) * 256 + off;
+    return f;
   };
-  // the MFMAs of one k-step, with loads q0 .. q1-1 of tile `c` spread evenly between them
+  auto read_one = [&](const FragSrc& f, int set, int r) {
+    if (r < NL * FR) {
+      const int o = r / FR, i = r % FR;
+      af[set][o][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(f.lb + o * OPB + i * 8 * 256));
+    } else {
+      const int o = (r - NL * FR) / FR, i = (r - NL * FR) % FR;
+      bfr[set][o][i] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(f.rb + o * OPB + i * 8 * 256));
+    }
+  };
+  // The MFMAs of one k-step on fragment set `set`.  Between them, one at a time (so that each is issued
+  // in the shadow of a running MFMA instead of holding up the next one): the fragment reads of the other
+  // set for the following k-step, and loads q0 .. q1-1 of tile `c`.
   constexpr int NM = T::NPAIR * FR * FR;
-  static_assert(TL <= NM, "at most one load per MFMA");
-  auto mfma_step = [&](int set, const TileSrc& c, int q0, int q1) {
+  static_assert(TL <= NM && NFRAG <= NM, "at most one load and one fragment read per MFMA");
+  auto mfma_step = [&](int set, const FragSrc& f, const TileSrc& c, int q0, int q1) {
 #pragma unroll
     for (int p = 0; p < T::NPAIR; ++p)
 #pragma unroll
@@ -156,11 +160,10 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
           const int m = (p * FR + i) * FR + j, nq = q1 - q0;
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[set][pair_l(KIND, p)][i], bfr[set][pair_r(KIND, p)][j],
                                                               acc[i][j], 0, 0, 0);
-          if ((m + 1) * nq / NM > m * nq / NM) {
-            __builtin_amdgcn_sched_barrier(0);
-            load_one(c, q0 + m * nq / NM);
-            __builtin_amdgcn_sched_barrier(0);
-          }
+          __builtin_amdgcn_sched_barrier(0);
+          if (m < NFRAG) read_one(f, set ^ 1, m);
+          if ((m + 1) * nq / NM > m * nq / NM) load_one(c, q0 + m * nq / NM);
+          __builtin_amdgcn_sched_barrier(0);
         }
   };
   // Pipeline: k-tile `it` is multiplied from stage it % NSTAGE.  One barrier per k-tile, in the middle of
@@ -185,19 +188,22 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   for (int q = 0; q < HF; ++q) load_one(c, q);
   wait_vm_and_lds<PENDING + HF>();
   wg_barrier();
-  read_frags(0, 0, 0);
+  {
+    const FragSrc f0 = frag_src(0, 0);
+#pragma unroll
+    for (int r = 0; r < NFRAG; ++r) read_one(f0, 0, r);
+  }
   for (int it = 0; it < total_it; ++it) {
     const int stage = it % NSTAGE;
     __builtin_amdgcn_sched_barrier(0);
-    read_frags(stage, 1, 1);
-    mfma_step(0, c, HF, TL);
+    mfma_step(0, frag_src(stage, 1), c, HF, TL);
     __builtin_amdgcn_sched_barrier(0);
     wait_vm_and_lds<PENDING>();
     wg_barrier();
     __builtin_amdgcn_sched_barrier(0);
     next_tile(c);
-    if (it + 1 < total_it) read_frags((it + 1) % NSTAGE, 0, 0);
-    mfma_step(1, c, 0, HF);
+    // (behind the last k-tile these fragment reads fetch a stale stage and nobody uses them)
+    mfma_step(1, frag_src((it + 1) % NSTAGE, 0), c, 0, HF);
     __builtin_amdgcn_sched_barrier(0);
   }
   wait_vm_and_lds<0>();   // the surplus loads past the last k-tile
