@@ -125,130 +125,88 @@ __device__ __forceinline__ double fast_rcp(double x) {
   r = fma(fma(-x, r, 1.0), r, r);
   return r;
 }
-// sum over the four neighbouring lanes of a quad (DPP quad permutes, no LDS traffic)
-template <int CTRL> __device__ __forceinline__ double dpp_quad(double v) {
-  const long long b = __builtin_bit_cast(long long, v);
-  int lo = (int)b, hi = (int)(b >> 32);
-  lo = __builtin_amdgcn_update_dpp(lo, lo, CTRL, 0xf, 0xf, false);
-  hi = __builtin_amdgcn_update_dpp(hi, hi, CTRL, 0xf, 0xf, false);
-  return __builtin_bit_cast(double, ((long long)hi << 32) | (unsigned int)lo);
-}
-__device__ __forceinline__ double quad_sum(double v) {
-  v += dpp_quad<0xB1>(v);      // lanes 1,0,3,2
-  v += dpp_quad<0x4E>(v);      // lanes 2,3,0,1
-  return v;
+// ------------------------------------------------------------------------------- diag
+// One wavefront: reverse Cholesky of the 64 x 64 diagonal block and the inverse of its factor, with no
+// barrier inside the 64 sequential steps.  Lane r keeps row r of the symmetric block S in registers (both
+// triangles).  At step j the pivot row is lane j's registers: the entry S[c][j] a lane needs to downdate
+// its column c is S[j][c].  Lane j stores its row to LDS and every lane reads it back (same address in
+// all lanes: a broadcast; LDS operations of one wavefront complete in order, so no barrier is needed),
+// then downdates its whole row with the unscaled pivot column; column j is final when step j starts and
+// is never touched again, columns are scaled at the end.  The inverse W of the factor is then built
+// column-per-lane, row by row from the bottom, from the same kind of broadcast of row i of the factor.
+// LDS written by some lanes of the wavefront becomes readable by the others: to the compiler the write
+// and the reads are ordered by a wavefront-scope fence (without it the unsynchronised exchange would be
+// a data race, and it does move the reads ahead of the write); to the hardware they already are.
+__device__ __forceinline__ void wave_publish() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// ------------------------------------------------------------------------------- diag
-// One workgroup: reverse Cholesky of the 64 x 64 diagonal block and the inverse of its factor.
-// Thread (ti, tl) keeps the 16 entries S[ti + 16p][tl + 16q] in registers.  At step j the pivot
-// column is published through LDS (two alternating buffers, one barrier per step) and every thread
-// applies the rank-1 downdate with the unscaled column (column j is final when step j starts and
-// is never touched again); columns are scaled at the end.
-__global__ __launch_bounds__(256) void diag_kernel(Sweep a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  double* S = reinterpret_cast<double*>(smem_raw);        // S[r*LDT + c]
-  double* Wi = S + NB * LDT;
-  __shared__ double col[2][NB];
-  const int tid = threadIdx.x;
+__global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
+  __shared__ double T[NB * LDT];
+  __shared__ __attribute__((aligned(16))) double row[2][NB];
+  __shared__ double dsh[NB];
+  const int lane = threadIdx.x;
   const int k0 = a.kb * NB, w = min(NB, a.n - k0);
-  const int ti = tid >> 4, tl = tid & 15;
-  double s[4][4];
+  // stage the stored (upper) triangle, T[c][r] = F[k0+c][k0+r] for c <= r, then mirror it into rows
+#pragma unroll 8
+  for (int c = 0; c < NB; ++c)
+    T[c * LDT + lane] = (c <= lane && lane < w) ? a.F[(int64_t)(k0 + c) * a.ldf + k0 + lane] : 0.0;
+  __syncthreads();
+  double s[NB];
 #pragma unroll
-  for (int p = 0; p < 4; ++p)
+  for (int c = 0; c < NB; ++c) {
+    const double v = c >= lane ? T[lane * LDT + c] : T[c * LDT + lane];
+    s[c] = (lane < w && c < w) ? v : (c == lane ? 1.0 : 0.0);     // identity in the padding
+  }
+  double piv = 1.0;                                               // S[lane][lane] when its step starts
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {                          // upper triangle mirrored, identity in the padding
-      const int r = ti + 16 * p, c = tl + 16 * q;
-      double v;
-      if (r < w && c < w) {
-        const int rr = min(r, c), cc = max(r, c);
-        v = a.F[(int64_t)(k0 + rr) * a.ldf + k0 + cc];
-      } else {
-        v = r == c ? 1.0 : 0.0;
-      }
-      s[p][q] = v;
-    }
   for (int j = NB - 1; j >= 0; --j) {
-    double* cb = col[j & 1];
-    if (tl == (j & 15)) {                                  // owners of column j publish it
+    double* rb = row[j & 1];
+    if (lane == j) {
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        double v = s[p][0];
-#pragma unroll
-        for (int q = 1; q < 4; ++q) v = (j >> 4) == q ? s[p][q] : v;
-        cb[ti + 16 * p] = v;
-      }
+      for (int c = 0; c <= j; ++c) rb[c] = s[c];
     }
-    __syncthreads();
-    const double sjj = cb[j];
+    wave_publish();
+    const double sjj = rb[j];
     const bool bad = !(sjj > 0.0);
-    if (bad && tid == 0) atomicCAS(a.info, 0, k0 + j + 1);
+    if (bad && lane == 0) atomicCAS(a.info, 0, k0 + j + 1);
     const double rinv = bad ? 0.0 : fast_rcp(sjj);
-    double ci[4], cl[4];
+    piv = lane == j ? sjj : piv;
+    const double ci = s[j] * rinv;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) { ci[p] = cb[ti + 16 * p] * rinv; cl[p] = cb[tl + 16 * p]; }
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-        if (ti + 16 * p < j && tl + 16 * q < j) s[p][q] = fma(-ci[p], cl[q], s[p][q]);
+    for (int c = 0; c < j; ++c) s[c] = fma(-ci, rb[c], s[c]);
   }
-  // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j, zero below the diagonal
-  __syncthreads();
-  if (ti == tl) {
+  // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j; 1 / V[j][j] is the same factor.  The rows of V go to
+  // LDS (the staging tile is free now), which ends the life of s[].
+  dsh[lane] = piv > 0.0 ? 1.0 / sqrt(piv) : 1.0;
+  wave_publish();
 #pragma unroll
-    for (int p = 0; p < 4; ++p) { const double d = s[p][p]; col[0][ti + 16 * p] = d > 0.0 ? 1.0 / sqrt(d) : 1.0; }
+  for (int j = 0; j < NB; ++j) T[lane * LDT + j] = s[j] * dsh[j];
+  wave_publish();
+  // W = V^-1 (upper): lane c holds column c.  W[i][c] = -(1/V[i][i]) sum_{i < l <= c} V[i][l] W[l][c]; the
+  // entries below the diagonal stay zero by themselves, so the sum may run over all l > i.  Row i of V
+  // is read from LDS at the same address by all lanes.
+  double wv[NB];
+#pragma unroll
+  for (int i = NB - 1; i >= 0; --i) {
+    double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
+#pragma unroll
+    for (int l = i + 1; l < NB; ++l) {
+      const double vil = T[i * LDT + l];
+      const int k = (l - i - 1) & 3;
+      if (k == 0) p0 = fma(vil, wv[l], p0);
+      else if (k == 1) p1 = fma(vil, wv[l], p1);
+      else if (k == 2) p2 = fma(vil, wv[l], p2);
+      else p3 = fma(vil, wv[l], p3);
+    }
+    const double rd = dsh[i];
+    wv[i] = lane == i ? rd : -rd * ((p0 + p1) + (p2 + p3));
   }
-  __syncthreads();
-#pragma unroll
-  for (int p = 0; p < 4; ++p)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = ti + 16 * p, c = tl + 16 * q;
-      S[r * LDT + c] = r <= c ? s[p][q] * col[0][c] : 0.0;
-      Wi[r * LDT + c] = 0.0;
-    }
-  __syncthreads();
-  // Wi = V^-1 by back substitution, row by row from the bottom.  The four threads that share a column
-  // are neighbouring lanes of one wavefront and columns are independent, so no barrier is needed inside.
-  {
-    const int c = tid >> 2, part = tid & 3;
-    if (part == 0) {
-      const double rd = 1.0 / S[c * LDT + c];
-      Wi[c * LDT + c] = rd;
-      col[1][c] = rd;                                       // reciprocal diagonal of V
-    }
-    __syncthreads();
-    for (int i = c - 1; i >= 0; --i) {
-      // thread `part` sums the terms l = part, part + 4, ... inside (i, c]; all 32 LDS reads are issued
-      // before the first use so their latencies overlap, and four partial sums shorten the fma chain
-      double sv[16], wv[16];
-#pragma unroll
-      for (int q = 0; q < 16; ++q) {
-        const int l = part + 4 * q;
-        const bool ok = l > i && l <= c;
-        sv[q] = ok ? S[i * LDT + l] : 0.0;
-        wv[q] = ok ? Wi[l * LDT + c] : 0.0;
-      }
-      const double ri = col[1][i];
-      double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-#pragma unroll
-      for (int q = 0; q < 16; q += 4) {
-        s0 = fma(sv[q], wv[q], s0); s1 = fma(sv[q + 1], wv[q + 1], s1);
-        s2 = fma(sv[q + 2], wv[q + 2], s2); s3 = fma(sv[q + 3], wv[q + 3], s3);
-      }
-      const double sum = quad_sum((s0 + s1) + (s2 + s3));
-      if (part == 0) Wi[i * LDT + c] = -sum * ri;
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    }
-  }
-  __syncthreads();
   double* D = a.Dinv + (int64_t)a.kb * NB * NB;
-  for (int idx = tid; idx < NB * NB; idx += 256) {
-    const int r = idx >> 6, c = idx & 63;
-    D[idx] = Wi[r * LDT + c];
-  }
+#pragma unroll
+  for (int i = 0; i < NB; ++i) D[i * NB + lane] = wv[i];
 }
 
 // ------------------------------------------------------------------------------ panel
@@ -395,32 +353,42 @@ struct DGemm {
   int M, N, K, beta, upper_only;
   double alpha;
 };
-constexpr int DG_LS = 144, DG_BK = 16;
-constexpr int DG_LDS = 2 * 2 * DG_BK * DG_LS * 8;
+constexpr int DG_BK = 16;
+// BW = 16 x 16 blocks per wavefront edge: 4 (128 x 128 tile per workgroup) or, for products too small to
+// give every CU a 128-tile, 2 (64 x 64 tile: four times the workgroups, each a quarter of the work).
+template <int BW> struct DgTile {
+  static constexpr int TILE = 32 * BW;
+  static constexpr int LS = TILE + 16;                  // LDS row stride (doubles): k and k+1 rows in different bank halves
+  static constexpr int LDS = 2 * 2 * DG_BK * LS * 8;
+  static constexpr int CH = DG_BK * TILE / 2 / 256;     // 16-byte chunks per thread per operand k-tile
+};
 typedef __attribute__((ext_vector_type(2))) double f64x2;
 
+template <int BW>
 __global__ __launch_bounds__(256) void dgemm_bulk_kernel(DGemm g) {
+  using D = DgTile<BW>;
+  constexpr int TILE = D::TILE, LS = D::LS, CH = D::CH, WT = TILE / 2, CPR = TILE / 2;   // CPR: chunks per k row
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  double* As = reinterpret_cast<double*>(smem_raw);              // [buf][k][DG_LS]
-  double* Bs = As + 2 * DG_BK * DG_LS;
-  const int i0 = blockIdx.y * 128, j0 = blockIdx.x * 128;
-  if (g.upper_only && j0 + 128 <= i0) return;
+  double* As = reinterpret_cast<double*>(smem_raw);              // [buf][k][LS]
+  double* Bs = As + 2 * DG_BK * LS;
+  const int i0 = blockIdx.y * TILE, j0 = blockIdx.x * TILE;
+  if (g.upper_only && j0 + TILE <= i0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  f64x4 acc[4][4];
+  f64x4 acc[BW][BW];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < BW; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int j = 0; j < BW; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-  // chunk id = tid + 256 p: k row = id >> 6, 16-byte chunk = id & 63 (two doubles)
+  // chunk id = tid + 256 p: k row = id / CPR, 16-byte chunk = id % CPR (two doubles)
   // loads stay in flight while the current k-tile is multiplied: nothing touches the loaded registers
   // until store(), which also zeroes the odd element of a chunk that straddles the edge
-  f64x2 ra[4], rb[4];
+  f64x2 ra[CH], rb[CH];
   auto load = [&](int k0) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int id = tid + 256 * p, k = k0 + (id >> 6), c = (id & 63) * 2;
+    for (int p = 0; p < CH; ++p) {
+      const int id = tid + 256 * p, k = k0 + id / CPR, c = (id % CPR) * 2;
       ra[p] = f64x2{0.0, 0.0};
       rb[p] = f64x2{0.0, 0.0};
       if (k < g.K && i0 + c < g.M) ra[p] = *reinterpret_cast<const f64x2*>(g.At + (int64_t)k * g.lda + i0 + c);
@@ -429,13 +397,13 @@ __global__ __launch_bounds__(256) void dgemm_bulk_kernel(DGemm g) {
   };
   auto store = [&](int buf) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int id = tid + 256 * p, kk = id >> 6, c = (id & 63) * 2;
+    for (int p = 0; p < CH; ++p) {
+      const int id = tid + 256 * p, kk = id / CPR, c = (id % CPR) * 2;
       f64x2 va = ra[p], vb = rb[p];
       if (i0 + c + 1 >= g.M) va[1] = 0.0;
       if (j0 + c + 1 >= g.N) vb[1] = 0.0;
-      *reinterpret_cast<f64x2*>(As + (buf * DG_BK + kk) * DG_LS + c) = va;
-      *reinterpret_cast<f64x2*>(Bs + (buf * DG_BK + kk) * DG_LS + c) = vb;
+      *reinterpret_cast<f64x2*>(As + (buf * DG_BK + kk) * LS + c) = va;
+      *reinterpret_cast<f64x2*>(Bs + (buf * DG_BK + kk) * LS + c) = vb;
     }
   };
   const int nkt = (g.K + DG_BK - 1) / DG_BK;
@@ -445,38 +413,38 @@ __global__ __launch_bounds__(256) void dgemm_bulk_kernel(DGemm g) {
   for (int kt = 0; kt < nkt; ++kt) {
     const int buf = kt & 1;
     if (kt + 1 < nkt) load((kt + 1) * DG_BK);
-    const double* a = As + buf * DG_BK * DG_LS + wm * 64 + (lane & 15);
-    const double* b = Bs + buf * DG_BK * DG_LS + wn * 64 + (lane & 15);
+    const double* a = As + buf * DG_BK * LS + wm * WT + (lane & 15);
+    const double* b = Bs + buf * DG_BK * LS + wn * WT + (lane & 15);
 #pragma unroll
     for (int ks = 0; ks < DG_BK / 4; ++ks) {
       const int kk = ks * 4 + (lane >> 4);
-      double fa[4], fb[4];
+      double fa[BW], fb[BW];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) { fa[i] = a[kk * DG_LS + i * 16]; fb[i] = b[kk * DG_LS + i * 16]; }
+      for (int i = 0; i < BW; ++i) { fa[i] = a[kk * LS + i * 16]; fb[i] = b[kk * LS + i * 16]; }
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < BW; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        for (int j = 0; j < BW; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
     }
     if (kt + 1 < nkt) store(buf ^ 1);
     __syncthreads();
   }
   // epilogue: all loads of a row of blocks are issued before the first store of it
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    double old[4][4];
+  for (int i = 0; i < BW; ++i) {
+    double old[BW][4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < BW; ++j)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int r = i0 + wm * 64 + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * 64 + j * 16 + (lane & 15);
+        const int r = i0 + wm * WT + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * WT + j * 16 + (lane & 15);
         old[j][v] = (g.beta && r < g.M && c < g.N) ? g.C[(int64_t)r * g.ldc + c] : 0.0;
       }
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < BW; ++j)
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int r = i0 + wm * 64 + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * 64 + j * 16 + (lane & 15);
+        const int r = i0 + wm * WT + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * WT + j * 16 + (lane & 15);
         if (r < g.M && c < g.N) g.C[(int64_t)r * g.ldc + c] = fma(g.alpha, acc[i][j][v], old[j][v]);
       }
   }
@@ -575,14 +543,13 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   if (!g_prep_attr) {
-    const void* fns[4] = {(const void*)&diag_kernel, (const void*)&panel_kernel, (const void*)&inner_update_kernel,
-                          (const void*)&trinv_kernel};
+    const void* fns[3] = {(const void*)&panel_kernel, (const void*)&inner_update_kernel, (const void*)&trinv_kernel};
     for (const void* f : fns) {
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, MM_LDS);
       if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
     }
-    hipError_t e2 = hipFuncSetAttribute((const void*)&dgemm_bulk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        DG_LDS);
+    hipError_t e2 = hipFuncSetAttribute((const void*)&dgemm_bulk_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        DgTile<4>::LDS);
     if (e2 != hipSuccess) { set_last_hip_error(e2); return GPTAQ_ELAUNCH; }
     g_prep_attr = true;
   }
@@ -615,7 +582,11 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
                      int K, double alpha, int beta, int upper_only) {
       if (M <= 0 || N <= 0 || K <= 0) return;
       DGemm g{At, lda, Bm, ldb, C, ldc, M, N, K, beta, upper_only, alpha};
-      hipLaunchKernelGGL(dgemm_bulk_kernel, dim3((N + 127) / 128, (M + 127) / 128), dim3(256), DG_LDS, s, g);
+      const int64_t t128 = (int64_t)((N + 127) / 128) * ((M + 127) / 128);
+      if ((upper_only ? t128 / 2 : t128) >= 256)
+        hipLaunchKernelGGL(dgemm_bulk_kernel<4>, dim3((N + 127) / 128, (M + 127) / 128), dim3(256), DgTile<4>::LDS, s, g);
+      else
+        hipLaunchKernelGGL(dgemm_bulk_kernel<2>, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), DgTile<2>::LDS, s, g);
     };
     auto copy = [&](const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols, int upper) {
       if (rows <= 0 || cols <= 0) return;
@@ -634,7 +605,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       const int kb_hi = (o1 + NB - 1) / NB - 1;
       for (int kb = kb_hi; kb >= a.jlo; --kb) {
         a.kb = kb;
-        hipLaunchKernelGGL(diag_kernel, dim3(1), dim3(256), MM_LDS, s, a);
+        hipLaunchKernelGGL(diag_kernel, dim3(1), dim3(64), 0, s, a);
         GPTAQ_LAUNCH_CHECK();
         if (kb > 0) {
           hipLaunchKernelGGL(panel_kernel, dim3(kb), dim3(256), MM_LDS, s, a);
