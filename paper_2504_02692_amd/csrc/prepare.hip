@@ -26,6 +26,7 @@
 namespace gptaq {
 
 constexpr int NB = 64;
+typedef __attribute__((ext_vector_type(2))) double f64x2;
 constexpr int LDT = 65;                       // padded LDS row (doubles)
 constexpr int MM_LDS = 2 * NB * LDT * 8;      // bytes for two staged tiles
 
@@ -127,16 +128,17 @@ __device__ __forceinline__ double fast_rcp(double x) {
 }
 // ------------------------------------------------------------------------------- diag
 // One wavefront: reverse Cholesky of the 64 x 64 diagonal block and the inverse of its factor, with no
-// barrier inside the 64 sequential steps.  Lane r keeps row r of the symmetric block S in registers (both
-// triangles).  At step j the pivot row is lane j's registers: the entry S[c][j] a lane needs to downdate
-// its column c is S[j][c].  Lane j stores its row to LDS and every lane reads it back (same address in
-// all lanes: a broadcast; LDS operations of one wavefront complete in order, so no barrier is needed),
-// then downdates its whole row with the unscaled pivot column; column j is final when step j starts and
-// is never touched again, columns are scaled at the end.  The inverse W of the factor is then built
-// column-per-lane, row by row from the bottom, from the same kind of broadcast of row i of the factor.
-// LDS written by some lanes of the wavefront becomes readable by the others: to the compiler the write
-// and the reads are ordered by a wavefront-scope fence (without it the unsynchronised exchange would be
-// a data race, and it does move the reads ahead of the write); to the hardware they already are.
+// workgroup barrier inside the sequential steps.  Lane r keeps row r of the symmetric block S in registers
+// (both triangles).  At step j a lane downdates its column c with S[r][j] S[c][j] / S[j][j], so it needs the
+// whole pivot column; by symmetry lane c holds S[c][j] in its own register j, so ONE LDS store (every lane
+// its own entry) publishes the column and all lanes read it back at the same addresses (broadcast reads).
+// Column j is final when step j starts and is never touched again; columns are scaled at the end.
+// The inverse W of the factor V is built the same way from W V = I, column by column: column c of V is
+// published with one store, W[r][c] = -(sum_{l < c} W[r][l] V[l][c]) / V[c][c] needs only the lane's own
+// row of W (entries left of the diagonal are zero, so the sum may start at 0).
+// LDS written by some lanes of the wavefront becomes readable by the others: to the compiler the store
+// and the loads are ordered by a wavefront-scope fence (without it the exchange is a data race, and the
+// loads do get moved ahead of the store); to the hardware they already are (one wavefront, in order).
 __device__ __forceinline__ void wave_publish() {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
   __builtin_amdgcn_wave_barrier();
@@ -145,15 +147,21 @@ __device__ __forceinline__ void wave_publish() {
 
 __global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
   __shared__ double T[NB * LDT];
-  __shared__ __attribute__((aligned(16))) double row[2][NB];
+  __shared__ __attribute__((aligned(16))) double colb[2][NB];
   __shared__ double dsh[NB];
   const int lane = threadIdx.x;
   const int k0 = a.kb * NB, w = min(NB, a.n - k0);
-  // stage the stored (upper) triangle, T[c][r] = F[k0+c][k0+r] for c <= r, then mirror it into rows
-#pragma unroll 8
-  for (int c = 0; c < NB; ++c)
-    T[c * LDT + lane] = (c <= lane && lane < w) ? a.F[(int64_t)(k0 + c) * a.ldf + k0 + lane] : 0.0;
-  __syncthreads();
+  // stage the stored (upper) triangle, T[c][r] = F[k0+c][k0+r] for c <= r, then mirror it into rows.
+  // All 64 loads are in flight together (the block was just written by other CUs: ~2 us each way).
+  {
+    double ld[NB];
+#pragma unroll
+    for (int c = 0; c < NB; ++c)
+      ld[c] = (c <= lane && lane < w) ? a.F[(int64_t)(k0 + c) * a.ldf + k0 + lane] : 0.0;
+#pragma unroll
+    for (int c = 0; c < NB; ++c) T[c * LDT + lane] = ld[c];
+  }
+  wave_publish();
   double s[NB];
 #pragma unroll
   for (int c = 0; c < NB; ++c) {
@@ -161,52 +169,85 @@ __global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
     s[c] = (lane < w && c < w) ? v : (c == lane ? 1.0 : 0.0);     // identity in the padding
   }
   double piv = 1.0;                                               // S[lane][lane] when its step starts
-#pragma unroll
-  for (int j = NB - 1; j >= 0; --j) {
-    double* rb = row[j & 1];
-    if (lane == j) {
-#pragma unroll
-      for (int c = 0; c <= j; ++c) rb[c] = s[c];
-    }
-    wave_publish();
-    const double sjj = rb[j];
+  // Step j uses nci = -S[lane][j] / S[j][j] and the published column cb_j.  The column of the next step,
+  // j-1, is downdated and published first, so that its LDS round trip and the reciprocal of the next
+  // pivot overlap with the rest of this step's downdates.
+  colb[(NB - 1) & 1][lane] = s[NB - 1];
+  wave_publish();
+  double nci;
+  {
+    const double sjj = colb[(NB - 1) & 1][NB - 1];
     const bool bad = !(sjj > 0.0);
-    if (bad && lane == 0) atomicCAS(a.info, 0, k0 + j + 1);
-    const double rinv = bad ? 0.0 : fast_rcp(sjj);
-    piv = lane == j ? sjj : piv;
-    const double ci = s[j] * rinv;
-#pragma unroll
-    for (int c = 0; c < j; ++c) s[c] = fma(-ci, rb[c], s[c]);
+    if (bad && lane == 0) atomicCAS(a.info, 0, k0 + NB);
+    piv = lane == NB - 1 ? sjj : piv;
+    nci = -(s[NB - 1] * (bad ? 0.0 : fast_rcp(sjj)));
   }
-  // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j; 1 / V[j][j] is the same factor.  The rows of V go to
-  // LDS (the staging tile is free now), which ends the life of s[].
+#pragma clang loop unroll(full)
+  for (int j = NB - 1; j >= 1; --j) {
+    const double* cb = colb[j & 1];
+    double* nb = colb[(j - 1) & 1];
+    s[j - 1] = fma(nci, cb[j - 1], s[j - 1]);
+    nb[lane] = s[j - 1];
+    wave_publish();
+    const double sjj = nb[j - 1];
+    const bool bad = !(sjj > 0.0);
+    if (bad && lane == 0) atomicCAS(a.info, 0, k0 + j);
+    piv = lane == j - 1 ? sjj : piv;
+    const double nci_next = -(s[j - 1] * (bad ? 0.0 : fast_rcp(sjj)));
+    // all reads of the published column go out before the first fma that uses one (left to itself the
+    // compiler waits for every single read)
+    {
+      f64x2 q[NB / 2];
+#pragma unroll
+      for (int u = 0; u < NB / 2; ++u)
+        if (2 * u < j - 1) q[u] = *reinterpret_cast<const f64x2*>(cb + 2 * u);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < NB / 2; ++u) {
+        if (2 * u < j - 1) s[2 * u] = fma(nci, q[u][0], s[2 * u]);
+        if (2 * u + 1 < j - 1) s[2 * u + 1] = fma(nci, q[u][1], s[2 * u + 1]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    nci = nci_next;
+  }
+  // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j; 1 / V[j][j] is the same factor.  All columns of V are
+  // published at once: Vt[c][l] = V[l][c] (entries below the diagonal are garbage and are not read).
   dsh[lane] = piv > 0.0 ? 1.0 / sqrt(piv) : 1.0;
   wave_publish();
 #pragma unroll
-  for (int j = 0; j < NB; ++j) T[lane * LDT + j] = s[j] * dsh[j];
+  for (int c = 0; c < NB; ++c) T[c * LDT + lane] = s[c] * dsh[c];
   wave_publish();
-  // W = V^-1 (upper): lane c holds column c.  W[i][c] = -(1/V[i][i]) sum_{i < l <= c} V[i][l] W[l][c]; the
-  // entries below the diagonal stay zero by themselves, so the sum may run over all l > i.  Row i of V
-  // is read from LDS at the same address by all lanes.
   double wv[NB];
-#pragma unroll
-  for (int i = NB - 1; i >= 0; --i) {
+#pragma clang loop unroll(full)
+  for (int c = 0; c < NB; ++c) {
     double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
+    {
+      double q[NB];
 #pragma unroll
-    for (int l = i + 1; l < NB; ++l) {
-      const double vil = T[i * LDT + l];
-      const int k = (l - i - 1) & 3;
-      if (k == 0) p0 = fma(vil, wv[l], p0);
-      else if (k == 1) p1 = fma(vil, wv[l], p1);
-      else if (k == 2) p2 = fma(vil, wv[l], p2);
-      else p3 = fma(vil, wv[l], p3);
+      for (int l = 0; l < NB; ++l)
+        if (l < c) q[l] = T[c * LDT + l];
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int l = 0; l < NB; l += 4) {
+        if (l < c) p0 = fma(wv[l], q[l], p0);
+        if (l + 1 < c) p1 = fma(wv[l + 1], q[l + 1], p1);
+        if (l + 2 < c) p2 = fma(wv[l + 2], q[l + 2], p2);
+        if (l + 3 < c) p3 = fma(wv[l + 3], q[l + 3], p3);
+      }
+      __builtin_amdgcn_sched_barrier(0);
     }
-    const double rd = dsh[i];
-    wv[i] = lane == i ? rd : -rd * ((p0 + p1) + (p2 + p3));
+    const double dc = dsh[c];
+    wv[c] = lane == c ? dc : (lane < c ? -dc * ((p0 + p1) + (p2 + p3)) : 0.0);
   }
+  // lane r holds row r of W: through LDS for coalesced stores
+  wave_publish();
+#pragma unroll
+  for (int c = 0; c < NB; ++c) T[lane * LDT + c] = wv[c];
+  wave_publish();
   double* D = a.Dinv + (int64_t)a.kb * NB * NB;
 #pragma unroll
-  for (int i = 0; i < NB; ++i) D[i * NB + lane] = wv[i];
+  for (int i = 0; i < NB; ++i) D[i * NB + lane] = T[i * LDT + lane];
 }
 
 // ------------------------------------------------------------------------------ panel
@@ -362,7 +403,6 @@ template <int BW> struct DgTile {
   static constexpr int LDS = 2 * 2 * DG_BK * LS * 8;
   static constexpr int CH = DG_BK * TILE / 2 / 256;     // 16-byte chunks per thread per operand k-tile
 };
-typedef __attribute__((ext_vector_type(2))) double f64x2;
 
 template <int BW>
 __global__ __launch_bounds__(256) void dgemm_bulk_kernel(DGemm g) {
