@@ -82,6 +82,10 @@ int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
  *   dead : n bytes, out: 1 for dead inputs else 0.  May be NULL.
  *   info : 2 x int32, out: info[0] = 0, or 1 + index of the first non-positive pivot (U, P are
  *          then garbage); info[1] = number of dead inputs.
+ * Streams: part of the factor sweep runs on a helper stream that the library creates once per device
+ * (default priority, kept until the process ends) and ties to `stream` with events on both ends, so to
+ * the caller the call is still one asynchronous operation on `stream`.  Host-side the call takes a
+ * library lock: concurrent calls from several host threads are serialised while they enqueue.
  */
 size_t gptaq_prepare_workspace_bytes(int64_t n);
 int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, float damp,

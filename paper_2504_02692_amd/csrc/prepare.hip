@@ -22,6 +22,8 @@
 // Theorem 4.2's two products then run on the bf16 MFMA GEMM with fp32 operands split into
 // bf16 hi+lo (three cross products per term).
 #include "common.h"
+#include <mutex>
+#include <vector>
 
 namespace gptaq {
 
@@ -561,12 +563,35 @@ PrepLayout prep_layout(int64_t n) {
   L.off_O = take((size_t)L.np * L.np * 4);
   for (int i = 0; i < 6; ++i) L.off_b[i] = take((size_t)L.np * L.np * 2);
   L.off_T1 = take((size_t)NBO * round_up(n, 16) * 8);
-  L.off_T2 = take((size_t)NBO * round_up(n, 16) * 8);
+  L.off_T2 = take((size_t)2 * NBO * round_up(n, 16) * 8);   // two: the side stream reads one while the next is written
   L.off_Uob = take((size_t)2 * NBO * NBO * 8);
   L.total = o;
   return L;
 }
 bool g_prep_attr = false;
+
+// The sweep runs as two chains (see gptaq_prepare): the factorisation on the caller's stream, the inverse on
+// a helper stream of the library, tied together with events.  One helper stream and one growing pool of
+// events per device, created on first use and kept until the process ends.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  std::vector<hipEvent_t> events;
+};
+std::mutex g_side_mutex;
+SideStream g_side[64];
+// Returns the device's helper stream and makes sure `nevents` events exist; nullptr on failure.
+SideStream* side_stream(int nevents) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  SideStream& ss = g_side[dev];
+  if (!ss.stream && hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+  while ((int)ss.events.size() < nevents) {
+    hipEvent_t e;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+    ss.events.push_back(e);
+  }
+  return &ss;
+}
 }  // namespace
 
 extern "C" size_t gptaq_prepare_workspace_bytes(int64_t n) {
@@ -613,67 +638,84 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
                      lam, F, ldf);
   GPTAQ_LAUNCH_CHECK();
 
+  // The sweep is two chains of kernels over the outer blocks OB = nob-1 .. 0 (I: rows above, J: columns right):
+  //   factor chain (caller's stream): inner factorisation of block column OB, T2t = V_I,OB^T, Schur update of F_II;
+  //   inverse chain (helper stream):  U_OB,OB, then U_OB,J = U_OB,OB R_OB,J, R_I,J -= V_I,OB U_OB,J, R_I,OB = -V_I,OB U_OB,OB.
+  // The inverse chain of a block needs that block's T2t and diagonal inverses and nothing later from the
+  // factor chain, and it only writes columns >= o0 of F while the factor chain has moved on to columns < o0,
+  // so the two overlap: the small sequential kernels of one hide behind the rank-256 products of the other.
+  // T2t alternates between two buffers; an event per block and direction orders the streams.
+  std::lock_guard<std::mutex> side_lock(g_side_mutex);
+  const int nob = (int)((n + NBO - 1) / NBO);
+  SideStream* side = side_stream(2 * nob + 2);
+  if (!side) { set_last_hip_error(hipGetLastError()); return GPTAQ_ELAUNCH; }
+  hipStream_t sb = side->stream;
   {
     ProfScope sweep_scope(kProfFactor, s);
     Sweep a;
     a.F = F; a.ldf = ldf; a.n = ni; a.nblk = (int)((n + NB - 1) / NB); a.Dinv = Dinv; a.info = info; a.Uob = Uob;
     double* Uobt = Uob + NBO * NBO;
-    auto dgemm = [&](const double* At, int64_t lda, const double* Bm, int64_t ldb, double* C, int64_t ldc, int M, int N,
-                     int K, double alpha, int beta, int upper_only) {
+    auto dgemm = [&](hipStream_t st, const double* At, int64_t lda, const double* Bm, int64_t ldb, double* C, int64_t ldc,
+                     int M, int N, int K, double alpha, int beta, int upper_only) {
       if (M <= 0 || N <= 0 || K <= 0) return;
       DGemm g{At, lda, Bm, ldb, C, ldc, M, N, K, beta, upper_only, alpha};
       const int64_t t128 = (int64_t)((N + 127) / 128) * ((M + 127) / 128);
       if ((upper_only ? t128 / 2 : t128) >= 256)
-        hipLaunchKernelGGL(dgemm_bulk_kernel<4>, dim3((N + 127) / 128, (M + 127) / 128), dim3(256), DgTile<4>::LDS, s, g);
+        hipLaunchKernelGGL(dgemm_bulk_kernel<4>, dim3((N + 127) / 128, (M + 127) / 128), dim3(256), DgTile<4>::LDS, st, g);
       else
-        hipLaunchKernelGGL(dgemm_bulk_kernel<2>, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), DgTile<2>::LDS, s, g);
+        hipLaunchKernelGGL(dgemm_bulk_kernel<2>, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), DgTile<2>::LDS, st, g);
     };
-    auto copy = [&](const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols, int upper) {
+    auto copy = [&](hipStream_t st, const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols, int upper) {
       if (rows <= 0 || cols <= 0) return;
-      hipLaunchKernelGGL(copy_block_kernel, dim3((cols + 255) / 256, rows), dim3(256), 0, s, src, lds_, dst, ldd, rows,
+      hipLaunchKernelGGL(copy_block_kernel, dim3((cols + 255) / 256, rows), dim3(256), 0, st, src, lds_, dst, ldd, rows,
                          cols, upper);
     };
-    auto transpose = [&](const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols) {
+    auto transpose = [&](hipStream_t st, const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols) {
       if (rows <= 0 || cols <= 0) return;
-      hipLaunchKernelGGL(transpose_block_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, s, src, lds_,
+      hipLaunchKernelGGL(transpose_block_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, st, src, lds_,
                          dst, ldd, rows, cols);
     };
-    const int nob = (int)((n + NBO - 1) / NBO);
-    for (int ob = nob - 1; ob >= 0; --ob) {
+    bool ok = true;
+    auto chk = [&](hipError_t e) { if (e != hipSuccess && ok) { ok = false; set_last_hip_error(e); } };
+    hipEvent_t ev_fork = side->events[2 * nob];
+    chk(hipEventRecord(ev_fork, s));                          // the helper stream starts behind build_F
+    chk(hipStreamWaitEvent(sb, ev_fork, 0));
+    for (int ob = nob - 1; ob >= 0 && ok; --ob) {
       const int o0 = ob * NBO, o1 = (int)(n < o0 + NBO ? n : o0 + NBO), wo = o1 - o0;
+      double* T2b = T2t + (int64_t)(ob & 1) * NBO * ldf;
+      hipEvent_t ev_factored = side->events[2 * ob], ev_inverted = side->events[2 * ob + 1];
       a.o0 = o0; a.o1 = o1; a.jlo = o0 / NB;
+      // ---- factor chain
       const int kb_hi = (o1 + NB - 1) / NB - 1;
       for (int kb = kb_hi; kb >= a.jlo; --kb) {
         a.kb = kb;
         hipLaunchKernelGGL(diag_kernel, dim3(1), dim3(64), 0, s, a);
-        GPTAQ_LAUNCH_CHECK();
-        if (kb > 0) {
-          hipLaunchKernelGGL(panel_kernel, dim3(kb), dim3(256), MM_LDS, s, a);
-          GPTAQ_LAUNCH_CHECK();
-        }
-        if (kb > a.jlo) {
-          hipLaunchKernelGGL(inner_update_kernel, dim3(kb - a.jlo, kb), dim3(256), MM_LDS, s, a);
-          GPTAQ_LAUNCH_CHECK();
-        }
+        if (kb > 0) hipLaunchKernelGGL(panel_kernel, dim3(kb), dim3(256), MM_LDS, s, a);
+        if (kb > a.jlo) hipLaunchKernelGGL(inner_update_kernel, dim3(kb - a.jlo, kb), dim3(256), MM_LDS, s, a);
       }
-      // T2t = V_I,OB^T (k-major operand of the three rank-256 products); T1 = R_OB,J
-      transpose(F + o0, ldf, T2t, ldf, o0, wo);
-      copy(F + (int64_t)o0 * ldf + o1, ldf, T1, ldf, wo, ni - o1, 0);
-      GPTAQ_LAUNCH_CHECK();
+      // this T2t buffer was last read by the inverse chain of block ob + 2
+      if (ob + 2 <= nob - 1) chk(hipStreamWaitEvent(s, side->events[2 * (ob + 2) + 1], 0));
+      transpose(s, F + o0, ldf, T2b, ldf, o0, wo);             // T2t = V_I,OB^T, k-major operand of the rank-256 products
+      chk(hipEventRecord(ev_factored, s));
       // Schur complement of everything above/left of the outer block: F_II -= V_I,OB V_I,OB^T (upper tiles)
-      dgemm(T2t, ldf, T2t, ldf, F, ldf, o0, o0, wo, -1.0, 1, 1);
-      GPTAQ_LAUNCH_CHECK();
-      // triangular inverse of the outer diagonal block, then the right-looking solve V U = I
-      hipLaunchKernelGGL(trinv_kernel, dim3((wo + NB - 1) / NB), dim3(256), MM_LDS, s, a);
-      GPTAQ_LAUNCH_CHECK();
-      copy(Uob, 256, F + (int64_t)o0 * ldf + o0, ldf, wo, wo, 1);             // U_OB,OB into F
-      transpose(Uob, 256, Uobt, 256, wo, wo);
-      GPTAQ_LAUNCH_CHECK();
-      dgemm(Uobt, 256, T1, ldf, F + (int64_t)o0 * ldf + o1, ldf, wo, ni - o1, wo, 1.0, 0, 0);       // U_OB,J = U_OB,OB R_OB,J
-      dgemm(T2t, ldf, F + (int64_t)o0 * ldf + o1, ldf, F + o1, ldf, o0, ni - o1, wo, -1.0, 1, 0);  // R_I,J -= V_I,OB U_OB,J
-      dgemm(T2t, ldf, Uob, 256, F + o0, ldf, o0, wo, wo, -1.0, 0, 0);                              // R_I,OB = -V_I,OB U_OB,OB
-      GPTAQ_LAUNCH_CHECK();
+      dgemm(s, T2b, ldf, T2b, ldf, F, ldf, o0, o0, wo, -1.0, 1, 1);
+      chk(hipGetLastError());
+      // ---- inverse chain
+      chk(hipStreamWaitEvent(sb, ev_factored, 0));
+      copy(sb, F + (int64_t)o0 * ldf + o1, ldf, T1, ldf, wo, ni - o1, 0);     // T1 = R_OB,J
+      hipLaunchKernelGGL(trinv_kernel, dim3((wo + NB - 1) / NB), dim3(256), MM_LDS, sb, a);
+      copy(sb, Uob, 256, F + (int64_t)o0 * ldf + o0, ldf, wo, wo, 1);         // U_OB,OB into F
+      transpose(sb, Uob, 256, Uobt, 256, wo, wo);
+      dgemm(sb, Uobt, 256, T1, ldf, F + (int64_t)o0 * ldf + o1, ldf, wo, ni - o1, wo, 1.0, 0, 0);       // U_OB,J = U_OB,OB R_OB,J
+      dgemm(sb, T2b, ldf, F + (int64_t)o0 * ldf + o1, ldf, F + o1, ldf, o0, ni - o1, wo, -1.0, 1, 0);  // R_I,J -= V_I,OB U_OB,J
+      dgemm(sb, T2b, ldf, Uob, 256, F + o0, ldf, o0, wo, wo, -1.0, 0, 0);                              // R_I,OB = -V_I,OB U_OB,OB
+      chk(hipGetLastError());
+      chk(hipEventRecord(ev_inverted, sb));
     }
+    // join: everything after the sweep runs on the caller's stream (blocks 0 and 1 have not been waited for yet)
+    chk(hipStreamWaitEvent(s, side->events[1], 0));
+    if (nob > 1) chk(hipStreamWaitEvent(s, side->events[3], 0));
+    if (!ok) return GPTAQ_ELAUNCH;
   }
   // U -> H (fp32) and the bf16 splits; dXXT (dead rows zeroed) split.
   const int64_t np = L.np;
