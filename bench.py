@@ -7,7 +7,7 @@ U, P <- prepare; then for every layer that reads that input  quantize_layer.
 Inputs are synthetic (paper_2504_02692_amd/synth.py) and resident in HBM before the timed
 region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 16384]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 32768]
 """
 from __future__ import annotations
 
@@ -60,7 +60,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama7b")
-    ap.add_argument("--chunk", type=int, default=16384, help="tokens per gptaq_accumulate call")
+    ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptaq_accumulate call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -78,7 +78,7 @@ using namespace gptaq;
 
 extern "C" size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n) {
   if (tokens <= 0 || n <= 0) return 0;
-  const int64_t c = round_up(tokens < 16384 ? tokens : 16384, 64);
+  const int64_t c = round_up(tokens < 32768 ? tokens : 32768, 64);
   return (size_t)(3 * padded_n(n) * c * 2);
 }
 

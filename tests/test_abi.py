@@ -43,7 +43,7 @@ def test_missing_library_fails_loudly(monkeypatch):
 
 def test_workspace_queries(lib):
     assert lib.gptaq_accumulate_workspace_bytes(4096, 512) == 3 * 512 * 4096 * 2
-    assert lib.gptaq_accumulate_workspace_bytes(262144, 4096) == 3 * 4096 * 16384 * 2
+    assert lib.gptaq_accumulate_workspace_bytes(262144, 4096) == 3 * 4096 * 32768 * 2
     assert lib.gptaq_accumulate_workspace_bytes(0, 512) == 0
     assert lib.gptaq_prepare_workspace_bytes(512) > 512 * 512 * 8
     assert lib.gptaq_quantize_workspace_bytes(512, 512) == (4 * 512 * 512 + 4 * 512 * 512 + 4 * 512 * 128) * 2

@@ -1,5 +1,5 @@
 """Parity at the full benchmark sizes (Llama-2-7B block shapes, 262144 tokens), in the launch
-configuration bench.py times (16384-token accumulate chunks, W4 g128, B = 128).
+configuration bench.py times (32768-token accumulate chunks, W4 g128, B = 128).
 
 The full fp64 oracle does not fit these sizes everywhere, so each stage is checked on what the
 oracle can compute exactly:
@@ -21,7 +21,7 @@ from paper_2504_02692_amd import synth
 from tests import parity_util as PU
 
 pytestmark = pytest.mark.gpu
-CHUNK = 16384
+CHUNK = 32768
 
 
 def bits_of(t: torch.Tensor) -> np.ndarray:
