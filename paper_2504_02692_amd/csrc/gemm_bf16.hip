@@ -49,7 +49,7 @@ template <int N> __device__ __forceinline__ void wait_vm_and_lds() {
 constexpr int kLds256 = 3 * 3 * 256 * 64;    // largest ring: 3 stages x 3 operand tiles (2 x 4 and 4 x 2 are smaller)
 constexpr int kLds128 = 3 * 3 * 128 * 64;
 
-template <int BT, int KIND>
+template <int BT, int KIND, bool MULTI>
 __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* smem, int m0, int n0, int klo, int nk,
                                           f32x16 (&acc)[BT / 64][BT / 64]) {
   using T = KindTraits<KIND>;
@@ -102,10 +102,11 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
     c.lkt = tm.ktl;
     c.rkt = tm.ktr;
   };
-  auto next_tile = [&](TileSrc& c) {
+  // moves the cursor on by one k-tile; `stage` (static) is the stage the new tile goes to
+  auto next_tile = [&](TileSrc& c, int stage) {
     ++c.seq;
-    c.st = smem + (c.seq % NSTAGE) * STAGE_BYTES + wave_s * LPW * 1024;
-    if (c.seq == nk && c.seq < total_it) {
+    c.st = smem + stage * STAGE_BYTES + wave_s * LPW * 1024;
+    if (MULTI && c.seq == nk && c.seq < total_it) {
       seek_term(c, 1);
     } else {
       const int64_t ls = c.seq < total_it ? c.lkt : 0, rs = c.seq < total_it ? c.rkt : 0;
@@ -179,10 +180,11 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   seek_term(c, 0);
   c.seq = 0;
   c.st = smem + wave_s * LPW * 1024;
+#pragma unroll
   for (int t = 0; t < NSTAGE - 1; ++t) {
 #pragma unroll
     for (int q = 0; q < TL; ++q) load_one(c, q);
-    next_tile(c);
+    next_tile(c, t + 1);
   }
 #pragma unroll
   for (int q = 0; q < HF; ++q) load_one(c, q);
@@ -193,18 +195,24 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
 #pragma unroll
     for (int r = 0; r < NFRAG; ++r) read_one(f0, 0, r);
   }
-  for (int it = 0; it < total_it; ++it) {
-    const int stage = it % NSTAGE;
-    __builtin_amdgcn_sched_barrier(0);
-    mfma_step(0, frag_src(stage, 1), c, HF, TL);
-    __builtin_amdgcn_sched_barrier(0);
-    wait_vm_and_lds<PENDING>();
-    wg_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-    next_tile(c);
-    // (behind the last k-tile these fragment reads fetch a stale stage and nobody uses them)
-    mfma_step(1, frag_src((it + 1) % NSTAGE, 0), c, 0, HF);
-    __builtin_amdgcn_sched_barrier(0);
+  // NSTAGE k-tiles per trip, so that every stage number below is a constant (LDS addresses and DMA targets
+  // become immediates and scalars instead of per-iteration vector arithmetic)
+  for (int it0 = 0; it0 < total_it; it0 += NSTAGE) {
+#pragma unroll
+    for (int sg = 0; sg < NSTAGE; ++sg) {
+      if (it0 + sg < total_it) {
+        __builtin_amdgcn_sched_barrier(0);
+        mfma_step(0, frag_src(sg, 1), c, HF, TL);
+        __builtin_amdgcn_sched_barrier(0);
+        wait_vm_and_lds<PENDING>();
+        wg_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        next_tile(c, sg);                                   // tile it + NSTAGE goes where tile it was
+        // (behind the last k-tile these fragment reads fetch a stale stage and nobody uses them)
+        mfma_step(1, frag_src((sg + 1) % NSTAGE, 0), c, 0, HF);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
   }
   wait_vm_and_lds<0>();   // the surplus loads past the last k-tile
 }
@@ -280,9 +288,15 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  if (P.kind == 0) tile_loop<BT, 0>(P, smem, m0, n0, klo, nk, acc);
-  else if (P.kind == 1) tile_loop<BT, 1>(P, smem, m0, n0, klo, nk, acc);
-  else tile_loop<BT, 2>(P, smem, m0, n0, klo, nk, acc);
+  if (P.nterm > 1) {
+    if (P.kind == 0) tile_loop<BT, 0, true>(P, smem, m0, n0, klo, nk, acc);
+    else if (P.kind == 1) tile_loop<BT, 1, true>(P, smem, m0, n0, klo, nk, acc);
+    else tile_loop<BT, 2, true>(P, smem, m0, n0, klo, nk, acc);
+  } else {
+    if (P.kind == 0) tile_loop<BT, 0, false>(P, smem, m0, n0, klo, nk, acc);
+    else if (P.kind == 1) tile_loop<BT, 1, false>(P, smem, m0, n0, klo, nk, acc);
+    else tile_loop<BT, 2, false>(P, smem, m0, n0, klo, nk, acc);
+  }
 
   // ---- epilogue.  MFMA 32x32 result: register v of a lane holds row 8*(v/4) + 4*(lane/32) + v%4,
   // column lane%32 of the block.
