@@ -326,8 +326,9 @@ QLayout q_layout(int64_t m, int64_t n) {
   size_t o = 0;
   for (int i = 0; i < 12; ++i) {
     L.off[i] = o;
-    // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of the far update; 8-11: of a near update
-    o += (size_t)(i < 4 ? L.mp * KS * 2 : i < 8 ? L.np * KS * 2 : (int64_t)KS * QB * 2);
+    // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of its updates (all columns from the
+    // super-block's first on, plus a tile of padding rows); 8-11: unused
+    o += (size_t)(i < 4 ? L.mp * KS * 2 : i < 8 ? (L.np + 256) * KS * 2 : (int64_t)256);
   }
   L.total = o;
   return L;
@@ -400,27 +401,24 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
   // Two-level lazy batching (a re-association of the sums of Eq. 18): a block's update reaches the rest
   // of its super-block at once ("near", K = one block), and the columns after the super-block once per
   // super-block ("far", K = SB blocks), which quarters the passes over W of the flat schedule.
-  auto trailing = [&](int64_t c0, int64_t c1, const uint16_t* const* L4, int64_t ldl, uint16_t* const* R4, int64_t ldr,
-                      int K, int sb0, int nchunks) -> int {
+  // The right operands (rows of U and P of the super-block, transposed and split into bf16 hi + lo) are
+  // made once per super-block for every column from its first on: row c - sb0 of R4[.] holds column c, the
+  // rows of block p at K offsets 128 p ...  Near and far updates read their part of it.
+  uint16_t* const* R4 = buf + 4;
+  auto trailing = [&](int64_t c0, int64_t c1, const uint16_t* const* L4, int64_t sb0, int koff, int K) -> int {
     if (terms == 0) return GPTAQ_OK;                    // no update at all: round to nearest
     const int64_t nt = c1 - c0;
     const int tile = gemm_tile_for(m, nt);
     const int64_t ntp = round_up(nt, tile);
-    {
-      ProfScope ps(kProfTrailSplit, s);
-      hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(ntp / 64), 2, (unsigned)nchunks), dim3(256), 0, s,
-                         U, (terms & 2) ? P : U, ldh, (int)n, sb0, blocksize, (int)c0, (int)c1, R4[0], R4[1], R4[2],
-                         R4[3], ldr);
-    }
-    GPTAQ_LAUNCH_CHECK();
+    const int64_t ro = (c0 - sb0) * KS + koff;
     GemmBatch b{};
     b.nprob = 1; b.tile = tile;
     GemmProblem& g = b.p[0];
     g.C = W + c0; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = K;
     g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(ntp / tile);
     g.kind = 2; g.nterm = 0; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
-    if (terms & 1) g.term[g.nterm++] = {{L4[0], L4[1]}, {R4[0], R4[1]}, ldl, ldr, 32, 32};
-    if (terms & 2) g.term[g.nterm++] = {{L4[2], L4[3]}, {R4[2], R4[3]}, ldl, ldr, 32, 32};
+    if (terms & 1) g.term[g.nterm++] = {{L4[0], L4[1]}, {R4[0] + ro, R4[1] + ro}, KS, KS, 32, 32};
+    if (terms & 2) g.term[g.nterm++] = {{L4[2], L4[3]}, {R4[2] + ro, R4[3] + ro}, KS, KS, 32, 32};
     hipError_t e;
     {
       ProfScope ps(kProfTrailGemm, s);
@@ -432,6 +430,14 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
   for (int64_t sb0 = 0; sb0 < n; sb0 += (int64_t)SB * blocksize) {
     const int64_t sb_end = n < sb0 + (int64_t)SB * blocksize ? n : sb0 + (int64_t)SB * blocksize;
     const int nb = (int)((sb_end - sb0 + blocksize - 1) / blocksize);
+    if (terms != 0 && sb0 + blocksize < n) {
+      ProfScope ps(kProfTrailSplit, s);
+      const int64_t rows = round_up(n - sb0, 256) + 256;   // a trailing GEMM reads whole tiles of rows: zeros past n
+      hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(rows / 64), 2, (unsigned)nb), dim3(256), 0, s,
+                         U, (terms & 2) ? P : U, ldh, (int)n, (int)sb0, blocksize, (int)sb0, (int)n, R4[0], R4[1], R4[2],
+                         R4[3], (int64_t)KS);
+      GPTAQ_LAUNCH_CHECK();
+    }
     for (int p = 0; p < nb; ++p) {
       const int64_t i0 = sb0 + (int64_t)p * blocksize;
       const int bw = (int)(n - i0 < blocksize ? n - i0 : blocksize);
@@ -444,13 +450,13 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
       }
       if (i2 < sb_end) {
         const uint16_t* L4[4] = {a.Eh + p * QB, a.El + p * QB, a.Vh + p * QB, a.Vl + p * QB};
-        const int rc = trailing(i2, sb_end, L4, KS, buf + 8, QB, QB, (int)i0, 1);
+        const int rc = trailing(i2, sb_end, L4, sb0, p * QB, QB);
         if (rc != GPTAQ_OK) return rc;
       }
     }
     if (sb_end < n) {
       const uint16_t* L4[4] = {a.Eh, a.El, a.Vh, a.Vl};
-      const int rc = trailing(sb_end, n, L4, KS, buf + 4, KS, nb * QB, (int)sb0, nb);
+      const int rc = trailing(sb_end, n, L4, sb0, 0, nb * QB);
       if (rc != GPTAQ_OK) return rc;
     }
   }
