@@ -639,15 +639,16 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   GPTAQ_LAUNCH_CHECK();
 
   // The sweep is two chains of kernels over the outer blocks OB = nob-1 .. 0 (I: rows above, J: columns right):
-  //   factor chain (caller's stream): inner factorisation of block column OB, T2t = V_I,OB^T, Schur update of F_II;
-  //   inverse chain (helper stream):  U_OB,OB, then U_OB,J = U_OB,OB R_OB,J, R_I,J -= V_I,OB U_OB,J, R_I,OB = -V_I,OB U_OB,OB.
+  //   factor chain (caller's stream): inner factorisation of block column OB, T2t = V_I,OB^T, Schur update of the
+  //                                   next block column;
+  //   inverse chain (helper stream):  Schur update of the rest of F_II, U_OB,OB, then U_OB,J = U_OB,OB R_OB,J, R_I,J -= V_I,OB U_OB,J, R_I,OB = -V_I,OB U_OB,OB.
   // The inverse chain of a block needs that block's T2t and diagonal inverses and nothing later from the
   // factor chain, and it only writes columns >= o0 of F while the factor chain has moved on to columns < o0,
   // so the two overlap: the small sequential kernels of one hide behind the rank-256 products of the other.
   // T2t alternates between two buffers; an event per block and direction orders the streams.
   std::lock_guard<std::mutex> side_lock(g_side_mutex);
   const int nob = (int)((n + NBO - 1) / NBO);
-  SideStream* side = side_stream(2 * nob + 2);
+  SideStream* side = side_stream(3 * nob + 2);
   if (!side) { set_last_hip_error(hipGetLastError()); return GPTAQ_ELAUNCH; }
   hipStream_t sb = side->stream;
   {
@@ -677,7 +678,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
     };
     bool ok = true;
     auto chk = [&](hipError_t e) { if (e != hipSuccess && ok) { ok = false; set_last_hip_error(e); } };
-    hipEvent_t ev_fork = side->events[2 * nob];
+    hipEvent_t ev_fork = side->events[3 * nob];
     chk(hipEventRecord(ev_fork, s));                          // the helper stream starts behind build_F
     chk(hipStreamWaitEvent(sb, ev_fork, 0));
     for (int ob = nob - 1; ob >= 0 && ok; --ob) {
@@ -697,11 +698,18 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       if (ob + 2 <= nob - 1) chk(hipStreamWaitEvent(s, side->events[2 * (ob + 2) + 1], 0));
       transpose(s, F + o0, ldf, T2b, ldf, o0, wo);             // T2t = V_I,OB^T, k-major operand of the rank-256 products
       chk(hipEventRecord(ev_factored, s));
-      // Schur complement of everything above/left of the outer block: F_II -= V_I,OB V_I,OB^T (upper tiles)
-      dgemm(s, T2b, ldf, T2b, ldf, F, ldf, o0, o0, wo, -1.0, 1, 1);
+      // Schur complement of everything above/left of the outer block, F_II -= V_I,OB V_I,OB^T, in two parts:
+      // the block column the next outer block factors (here, it is on the critical path) and the rest (upper
+      // tiles, on the helper stream).  The next block's part-one update overlaps this block's part two in
+      // memory, so it waits for it.
+      const int c_lo = o0 > NBO ? o0 - NBO : 0;
+      if (ob + 1 <= nob - 1) chk(hipStreamWaitEvent(s, side->events[2 * nob + ob + 1], 0));
+      dgemm(s, T2b, ldf, T2b + c_lo, ldf, F + c_lo, ldf, o0, o0 - c_lo, wo, -1.0, 1, 0);
       chk(hipGetLastError());
       // ---- inverse chain
       chk(hipStreamWaitEvent(sb, ev_factored, 0));
+      dgemm(sb, T2b, ldf, T2b, ldf, F, ldf, c_lo, c_lo, wo, -1.0, 1, 1);
+      chk(hipEventRecord(side->events[2 * nob + ob], sb));
       copy(sb, F + (int64_t)o0 * ldf + o1, ldf, T1, ldf, wo, ni - o1, 0);     // T1 = R_OB,J
       hipLaunchKernelGGL(trinv_kernel, dim3((wo + NB - 1) / NB), dim3(256), MM_LDS, sb, a);
       copy(sb, Uob, 256, F + (int64_t)o0 * ldf + o0, ldf, wo, wo, 1);         // U_OB,OB into F
