@@ -313,7 +313,7 @@ __global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* 
 using namespace gptaq;
 
 namespace {
-constexpr int SB = 4;                         // column blocks per super-block (two-level lazy batching)
+constexpr int SB = 8;                         // column blocks per super-block (two-level lazy batching; 2, 4, 16 measured slower)
 constexpr int KS = SB * QB;
 struct QLayout {
   int64_t mp, np;
@@ -400,7 +400,7 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
   }
   // Two-level lazy batching (a re-association of the sums of Eq. 18): a block's update reaches the rest
   // of its super-block at once ("near", K = one block), and the columns after the super-block once per
-  // super-block ("far", K = SB blocks), which quarters the passes over W of the flat schedule.
+  // super-block ("far", K = SB blocks), which cuts the passes over W of the flat schedule by SB.
   // The right operands (rows of U and P of the super-block, transposed and split into bf16 hi + lo) are
   // made once per super-block for every column from its first on: row c - sb0 of R4[.] holds column c, the
   // rows of block p at K offsets 128 p ...  Near and far updates read their part of it.

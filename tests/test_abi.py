@@ -46,8 +46,8 @@ def test_workspace_queries(lib):
     assert lib.gptaq_accumulate_workspace_bytes(262144, 4096) == 3 * 4096 * 32768 * 2
     assert lib.gptaq_accumulate_workspace_bytes(0, 512) == 0
     assert lib.gptaq_prepare_workspace_bytes(512) > 512 * 512 * 8
-    # -E / V operands of one super-block (512 columns), right operands for all columns + one tile of padding rows
-    assert lib.gptaq_quantize_workspace_bytes(512, 512) == (4 * 512 * 512 + 4 * (512 + 256) * 512) * 2 + 4 * 256
+    # -E / V operands of one super-block (1024 columns), right operands for all columns + one tile of padding rows
+    assert lib.gptaq_quantize_workspace_bytes(512, 512) == (4 * 512 * 1024 + 4 * (512 + 256) * 1024) * 2 + 4 * 256
     assert lib.gptaq_status_string(0) == b"ok"
 
 
