@@ -82,18 +82,22 @@ def main() -> int:
     # ---- resident inputs
     acts = {iid: synth.make_activations_device(wl.tokens, n, wl.seed, iid, dev, wl.n_outliers, wl.outlier_scale,
                                                wl.noise) for iid, n in inputs.items()}
-    W0 = {l.name: synth.make_weights_device(l.m, l.n, wl.seed, l.name, dev) for l in wl.layers}
+    # Layers that share an input share U and P and their rows are independent (Step 1 of the paper), so they
+    # are solved as one stacked matrix: q/k/v as 12288 x 4096, gate/up as 22016 x 4096.
+    groups = {iid: [l for l in wl.layers if l.input_id == iid] for iid in inputs}
+    W0 = {iid: torch.cat([synth.make_weights_device(l.m, l.n, wl.seed, l.name, dev) for l in ls], dim=0)
+          for iid, ls in groups.items()}
     rounds = args.steps + args.warmup
-    Wwork = {l.name: [W0[l.name].clone() for _ in range(rounds)] for l in wl.layers}
+    Wwork = {iid: [W0[iid].clone() for _ in range(rounds)] for iid in inputs}
     HA = {iid: (torch.empty((n, n), device=dev), torch.empty((n, n), device=dev)) for iid, n in inputs.items()}
-    nmax, mmax = max(inputs.values()), max(l.m for l in wl.layers)
+    nmax, mmax = max(inputs.values()), max(w.shape[0] for w in W0.values())
     ws_acc = B.workspace(B.gptaq_accumulate_workspace_bytes(args.chunk, nmax))
     ws_prep = B.workspace(B.gptaq_prepare_workspace_bytes(nmax))
     ws_q = B.workspace(B.gptaq_quantize_workspace_bytes(mmax, nmax))
-    outs = {l.name: (torch.empty((l.m, l.n), dtype=torch.uint8, device=dev),
-                     torch.empty((l.m, max(1, l.n // wl.group) if wl.group > 0 else 1), device=dev),
-                     torch.empty((l.m, max(1, l.n // wl.group) if wl.group > 0 else 1), device=dev))
-            for l in wl.layers}
+    outs = {iid: (torch.empty(tuple(w.shape), dtype=torch.uint8, device=dev),
+                  torch.empty((w.shape[0], max(1, w.shape[1] // wl.group) if wl.group > 0 else 1), device=dev),
+                  torch.empty((w.shape[0], max(1, w.shape[1] // wl.group) if wl.group > 0 else 1), device=dev))
+            for iid, w in W0.items()}
     info = {iid: torch.zeros(2, dtype=torch.int32, device=dev) for iid in inputs}
     dead = {iid: torch.zeros(n, dtype=torch.uint8, device=dev) for iid, n in inputs.items()}
     stage_ms = {"accumulate": 0.0, "prepare": 0.0, "quantize": 0.0}
@@ -110,12 +114,9 @@ def main() -> int:
             if ev: ev[1].record()
             B.gptaq_prepare(H, A, wl.damp, ws_prep, dead=dead[iid], info=info[iid])
             if ev: ev[2].record()
-            for l in wl.layers:
-                if l.input_id != iid:
-                    continue
-                c, s, z = outs[l.name]
-                B.gptaq_quantize_layer(Wwork[l.name][r], H, A, wl.bits, wl.group, wl.sym, wl.blocksize, ws_q,
-                                       dead=dead[iid], codes=c, scales=s, zeros=z)
+            c, s, z = outs[iid]
+            B.gptaq_quantize_layer(Wwork[iid][r], H, A, wl.bits, wl.group, wl.sym, wl.blocksize, ws_q,
+                                   dead=dead[iid], codes=c, scales=s, zeros=z)
             if ev:
                 ev[3].record(); ev[3].synchronize()
                 stage_ms["accumulate"] += ev[0].elapsed_time(ev[1])
@@ -137,7 +138,7 @@ def main() -> int:
         assert info[iid].cpu().tolist()[0] == 0, "factorisation reported a non-positive pivot"
 
     # stage and kernel split: one extra, untimed pass with every kernel bracketed
-    Wwork = {l.name: [W0[l.name].clone()] for l in wl.layers}
+    Wwork = {iid: [W0[iid].clone()] for iid in inputs}
     B.gptaq_profile_enable((1 << len(B.PROFILE_TAGS)) - 1)
     step(0, ev=[torch.cuda.Event(enable_timing=True) for _ in range(4)])
     torch.cuda.synchronize()
@@ -177,7 +178,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: " + ", ".join(f"{l.name} {l.m}x{l.n}" for l in wl.layers) +
                                f"; {wl.tokens} tokens; W{wl.bits} g{wl.group} {'sym' if wl.sym else 'asym'} "
-                               f"B{wl.blocksize}; accumulate chunk {args.chunk}",
+                               f"B{wl.blocksize}; accumulate chunk {args.chunk}; layers with a common input (q/k/v, gate/up) "
+                               f"quantised as one stacked matrix",
                    "layers_per_step": n_layers},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel<256> (accumulate: H and dXXT)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",

@@ -74,7 +74,8 @@ int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
  *   dead inputs (H_qq == 0): H_qq <- 1, row q of dXXT <- 0, dead[q] <- 1;
  *   lambda = damp * mean(diag H)  ("dampened by 1% of the average", end of Section 4.2);
  *   H + lambda I = V V^T with V upper triangular, U = V^-1, so that (H + lambda I)^-1 = L L^T
- *   with L = U^T the lower factor of Step 3 / Lemma 4.1 (factorisation in fp64);
+ *   with L = U^T the lower factor of Step 3 / Lemma 4.1 (factorisation on fp64 data: its 64 x 64 blocks in
+ *   fp64, its rank-256 block products in 46-bit row-scaled fixed point, exact in int32);
  *   P = ((dXXT L) (.) M_U) L^T = triu(dXXT U^T, 1) U   (Eq. 17).
  *
  *   H    : in: upper triangle of H.  out: U (upper triangular, zeros below), fp32.

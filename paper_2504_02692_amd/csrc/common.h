@@ -61,6 +61,33 @@ inline int gemm_tile_for(int64_t M, int64_t N) {
   return (M >= 1024 && N >= 1024 && t256 >= 224) ? 256 : 128;
 }
 
+// fp64-grade rank-k products through digit-sliced int8 MFMA (gemm_i8s.hip).  A sliced operand holds
+// kI8Planes digit planes of rows_pad x kI8MaxK signed bytes (rows_pad a multiple of 128; rows and k beyond the
+// source are zero) and one power-of-two scale per row.
+constexpr int kI8Planes = 6;
+constexpr int kI8MaxK = 256;
+struct I8Operand {
+  uint8_t* planes;
+  double* scale;
+  int64_t rows_pad;
+  int64_t chunk_stride() const { return rows_pad * 32; }
+  int64_t plane_stride() const { return rows_pad * kI8MaxK; }
+  static size_t plane_bytes(int64_t rows_pad) { return (size_t)kI8Planes * rows_pad * kI8MaxK; }
+};
+struct I8Gemm {
+  const uint8_t* A; int64_t a_plane, a_chunk; const double* sa;
+  const uint8_t* B; int64_t b_plane, b_chunk; const double* sb;
+  double* C; int64_t ldc;
+  int32_t M, N, nchunk, beta, upper_only, tiles_m, tiles_n;
+  double alpha;
+};
+// Slices the R x K matrix with element (r, k) at src[r * sr + k * sk] (one stride must be 1, K <= kI8MaxK).
+hipError_t launch_slice_i8(const double* src, int64_t sr, int64_t sk, int R, int K, const I8Operand& o, hipStream_t s);
+// C = beta C + alpha A B^T over rows [a_row0, a_row0 + M) of A and [b_row0, b_row0 + N) of B (offsets multiples
+// of 128 and 64); upper_only skips the tiles entirely below the diagonal of C.
+hipError_t launch_gemm_i8s(const I8Operand& A, int a_row0, const I8Operand& B, int b_row0, double* C, int64_t ldc, int M,
+                           int N, int K, double alpha, int beta, int upper_only, hipStream_t s);
+
 void set_last_hip_error(hipError_t e);
 
 // Optional per-kernel timing with HIP events (gptaq_profile_* in the public header).

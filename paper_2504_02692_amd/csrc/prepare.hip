@@ -33,7 +33,6 @@ constexpr int LDT = 65;                       // padded LDS row (doubles)
 constexpr int MM_LDS = 2 * NB * LDT * 8;      // bytes for two staged tiles
 
 constexpr int NBO = 256;                      // outer block (columns per rank-256 update)
-typedef __attribute__((ext_vector_type(4))) double f64x4;
 
 struct Sweep {
   double* F;
@@ -365,133 +364,6 @@ __global__ void copy_block_kernel(const double* src, int64_t lds_, double* dst, 
   dst[(int64_t)r * ldd + c] = src[(int64_t)r * lds_ + c];
 }
 
-// dst[c][r] = src[r][c] for an (rows x cols) block of doubles (LDS tile transpose).  grid (ceil(cols/64), ceil(rows/64)).
-__global__ __launch_bounds__(256) void transpose_block_kernel(const double* src, int64_t lds_, double* dst, int64_t ldd,
-                                                              int rows, int cols) {
-  __shared__ double t[64][65];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
-  for (int p = 0; p < 16; ++p) {
-    const int r = r0 + y + 4 * p, c = c0 + x;
-    t[y + 4 * p][x] = (r < rows && c < cols) ? src[(int64_t)r * lds_ + c] : 0.0;
-  }
-  __syncthreads();
-  for (int p = 0; p < 16; ++p) {
-    const int c = c0 + y + 4 * p, r = r0 + x;
-    if (r < rows && c < cols) dst[(int64_t)c * ldd + r] = t[x][y + 4 * p];
-  }
-}
-
-// ------------------------------------------------------------------- rank-256 updates: fp64 MFMA
-// C = beta C + alpha At^T B with both operands k-major: At is K x M, B is K x N, row-major, rows
-// 16-byte aligned.  128 x 128 tile per workgroup, four wavefronts 2 x 2, each 4 x 4 blocks of
-// v_mfma_f64_16x16x4_f64 (A: lane l holds row l%16, k l/16; B: column l%16, k l/16; D: register v
-// holds row 4v + l/16, column l%16).  k-tiles of 16 are copied to LDS as they are (16-byte chunks,
-// coalesced, conflict-free); the LDS row stride of 144 doubles puts the k and k+1 rows that a fragment
-// read touches into different bank halves.
-struct DGemm {
-  const double* At; int64_t lda;
-  const double* B; int64_t ldb;
-  double* C; int64_t ldc;
-  int M, N, K, beta, upper_only;
-  double alpha;
-};
-constexpr int DG_BK = 16;
-// BW = 16 x 16 blocks per wavefront edge: 4 (128 x 128 tile per workgroup) or, for products too small to
-// give every CU a 128-tile, 2 (64 x 64 tile: four times the workgroups, each a quarter of the work).
-template <int BW> struct DgTile {
-  static constexpr int TILE = 32 * BW;
-  static constexpr int LS = TILE + 16;                  // LDS row stride (doubles): k and k+1 rows in different bank halves
-  static constexpr int LDS = 2 * 2 * DG_BK * LS * 8;
-  static constexpr int CH = DG_BK * TILE / 2 / 256;     // 16-byte chunks per thread per operand k-tile
-};
-
-template <int BW>
-__global__ __launch_bounds__(256) void dgemm_bulk_kernel(DGemm g) {
-  using D = DgTile<BW>;
-  constexpr int TILE = D::TILE, LS = D::LS, CH = D::CH, WT = TILE / 2, CPR = TILE / 2;   // CPR: chunks per k row
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  double* As = reinterpret_cast<double*>(smem_raw);              // [buf][k][LS]
-  double* Bs = As + 2 * DG_BK * LS;
-  const int i0 = blockIdx.y * TILE, j0 = blockIdx.x * TILE;
-  if (g.upper_only && j0 + TILE <= i0) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  f64x4 acc[BW][BW];
-#pragma unroll
-  for (int i = 0; i < BW; ++i)
-#pragma unroll
-    for (int j = 0; j < BW; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
-
-  // chunk id = tid + 256 p: k row = id / CPR, 16-byte chunk = id % CPR (two doubles)
-  // loads stay in flight while the current k-tile is multiplied: nothing touches the loaded registers
-  // until store(), which also zeroes the odd element of a chunk that straddles the edge
-  f64x2 ra[CH], rb[CH];
-  auto load = [&](int k0) {
-#pragma unroll
-    for (int p = 0; p < CH; ++p) {
-      const int id = tid + 256 * p, k = k0 + id / CPR, c = (id % CPR) * 2;
-      ra[p] = f64x2{0.0, 0.0};
-      rb[p] = f64x2{0.0, 0.0};
-      if (k < g.K && i0 + c < g.M) ra[p] = *reinterpret_cast<const f64x2*>(g.At + (int64_t)k * g.lda + i0 + c);
-      if (k < g.K && j0 + c < g.N) rb[p] = *reinterpret_cast<const f64x2*>(g.B + (int64_t)k * g.ldb + j0 + c);
-    }
-  };
-  auto store = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < CH; ++p) {
-      const int id = tid + 256 * p, kk = id / CPR, c = (id % CPR) * 2;
-      f64x2 va = ra[p], vb = rb[p];
-      if (i0 + c + 1 >= g.M) va[1] = 0.0;
-      if (j0 + c + 1 >= g.N) vb[1] = 0.0;
-      *reinterpret_cast<f64x2*>(As + (buf * DG_BK + kk) * LS + c) = va;
-      *reinterpret_cast<f64x2*>(Bs + (buf * DG_BK + kk) * LS + c) = vb;
-    }
-  };
-  const int nkt = (g.K + DG_BK - 1) / DG_BK;
-  load(0);
-  store(0);
-  __syncthreads();
-  for (int kt = 0; kt < nkt; ++kt) {
-    const int buf = kt & 1;
-    if (kt + 1 < nkt) load((kt + 1) * DG_BK);
-    const double* a = As + buf * DG_BK * LS + wm * WT + (lane & 15);
-    const double* b = Bs + buf * DG_BK * LS + wn * WT + (lane & 15);
-#pragma unroll
-    for (int ks = 0; ks < DG_BK / 4; ++ks) {
-      const int kk = ks * 4 + (lane >> 4);
-      double fa[BW], fb[BW];
-#pragma unroll
-      for (int i = 0; i < BW; ++i) { fa[i] = a[kk * LS + i * 16]; fb[i] = b[kk * LS + i * 16]; }
-#pragma unroll
-      for (int i = 0; i < BW; ++i)
-#pragma unroll
-        for (int j = 0; j < BW; ++j) acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nkt) store(buf ^ 1);
-    __syncthreads();
-  }
-  // epilogue: all loads of a row of blocks are issued before the first store of it
-#pragma unroll
-  for (int i = 0; i < BW; ++i) {
-    double old[BW][4];
-#pragma unroll
-    for (int j = 0; j < BW; ++j)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int r = i0 + wm * WT + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * WT + j * 16 + (lane & 15);
-        old[j][v] = (g.beta && r < g.M && c < g.N) ? g.C[(int64_t)r * g.ldc + c] : 0.0;
-      }
-#pragma unroll
-    for (int j = 0; j < BW; ++j)
-#pragma unroll
-      for (int v = 0; v < 4; ++v) {
-        const int r = i0 + wm * WT + i * 16 + 4 * v + (lane >> 4), c = j0 + wn * WT + j * 16 + (lane & 15);
-        if (r < g.M && c < g.N) g.C[(int64_t)r * g.ldc + c] = fma(g.alpha, acc[i][j][v], old[j][v]);
-      }
-  }
-}
-
 // --------------------------------------------------------------- extraction and splits
 __device__ __forceinline__ uint16_t bf16_rne(float f) {
   __bf16 b = (__bf16)f;
@@ -548,7 +420,8 @@ using namespace gptaq;
 namespace {
 struct PrepLayout {
   int64_t np;
-  size_t off_F, off_Dinv, off_lam, off_dead, off_O, off_b[6], off_T1, off_T2, off_Uob, total;
+  int64_t rp;                      // rows of a sliced operand that spans the whole matrix
+  size_t off_F, off_Dinv, off_lam, off_dead, off_O, off_b[6], off_Uob, off_pl[5], off_sc[5], total;
 };
 PrepLayout prep_layout(int64_t n) {
   PrepLayout L;
@@ -562,9 +435,15 @@ PrepLayout prep_layout(int64_t n) {
   L.off_dead = take((size_t)n);
   L.off_O = take((size_t)L.np * L.np * 4);
   for (int i = 0; i < 6; ++i) L.off_b[i] = take((size_t)L.np * L.np * 2);
-  L.off_T1 = take((size_t)NBO * round_up(n, 16) * 8);
-  L.off_T2 = take((size_t)2 * NBO * round_up(n, 16) * 8);   // two: the side stream reads one while the next is written
-  L.off_Uob = take((size_t)2 * NBO * NBO * 8);
+  L.off_Uob = take((size_t)NBO * NBO * 8);
+  // sliced operands of the rank-256 products: V_I,OB (two: the helper stream reads one while the next is
+  // written), R_OB,J / U_OB,J, and U_OB,OB by rows and by columns
+  L.rp = round_up(n, 128);
+  for (int i = 0; i < 5; ++i) {
+    const int64_t rows = i < 3 ? L.rp : NBO;
+    L.off_pl[i] = take(I8Operand::plane_bytes(rows));
+    L.off_sc[i] = take((size_t)rows * 8);
+  }
   L.total = o;
   return L;
 }
@@ -613,9 +492,6 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, MM_LDS);
       if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
     }
-    hipError_t e2 = hipFuncSetAttribute((const void*)&dgemm_bulk_kernel<4>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        DgTile<4>::LDS);
-    if (e2 != hipSuccess) { set_last_hip_error(e2); return GPTAQ_ELAUNCH; }
     g_prep_attr = true;
   }
   unsigned char* base = (unsigned char*)ws;
@@ -624,8 +500,9 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   double* Dinv = (double*)(base + L.off_Dinv);
   uint8_t* deadbuf = dead ? dead : (uint8_t*)(base + L.off_dead);
   float* Obuf = (float*)(base + L.off_O);
-  double* T1 = (double*)(base + L.off_T1);
-  double* T2t = (double*)(base + L.off_T2);
+  I8Operand sl[5];
+  for (int i = 0; i < 5; ++i) sl[i] = I8Operand{base + L.off_pl[i], (double*)(base + L.off_sc[i]), i < 3 ? L.rp : (int64_t)NBO};
+  const I8Operand &RJs = sl[2], &Urow = sl[3], &Ucol = sl[4];
   const int64_t ldf = round_up(n, 16);
   double* Uob = (double*)(base + L.off_Uob);
   uint16_t* bb[6];
@@ -639,13 +516,14 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   GPTAQ_LAUNCH_CHECK();
 
   // The sweep is two chains of kernels over the outer blocks OB = nob-1 .. 0 (I: rows above, J: columns right):
-  //   factor chain (caller's stream): inner factorisation of block column OB, T2t = V_I,OB^T, Schur update of the
-  //                                   next block column;
+  //   factor chain (caller's stream): inner factorisation of block column OB, int8 digits of V_I,OB, Schur update
+  //                                   of the next block column;
   //   inverse chain (helper stream):  Schur update of the rest of F_II, U_OB,OB, then U_OB,J = U_OB,OB R_OB,J, R_I,J -= V_I,OB U_OB,J, R_I,OB = -V_I,OB U_OB,OB.
-  // The inverse chain of a block needs that block's T2t and diagonal inverses and nothing later from the
+  // The rank-256 products run on the int8 matrix cores from digit-sliced operands (gemm_i8s.hip).
+  // The inverse chain of a block needs that block's V_I,OB digits and diagonal inverses and nothing later from the
   // factor chain, and it only writes columns >= o0 of F while the factor chain has moved on to columns < o0,
   // so the two overlap: the small sequential kernels of one hide behind the rank-256 products of the other.
-  // T2t alternates between two buffers; an event per block and direction orders the streams.
+  // The V_I,OB digits alternate between two buffers; an event per block and direction orders the streams.
   std::lock_guard<std::mutex> side_lock(g_side_mutex);
   const int nob = (int)((n + NBO - 1) / NBO);
   SideStream* side = side_stream(3 * nob + 2);
@@ -655,35 +533,19 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
     ProfScope sweep_scope(kProfFactor, s);
     Sweep a;
     a.F = F; a.ldf = ldf; a.n = ni; a.nblk = (int)((n + NB - 1) / NB); a.Dinv = Dinv; a.info = info; a.Uob = Uob;
-    double* Uobt = Uob + NBO * NBO;
-    auto dgemm = [&](hipStream_t st, const double* At, int64_t lda, const double* Bm, int64_t ldb, double* C, int64_t ldc,
-                     int M, int N, int K, double alpha, int beta, int upper_only) {
-      if (M <= 0 || N <= 0 || K <= 0) return;
-      DGemm g{At, lda, Bm, ldb, C, ldc, M, N, K, beta, upper_only, alpha};
-      const int64_t t128 = (int64_t)((N + 127) / 128) * ((M + 127) / 128);
-      if ((upper_only ? t128 / 2 : t128) >= 256)
-        hipLaunchKernelGGL(dgemm_bulk_kernel<4>, dim3((N + 127) / 128, (M + 127) / 128), dim3(256), DgTile<4>::LDS, st, g);
-      else
-        hipLaunchKernelGGL(dgemm_bulk_kernel<2>, dim3((N + 63) / 64, (M + 63) / 64), dim3(256), DgTile<2>::LDS, st, g);
-    };
+    bool ok = true;
+    auto chk = [&](hipError_t e) { if (e != hipSuccess && ok) { ok = false; set_last_hip_error(e); } };
     auto copy = [&](hipStream_t st, const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols, int upper) {
       if (rows <= 0 || cols <= 0) return;
       hipLaunchKernelGGL(copy_block_kernel, dim3((cols + 255) / 256, rows), dim3(256), 0, st, src, lds_, dst, ldd, rows,
                          cols, upper);
     };
-    auto transpose = [&](hipStream_t st, const double* src, int64_t lds_, double* dst, int64_t ldd, int rows, int cols) {
-      if (rows <= 0 || cols <= 0) return;
-      hipLaunchKernelGGL(transpose_block_kernel, dim3((cols + 63) / 64, (rows + 63) / 64), dim3(256), 0, st, src, lds_,
-                         dst, ldd, rows, cols);
-    };
-    bool ok = true;
-    auto chk = [&](hipError_t e) { if (e != hipSuccess && ok) { ok = false; set_last_hip_error(e); } };
     hipEvent_t ev_fork = side->events[3 * nob];
     chk(hipEventRecord(ev_fork, s));                          // the helper stream starts behind build_F
     chk(hipStreamWaitEvent(sb, ev_fork, 0));
     for (int ob = nob - 1; ob >= 0 && ok; --ob) {
       const int o0 = ob * NBO, o1 = (int)(n < o0 + NBO ? n : o0 + NBO), wo = o1 - o0;
-      double* T2b = T2t + (int64_t)(ob & 1) * NBO * ldf;
+      const I8Operand& Vs = sl[ob & 1];
       hipEvent_t ev_factored = side->events[2 * ob], ev_inverted = side->events[2 * ob + 1];
       a.o0 = o0; a.o1 = o1; a.jlo = o0 / NB;
       // ---- factor chain
@@ -694,9 +556,9 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
         if (kb > 0) hipLaunchKernelGGL(panel_kernel, dim3(kb), dim3(256), MM_LDS, s, a);
         if (kb > a.jlo) hipLaunchKernelGGL(inner_update_kernel, dim3(kb - a.jlo, kb), dim3(256), MM_LDS, s, a);
       }
-      // this T2t buffer was last read by the inverse chain of block ob + 2
+      // this buffer of V_I,OB digits was last read by the inverse chain of block ob + 2
       if (ob + 2 <= nob - 1) chk(hipStreamWaitEvent(s, side->events[2 * (ob + 2) + 1], 0));
-      transpose(s, F + o0, ldf, T2b, ldf, o0, wo);             // T2t = V_I,OB^T, k-major operand of the rank-256 products
+      chk(launch_slice_i8(F + o0, ldf, 1, o0, wo, Vs, s));     // V_I,OB, the operand of all four products with it
       chk(hipEventRecord(ev_factored, s));
       // Schur complement of everything above/left of the outer block, F_II -= V_I,OB V_I,OB^T, in two parts:
       // the block column the next outer block factors (here, it is on the critical path) and the rest (upper
@@ -704,19 +566,21 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       // memory, so it waits for it.
       const int c_lo = o0 > NBO ? o0 - NBO : 0;
       if (ob + 1 <= nob - 1) chk(hipStreamWaitEvent(s, side->events[2 * nob + ob + 1], 0));
-      dgemm(s, T2b, ldf, T2b + c_lo, ldf, F + c_lo, ldf, o0, o0 - c_lo, wo, -1.0, 1, 0);
-      chk(hipGetLastError());
+      chk(launch_gemm_i8s(Vs, 0, Vs, c_lo, F + c_lo, ldf, o0, o0 - c_lo, wo, -1.0, 1, 0, s));
       // ---- inverse chain
       chk(hipStreamWaitEvent(sb, ev_factored, 0));
-      dgemm(sb, T2b, ldf, T2b, ldf, F, ldf, c_lo, c_lo, wo, -1.0, 1, 1);
+      chk(launch_gemm_i8s(Vs, 0, Vs, 0, F, ldf, c_lo, c_lo, wo, -1.0, 1, 1, sb));
       chk(hipEventRecord(side->events[2 * nob + ob], sb));
-      copy(sb, F + (int64_t)o0 * ldf + o1, ldf, T1, ldf, wo, ni - o1, 0);     // T1 = R_OB,J
+      double* FJ = F + (int64_t)o0 * ldf + o1;                  // block row OB right of the diagonal block
+      chk(launch_slice_i8(FJ, 1, ldf, ni - o1, wo, RJs, sb));   // R_OB,J (digits per column of it)
       hipLaunchKernelGGL(trinv_kernel, dim3((wo + NB - 1) / NB), dim3(256), MM_LDS, sb, a);
       copy(sb, Uob, 256, F + (int64_t)o0 * ldf + o0, ldf, wo, wo, 1);         // U_OB,OB into F
-      transpose(sb, Uob, 256, Uobt, 256, wo, wo);
-      dgemm(sb, Uobt, 256, T1, ldf, F + (int64_t)o0 * ldf + o1, ldf, wo, ni - o1, wo, 1.0, 0, 0);       // U_OB,J = U_OB,OB R_OB,J
-      dgemm(sb, T2b, ldf, F + (int64_t)o0 * ldf + o1, ldf, F + o1, ldf, o0, ni - o1, wo, -1.0, 1, 0);  // R_I,J -= V_I,OB U_OB,J
-      dgemm(sb, T2b, ldf, Uob, 256, F + o0, ldf, o0, wo, wo, -1.0, 0, 0);                              // R_I,OB = -V_I,OB U_OB,OB
+      chk(launch_slice_i8(Uob, 256, 1, wo, wo, Urow, sb));
+      chk(launch_slice_i8(Uob, 1, 256, wo, wo, Ucol, sb));
+      chk(launch_gemm_i8s(Urow, 0, RJs, 0, FJ, ldf, wo, ni - o1, wo, 1.0, 0, 0, sb));           // U_OB,J = U_OB,OB R_OB,J
+      chk(launch_slice_i8(FJ, 1, ldf, ni - o1, wo, RJs, sb));                                    // now U_OB,J
+      chk(launch_gemm_i8s(Vs, 0, RJs, 0, F + o1, ldf, o0, ni - o1, wo, -1.0, 1, 0, sb));         // R_I,J -= V_I,OB U_OB,J
+      chk(launch_gemm_i8s(Vs, 0, Ucol, 0, F + o0, ldf, o0, wo, wo, -1.0, 0, 0, sb));             // R_I,OB = -V_I,OB U_OB,OB
       chk(hipGetLastError());
       chk(hipEventRecord(ev_inverted, sb));
     }
