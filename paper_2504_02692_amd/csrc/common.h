@@ -63,22 +63,22 @@ inline int gemm_tile_for(int64_t M, int64_t N) {
 
 // fp64-grade rank-k products through digit-sliced int8 MFMA (gemm_i8s.hip).  A sliced operand holds
 // kI8Planes digit planes of rows_pad x kI8MaxK signed bytes (rows_pad a multiple of 128; rows and k beyond the
-// source are zero) and one power-of-two scale per row.
+// source are zero) and one power-of-two scale (its exponent) per row.
 constexpr int kI8Planes = 6;
 constexpr int kI8MaxK = 256;
 struct I8Operand {
   uint8_t* planes;
-  double* scale;
+  int32_t* scale;
   int64_t rows_pad;
   int64_t chunk_stride() const { return rows_pad * 32; }
   int64_t plane_stride() const { return rows_pad * kI8MaxK; }
   static size_t plane_bytes(int64_t rows_pad) { return (size_t)kI8Planes * rows_pad * kI8MaxK; }
 };
 struct I8Gemm {
-  const uint8_t* A; int64_t a_plane, a_chunk; const double* sa;
-  const uint8_t* B; int64_t b_plane, b_chunk; const double* sb;
+  const uint8_t* A; int64_t a_plane, a_chunk; const int32_t* sa;
+  const uint8_t* B; int64_t b_plane, b_chunk; const int32_t* sb;
   double* C; int64_t ldc;
-  int32_t M, N, nchunk, beta, upper_only, tiles_m, tiles_n;
+  int32_t M, N, nchunk, beta, upper_only, tiles_m, tiles_n, ntile;
   double alpha;
 };
 // Slices the R x K matrix with element (r, k) at src[r * sr + k * sk] (one stride must be 1, K <= kI8MaxK).

@@ -30,7 +30,8 @@ constexpr int BM = 128, BN = 64;             // workgroup tile: four wavefronts 
 constexpr int KC = 32;                       // digits per k-chunk = one MFMA k-step
 constexpr int SLABS_A = BM / 32, SLABS_B = BN / 32;
 constexpr int STAGE = NP * (BM + BN) * KC;   // 36 KB: all planes of both operands for one k-chunk
-constexpr int NSTAGE = 3;
+constexpr int NSTAGE = 4;
+constexpr int kI8Workgroups = 256;         // one per CU
 constexpr int LOADS = NP * (SLABS_A + SLABS_B);   // 1 KB wave loads per chunk
 constexpr int LPW = LOADS / 4;                    // per wavefront
 static_assert(LOADS % 4 == 0, "loads divide over the four wavefronts");
@@ -43,6 +44,14 @@ __device__ __forceinline__ void wg_barrier_nofence() {
 template <int N> __device__ __forceinline__ void wait_vm_lds() {
   __builtin_amdgcn_s_waitcnt((N & 15) | ((N >> 4) << 14) | (7 << 4));     // vmcnt <= N, lgkmcnt == 0
 }
+// the same for a count known at run time: `chunks` later chunks of LPW loads, plus the epilogue's EPI loads
+template <int LPW, int EPI> __device__ __forceinline__ void wait_vm_lds_for(int chunks, bool epi) {
+  if (epi) {
+    if (chunks >= 2) wait_vm_lds<2 * LPW + EPI>(); else if (chunks == 1) wait_vm_lds<LPW + EPI>(); else wait_vm_lds<EPI>();
+  } else {
+    if (chunks >= 2) wait_vm_lds<2 * LPW>(); else if (chunks == 1) wait_vm_lds<LPW>(); else wait_vm_lds<0>();
+  }
+}
 }  // namespace
 
 // ---------------------------------------------------------------------------------------------- slicing
@@ -52,7 +61,7 @@ template <int N> __device__ __forceinline__ void wait_vm_lds() {
 // product only stores the rows it was asked for, whatever digits the padding holds).
 __global__ __launch_bounds__(256) void slice_i8_kernel(const double* src, int64_t sr, int64_t sk, int R, int K,
                                                        uint8_t* planes, int64_t plane_stride, int64_t chunk_stride,
-                                                       double* scale) {
+                                                       int32_t* scale) {
   __shared__ double smax[32][9];
   const int t = threadIdx.x;
   const bool kmajor = sr == 1;                   // consecutive threads along the contiguous direction
@@ -72,7 +81,7 @@ __global__ __launch_bounds__(256) void slice_i8_kernel(const double* src, int64_
   for (int q = 0; q < 8; ++q) mx = fmax(mx, smax[rl][q]);
   int e = 0;
   if (mx > 0.0) (void)frexp(mx, &e);              // mx = f * 2^e, f in [0.5, 1)
-  if (c == 0) scale[r] = ldexp(1.0, e - 26);      // the product of two scales carries 2^-52: see the epilogue
+  if (c == 0) scale[r] = e - 26;                  // the product of two scaled rows carries 2^-52: see the epilogue
   uint32_t w[NP][8];
 #pragma unroll
   for (int i = 0; i < NP; ++i)
@@ -102,115 +111,210 @@ __global__ __launch_bounds__(256) void slice_i8_kernel(const double* src, int64_
 }
 
 // ------------------------------------------------------------------------------------------------ product
+// Persistent workgroups: each walks its share of the tile list, and the k-chunks of consecutive tiles form
+// one stream through the LDS ring, so the first chunks of the next tile arrive while the current one is
+// finished and written out.
 __global__ __launch_bounds__(256) void gemm_i8s_kernel(I8Gemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int wm = wave >> 1, wn = wave & 1;
 
-  // ---- which tile.  Workgroups go round-robin to the 8 XCDs; each XCD gets one contiguous run of the tile
-  // list, and the list runs through groups of four tile rows column by column, so the tiles an XCD works on
-  // at one time form a 4 x 8 patch whose operand slabs (1.5 MB) stay in that XCD's L2.
-  int id = blockIdx.x;
+  // ---- which tiles.  Workgroups go round-robin to the 8 XCDs; each XCD gets one contiguous run of the tile
+  // list and its workgroups take the tiles of that run in turn.  The list runs through groups of four tile
+  // rows column by column, so the tiles an XCD works on at one time form a 4 x 8 patch whose operand slabs
+  // (1.5 MB) stay in that XCD's L2.
+  int t_next, t_end, t_step;
   {
-    const int ntile = gridDim.x, per = ntile >> 3, rem = ntile & 7, xcd = id & 7, loc = id >> 3;
-    id = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
+    const int nwg = gridDim.x, xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+    const int per = g.ntile >> 3, rem = g.ntile & 7;
+    t_next = (xcd < rem ? xcd * (per + 1) : rem * (per + 1) + (xcd - rem) * per) + loc;
+    t_end = t_next - loc + per + (xcd < rem ? 1 : 0);
+    t_step = (nwg >> 3) + (xcd < (nwg & 7) ? 1 : 0);
   }
-  int tm, tn;
-  {
-    // with upper_only, a group of tile rows starts at the tile column of its first row's diagonal
-    int first = 0, gsz, c0, cnt;
-    for (;;) {
-      gsz = min(4, g.tiles_m - first);
-      c0 = g.upper_only ? min(first * (BM / BN), g.tiles_n) : 0;
-      cnt = gsz * (g.tiles_n - c0);
-      if (id < cnt || first + gsz >= g.tiles_m) break;
-      id -= cnt;
-      first += gsz;
+  struct Tile { int i0, j0; bool ok; };
+  // the next tile of this workgroup that has work (with upper_only, a group of tile rows starts at the tile
+  // column of its first row's diagonal, and the few tiles of its other rows left of theirs are skipped)
+  auto advance = [&]() -> Tile {
+    while (t_next < t_end) {
+      int id = t_next;
+      t_next += t_step;
+      int first = 0, gsz, c0, cnt;
+      for (;;) {
+        gsz = min(4, g.tiles_m - first);
+        c0 = g.upper_only ? min(first * (BM / BN), g.tiles_n) : 0;
+        cnt = gsz * (g.tiles_n - c0);
+        if (id < cnt || first + gsz >= g.tiles_m) break;
+        id -= cnt;
+        first += gsz;
+      }
+      if (id >= cnt) continue;
+      const int i0 = (first + id % gsz) * BM, j0 = (c0 + id / gsz) * BN;
+      if (g.upper_only && j0 + BN <= i0) continue;
+      return Tile{i0, j0, true};
     }
-    if (id >= cnt) return;                     // (cannot happen: the grid is the sum of the group counts)
-    tm = first + id % gsz;
-    tn = c0 + id / gsz;
-  }
-  const int i0 = tm * BM, j0 = tn * BN;
-  if (g.upper_only && j0 + BN <= i0) return;
-
-  // loads: block q of a chunk (q < NP * SLABS_A: plane q / SLABS_A, slab q % SLABS_A of A; then B) goes to
-  // stage + 1024 q.  Wavefront w moves blocks w * LPW .. w * LPW + LPW - 1.
-  auto load_chunk = [&](int c, int stage) {
-#pragma unroll
-    for (int u = 0; u < LPW; ++u) {
-      const int q = wave * LPW + u;
-      const uint8_t* src;
-      if (q < NP * SLABS_A)
-        src = g.A + (int64_t)(q / SLABS_A) * g.a_plane + (int64_t)c * g.a_chunk + (int64_t)(i0 + (q % SLABS_A) * 32) * KC;
-      else
-        src = g.B + (int64_t)((q - NP * SLABS_A) / SLABS_B) * g.b_plane + (int64_t)c * g.b_chunk +
-              (int64_t)(j0 + ((q - NP * SLABS_A) % SLABS_B) * 32) * KC;
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + lane * 16),
-                                       (__attribute__((address_space(3))) void*)(smem + stage * STAGE + q * 1024), 16, 0, 0);
-    }
+    return Tile{0, 0, false};
   };
 
-  i32x16 acc[NP][2];
-#pragma unroll
-  for (int s = 0; s < NP; ++s)
-#pragma unroll
-    for (int f = 0; f < 2; ++f)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[s][f][v] = 0;
+  // loads: a chunk is NP * SLABS_A blocks of A (plane p, slab f at stage + 1024 (SLABS_A p + f)) and then
+  // NP * SLABS_B blocks of B.  Wavefront w moves slab w of every A plane and B blocks 3 w .. 3 w + 2, one
+  // load at a time between the MFMAs of the chunk being multiplied (a wave stalls some tens of clocks per
+  // load it hands to the memory pipeline; in a burst that is time the matrix unit idles).
+  static_assert(SLABS_A == 4 && NP * SLABS_B == 12 && LPW == NP + 3, "load assignment");
+  int lstage = 0;                                // ring position of the next chunk to load
+  const uint8_t* a_src = g.A + wave * 1024 + lane * 16;
+  struct LoadCtx { const uint8_t* pa; const uint8_t* pb; unsigned char* st; bool on; };
+  auto begin_load = [&](const Tile& t, int c, bool on) {
+    LoadCtx L;
+    L.on = on;
+    L.st = smem + lstage * STAGE;
+    L.pa = a_src + (int64_t)c * g.a_chunk + (int64_t)t.i0 * KC;
+    L.pb = g.B + (int64_t)c * g.b_chunk + (int64_t)t.j0 * KC + lane * 16;
+    if (on) lstage = lstage == NSTAGE - 1 ? 0 : lstage + 1;
+    return L;
+  };
+  auto load_one = [&](const LoadCtx& L, int u) {
+    if (!L.on) return;
+    if (u < NP) {
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(L.pa + u * g.a_plane),
+                                       (__attribute__((address_space(3))) void*)(L.st + (u * SLABS_A + wave) * 1024), 16, 0, 0);
+    } else {
+      const int q = wave * 3 + (u - NP);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(L.pb + (q >> 1) * g.b_plane + (q & 1) * 1024),
+                                       (__attribute__((address_space(3))) void*)(L.st + (NP * SLABS_A + q) * 1024), 16, 0, 0);
+    }
+  };
 
   const int rl = lane & 31, line = rl >> 3;
   const int lane_off = line * 256 + ((((rl & 7) << 1) | ((lane >> 5) ^ (line & 1))) << 4);
   const int a_off = wm * 2 * 1024 + lane_off, b_off = NP * SLABS_A * 1024 + wn * 1024 + lane_off;
+  const int nch = g.nchunk;                      // >= 3: the three chunks in flight never reach past the next tile
 
-  const int nch = g.nchunk;
-  load_chunk(0, 0);
-  if (nch > 1) load_chunk(1, 1);
-  for (int c = 0; c < nch; ++c) {
-    // loads return in order: "at most LPW outstanding" means chunk c has landed (its successor may not have)
-    if (c + 1 < nch) wait_vm_lds<LPW>(); else wait_vm_lds<0>();
-    wg_barrier_nofence();                          // chunk c visible to all; every wave is done with chunk c - 1
-    if (c + 2 < nch) load_chunk(c + 2, (c + 2) % NSTAGE);
-    const unsigned char* st = smem + (c % NSTAGE) * STAGE;
-    i32x4 a[NP][2], b[NP];
+  Tile cur = advance();
+  if (!cur.ok) return;
+  Tile nxt = advance();
+  {
+    const LoadCtx L0 = begin_load(cur, 0, true);
 #pragma unroll
-    for (int p = 0; p < NP; ++p) {
-      b[p] = *reinterpret_cast<const i32x4*>(st + b_off + p * SLABS_B * 1024);
+    for (int u = 0; u < LPW; ++u) load_one(L0, u);
+    const LoadCtx L1 = begin_load(cur, 1, true);
 #pragma unroll
-      for (int f = 0; f < 2; ++f) a[p][f] = *reinterpret_cast<const i32x4*>(st + a_off + (p * SLABS_A + f) * 1024);
-    }
-    // digit pair (i, j) adds into the accumulator of weight i + j; consecutive MFMAs use different accumulators
+    for (int u = 0; u < LPW; ++u) load_one(L1, u);
+    const LoadCtx L2 = begin_load(cur, 2, true);
 #pragma unroll
-    for (int i = 0; i < NP; ++i)
+    for (int u = 0; u < LPW; ++u) load_one(L2, u);
+  }
+  int cstage = 0;                                // ring position of the next chunk to multiply
+  bool first = true;
+  constexpr int EPI_LOADS = 32 + 8 + 1;          // old C, row exponents (four rows per load), column exponent
+  static_assert(2 * LPW + EPI_LOADS <= 63, "vmcnt is a 6-bit counter");
+  for (;;) {
+    i32x16 acc[NP][2];
 #pragma unroll
-      for (int j = 0; j + i < NP; ++j)
+    for (int s = 0; s < NP; ++s)
+#pragma unroll
+      for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[s][f][v] = 0;
+    // 32x32 result block: register v of a lane holds row 8 (v / 4) + 4 (lane / 32) + v % 4, column lane % 32.
+    const int col = cur.j0 + wn * 32 + rl;
+    const int rbase = cur.i0 + wm * 64 + 4 * (lane >> 5);
+    double old[2][16];
+    i32x4 ea[2][4];
+    int eb;
+
+    for (int c = 0; c < nch; ++c) {
+      // This wave's loads return in order, so "at most N outstanding" means that everything issued before
+      // the last N has landed; N counts what was issued after the chunk needed now: up to two later chunks
+      // and, in the first tile, the epilogue's loads (issued between chunks 2 and 3).  Stores of the previous
+      // epilogue may still be counted: that only makes the wait longer.  The first three chunks of a later
+      // tile were waited for before that epilogue.
+      const int later = ((c + 1 < nch || nxt.ok) ? 1 : 0) + ((c + 2 < nch || nxt.ok) ? 1 : 0);
+      if (c >= 3 || (first && c == 0)) wait_vm_lds_for<LPW, EPI_LOADS>(later, false);
+      else if (first) wait_vm_lds_for<LPW, EPI_LOADS>(later, true);
+      else wait_vm_lds<63>();
+      wg_barrier_nofence();                        // this chunk is visible to all; every wave is done with the one before
+      if (c == 0) {
+        // What the epilogue needs from memory is requested now and arrives while the tile is multiplied.
+        // The addresses are clamped instead of predicated: the number of loads issued must not depend on data.
+        const int cc = min(col, g.N - 1);
 #pragma unroll
         for (int f = 0; f < 2; ++f)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int row = min(rbase + f * 32 + 8 * (v >> 2) + (v & 3), g.M - 1);
+            old[f][v] = g.C[(int64_t)row * g.ldc + cc];
+          }
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) ea[f][q] = *reinterpret_cast<const i32x4*>(g.sa + rbase + f * 32 + 8 * q);
+        eb = g.sb[col];
+      }
+      const bool in_tile = c + 3 < nch;
+      const LoadCtx L = begin_load(in_tile ? cur : nxt, in_tile ? c + 3 : c + 3 - nch, in_tile || nxt.ok);
+      const unsigned char* st = smem + cstage * STAGE;
+      cstage = cstage == NSTAGE - 1 ? 0 : cstage + 1;
+      // Fragments are read in the order in which the MFMAs first need them (LDS returns in order, so the
+      // first MFMA waits for three reads only, and the rest arrive behind running MFMAs): the digit pairs
+      // (i, j) are taken by max(i, j), so plane p of A and of B comes into play at step p.
+      // (In two batches: the LDS counter of a wave holds 15 outstanding reads, and with more than that in
+      // flight the compiler waits for all of them at once.)
+      i32x4 a[NP][2], b[NP];
+      auto read_plane = [&](int p) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) a[p][f] = *reinterpret_cast<const i32x4*>(st + a_off + (p * SLABS_A + f) * 1024);
+        b[p] = *reinterpret_cast<const i32x4*>(st + b_off + p * SLABS_B * 1024);
+      };
+#pragma unroll
+      for (int p = 0; p < NP / 2; ++p) read_plane(p);
+      __builtin_amdgcn_sched_barrier(0);
+      // pair (i, j) adds into the accumulator of weight i + j; an accumulator is never used by two MFMAs in a row
+      int m = 0;
+      auto pair = [&](int i, int j) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
           acc[i + j][f] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[i][f], b[j], acc[i + j][f], 0, 0, 0);
-  }
+          if (m == 2) {
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int p = NP / 2; p < NP; ++p) read_plane(p);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          if (m % 4 == 1 && m / 4 < LPW) {
+            __builtin_amdgcn_sched_barrier(0);
+            load_one(L, m / 4);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          ++m;
+        }
+      };
+#pragma unroll
+      for (int p = 0; p < NP; ++p) {
+#pragma unroll
+        for (int q = 0; q < p; ++q)
+          if (p + q < NP) { pair(q, p); pair(p, q); }
+        if (2 * p < NP) pair(p, p);
+      }
+    }
 
-  // ---- epilogue.  a b = 2^(Ea + Eb - 92) sum_s acc_s 256^(10 - s) = 2^(Ea + Eb - 52) t with
-  // t = sum_s acc_s 256^(5 - s) (Horner form below), and the row scales are 2^(E - 26): value = sa sb t.
-  // 32x32 result block: register v of a lane holds row 8 (v / 4) + 4 (lane / 32) + v % 4, column lane % 32.
-  const int col = j0 + wn * 32 + rl;
-  const double sbv = g.alpha * g.sb[col];          // scale arrays are padded to whole tiles
+    // ---- epilogue.  a b = 2^(Ea + Eb - 92) sum_s acc_s 256^(10 - s) = 2^(Ea + Eb - 52) t with
+    // t = sum_s acc_s 256^(5 - s) (Horner form below); the stored row exponents are E - 26.
+    wait_vm_lds<0>();                                // old C and exponents; the next tile's first three chunks
 #pragma unroll
-  for (int f = 0; f < 2; ++f) {
-    const int rbase = i0 + wm * 64 + f * 32 + 4 * (lane >> 5);
-    double old[16];
+    for (int f = 0; f < 2; ++f)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = rbase + 8 * (v >> 2) + (v & 3);
-      old[v] = (g.beta && row < g.M && col < g.N) ? g.C[(int64_t)row * g.ldc + col] : 0.0;
-    }
+      for (int v = 0; v < 16; ++v) {
+        const int row = rbase + f * 32 + 8 * (v >> 2) + (v & 3);
+        double t = (double)acc[0][f][v];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int row = rbase + 8 * (v >> 2) + (v & 3);
-      double t = (double)acc[0][f][v];
-#pragma unroll
-      for (int s = 1; s < NP; ++s) t = fma(t, 256.0, (double)acc[s][f][v]);
-      if (row < g.M && col < g.N) g.C[(int64_t)row * g.ldc + col] = fma(g.sa[row] * sbv, t, old[v]);
-    }
+        for (int s = 1; s < NP; ++s) t = fma(t, 256.0, (double)acc[s][f][v]);
+        t = ldexp(t, ea[f][v >> 2][v & 3] + eb);
+        if (row < g.M && col < g.N) g.C[(int64_t)row * g.ldc + col] = g.beta ? fma(g.alpha, t, old[f][v]) : g.alpha * t;
+      }
+    if (!nxt.ok) break;
+    first = false;
+    cur = nxt;
+    nxt = advance();
   }
 }
 
@@ -240,7 +344,8 @@ hipError_t launch_gemm_i8s(const I8Operand& A, int a_row0, const I8Operand& B, i
   }
   g.A = A.planes + (int64_t)a_row0 * KC; g.a_plane = A.plane_stride(); g.a_chunk = A.chunk_stride(); g.sa = A.scale + a_row0;
   g.B = B.planes + (int64_t)b_row0 * KC; g.b_plane = B.plane_stride(); g.b_chunk = B.chunk_stride(); g.sb = B.scale + b_row0;
-  g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.nchunk = (K + KC - 1) / KC; g.beta = beta; g.upper_only = upper_only;
+  g.C = C; g.ldc = ldc; g.M = M; g.N = N; g.beta = beta; g.upper_only = upper_only;
+  g.nchunk = K <= 2 * KC ? 3 : (K + KC - 1) / KC;  // (a sliced operand is zero past its K)
   g.alpha = alpha;
   int total = 0;
   for (int first = 0; first < g.tiles_m; first += 4) {
@@ -249,7 +354,9 @@ hipError_t launch_gemm_i8s(const I8Operand& A, int a_row0, const I8Operand& B, i
     total += gsz * (g.tiles_n - c0);
   }
   if (total == 0) return hipSuccess;
-  hipLaunchKernelGGL(gemm_i8s_kernel, dim3((unsigned)total), dim3(256), NSTAGE * STAGE, s, g);
+  g.ntile = total;
+  hipLaunchKernelGGL(gemm_i8s_kernel, dim3((unsigned)(total < kI8Workgroups ? total : kI8Workgroups)), dim3(256),
+                     NSTAGE * STAGE, s, g);
   return hipGetLastError();
 }
 

@@ -442,7 +442,7 @@ PrepLayout prep_layout(int64_t n) {
   for (int i = 0; i < 5; ++i) {
     const int64_t rows = i < 3 ? L.rp : NBO;
     L.off_pl[i] = take(I8Operand::plane_bytes(rows));
-    L.off_sc[i] = take((size_t)rows * 8);
+    L.off_sc[i] = take((size_t)rows * 4);
   }
   L.total = o;
   return L;
@@ -501,7 +501,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   uint8_t* deadbuf = dead ? dead : (uint8_t*)(base + L.off_dead);
   float* Obuf = (float*)(base + L.off_O);
   I8Operand sl[5];
-  for (int i = 0; i < 5; ++i) sl[i] = I8Operand{base + L.off_pl[i], (double*)(base + L.off_sc[i]), i < 3 ? L.rp : (int64_t)NBO};
+  for (int i = 0; i < 5; ++i) sl[i] = I8Operand{base + L.off_pl[i], (int32_t*)(base + L.off_sc[i]), i < 3 ? L.rp : (int64_t)NBO};
   const I8Operand &RJs = sl[2], &Urow = sl[3], &Ucol = sl[4];
   const int64_t ldf = round_up(n, 16);
   double* Uob = (double*)(base + L.off_Uob);
