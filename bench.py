@@ -174,7 +174,7 @@ def main() -> int:
     out = {
         "metric": "ms_per_layer_solve", "value": ms_per_step / n_layers, "unit": "ms/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 MFMA -> fp32 (fp64 factor)",
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 MFMA -> fp32 (factor: fp64 data, int8-sliced block products)",
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: " + ", ".join(f"{l.name} {l.m}x{l.n}" for l in wl.layers) +
                                f"; {wl.tokens} tokens; W{wl.bits} g{wl.group} {'sym' if wl.sym else 'asym'} "
