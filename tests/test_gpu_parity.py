@@ -89,6 +89,35 @@ def test_prepare_ragged_sizes(n, k):
     assert PU.rel_fro(Pd.cpu().numpy(), P) <= 5e-5
 
 
+def test_prepare_ill_conditioned_hessian():
+    # The rank-256 products of the factor sweep run in 46-bit row-scaled fixed point.  A Hessian whose damped
+    # condition number is ~1e7-1e8 (strongly correlated inputs, a few outlier channels with 1e4 times the energy,
+    # damping 1e-6 of the mean diagonal instead of 1e-2) amplifies any error of the factorisation by that factor:
+    # U must still reach the oracle to a few fp32 roundings.  n = 900 spans four outer blocks, the first one
+    # partial.  (P is a product of fp32-grade GEMMs whose terms cancel at this conditioning; it is only held to
+    # 1e-2 here, its bar on the paper's 1 % damping is in the tests above.)
+    rng = np.random.default_rng(77)
+    n, k = 900, 2400
+    Z = rng.standard_normal((k, 60)) @ rng.standard_normal((60, n)) + 0.02 * rng.standard_normal((k, n))
+    Z[:, rng.choice(n, 5, replace=False)] *= 100.0
+    # both sides start from the same fp32 values (at this condition number the rounding of H to fp32 alone
+    # moves U by 1e-3)
+    H = (Z.T @ Z).astype(np.float32).astype(np.float64)
+    H = np.triu(H) + np.triu(H, 1).T
+    A = (0.05 * rng.standard_normal((k, n)).T @ Z).astype(np.float32).astype(np.float64)
+    damp = 1e-6
+    lam = damp * np.mean(np.diag(H))
+    ev = np.linalg.eigvalsh(H + lam * np.eye(n))
+    cond = ev[-1] / ev[0]
+    U, P, _ = O.prepare(H, A, damp)
+    Ud, Pd, dead, info = run_prepare(H, A, damp)
+    assert info.cpu().tolist() == [0, 0]
+    eu, ep = PU.rel_fro(Ud.cpu().numpy(), U), PU.rel_fro(Pd.cpu().numpy(), P)
+    print(f"cond(H + lam I) = {cond:.2e}: U rel. Frobenius {eu:.3e}  P rel. Frobenius {ep:.3e}")
+    assert cond > 1e6
+    assert eu <= 1e-6 and ep <= 1e-2
+
+
 def test_prepare_reports_dead_inputs_and_bad_pivots():
     Xb, Xtb = synth.make_activations(300, 96, 6, "dead", 2, 20.0)
     Xb = Xb.copy(); Xb[:, 17] = 0
