@@ -42,13 +42,19 @@ def cpu_baseline(wl, budget_s: float = 20.0):
     W = synth.make_weights(m_s, n_s, wl.seed, "cpu")
     t0 = time.perf_counter(); H, A = O.accumulate(Xb, Xtb); t_acc = time.perf_counter() - t0
     t0 = time.perf_counter(); U, P, dead = O.prepare(H, A, wl.damp); t_prep = time.perf_counter() - t0
-    t0 = time.perf_counter(); O.quantize_layer(W, U, P, wl.bits, wl.group, wl.sym); t_q = time.perf_counter() - t0
+    t0 = time.perf_counter(); ref = O.quantize_layer(W, U, P, wl.bits, wl.group, wl.sym); t_q = time.perf_counter() - t0
+    # the same loop with the oracle's lazy-batched (BLAS-3) variant: the fairer CPU figure, reported beside it
+    t0 = time.perf_counter(); blk = O.quantize_layer_blocked(W, U, P, wl.bits, wl.group, wl.sym, wl.blocksize)
+    t_qb = time.perf_counter() - t0
+    same = bool((ref["codes"] == blk["codes"]).all())
     # operation counts: accumulate ~ n^2 k, prepare ~ n^3, quantize ~ m n^2
     acc = sum(n * n * wl.tokens for n in wl.inputs().values()) / (n_s * n_s * tok_s) * t_acc
     prep = sum(n ** 3 for n in wl.inputs().values()) / n_s ** 3 * t_prep
     quant = sum(l.m * l.n * l.n for l in wl.layers) / (m_s * n_s * n_s) * t_q
     ms_per_layer = (acc + prep + quant) * 1e3 / len(wl.layers)
+    ms_blocked = (acc + prep + quant * t_qb / t_q) * 1e3 / len(wl.layers)
     return {"value": ms_per_layer, "unit": "ms/layer", "cores": int(cores), "kind": "oracle",
+            "value_with_blocked_loop": ms_blocked, "blocked_loop_s": t_qb, "blocked_equals_unblocked": same,
             "sample": f"fp64 numpy oracle timed on n={n_s}, {tok_s} tokens, {m_s} rows "
                       f"(accumulate {t_acc:.2f}s, prepare {t_prep:.2f}s, quantize {t_q:.2f}s), each stage scaled by "
                       f"its operation count (n^2 k, n^3, m n^2) to the workload's layer set: extrapolated"}
