@@ -358,6 +358,10 @@ hipError_t launch_quant_for(const QuantArgs& a, hipStream_t s) {
   if (r <= 3) return launch_quant<3, 8>(a, s);
   if (r <= 4) return launch_quant<4, 8>(a, s);
   if (r <= 6) return launch_quant<6, 8>(a, s);
+  if (r <= 8) return launch_quant<8, 8>(a, s);
+  // up to 24576 rows still fit one round of workgroups (a second round would run less than half full)
+  if (r <= 10) return launch_quant<10, 8>(a, s);
+  if (r <= 12) return launch_quant<12, 8>(a, s);
   return launch_quant<8, 8>(a, s);
 }
 }  // namespace

@@ -171,7 +171,10 @@ def test_whole_path_c1(c1):
     (4, 128, False, 128, 5100, 256),     # three
     (3, 0, False, 128, 7000, 128),       # four
     (4, 64, False, 64, 8200, 256),       # six
-    (4, 0, False, 128, 16500, 128),      # eight, more than one round of workgroups
+    (4, 0, False, 128, 16500, 128),      # eight
+    (4, 128, False, 128, 19000, 128),    # ten
+    (4, 128, False, 128, 22016, 256),    # twelve (gate and up of the Llama-2-7B block stacked)
+    (4, 0, False, 128, 26000, 128),      # eight again, more than one round of workgroups
 ])
 def test_quantize_variants(c1, bits, group, sym, blocksize, m, n):
     Hn = c1["H"][:n, :n]; An = c1["A"][:n, :n]
