@@ -31,7 +31,12 @@ constexpr int KC = 32;                       // digits per k-chunk = one MFMA k-
 constexpr int SLABS_A = BM / 32, SLABS_B = BN / 32;
 constexpr int STAGE = NP * (BM + BN) * KC;   // 36 KB: all planes of both operands for one k-chunk
 constexpr int NSTAGE = 4;
-constexpr int kI8Workgroups = 256;         // one per CU
+// Workgroups per launch, at most.  A workgroup fills a CU (registers), and the products run beside the small
+// sequential kernels of the other chain of the sweep, which can only start on a CU that a workgroup has
+// left: with one workgroup per CU for the whole launch those kernels waited (n = 11008: 32.6 ms per
+// prepare; 31.5 with 512, 30.7 with 1024, 30.6 with one tile per workgroup).  1024 keeps the workgroups of the
+// sweep's products short and still lets very large products (n >= 28672) run tens of tiles per workgroup.
+constexpr int kI8Workgroups = 1024;
 constexpr int LOADS = NP * (SLABS_A + SLABS_B);   // 1 KB wave loads per chunk
 constexpr int LPW = LOADS / 4;                    // per wavefront
 static_assert(LOADS % 4 == 0, "loads divide over the four wavefronts");
@@ -111,8 +116,8 @@ __global__ __launch_bounds__(256) void slice_i8_kernel(const double* src, int64_
 }
 
 // ------------------------------------------------------------------------------------------------ product
-// Persistent workgroups: each walks its share of the tile list, and the k-chunks of consecutive tiles form
-// one stream through the LDS ring, so the first chunks of the next tile arrive while the current one is
+// Each workgroup walks its share of the tile list (one tile, or many for large products), and the k-chunks of
+// consecutive tiles form one stream through the LDS ring, so the first chunks of the next tile arrive while the current one is
 // finished and written out.
 __global__ __launch_bounds__(256) void gemm_i8s_kernel(I8Gemm g) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
