@@ -304,55 +304,103 @@ __global__ __launch_bounds__(256) void inner_update_kernel(Sweep a) {
 // U_kl = -Winv_k sum_{k < j <= l} V_kj U_jl.  One workgroup per block column l; results go to the
 // dense scratch Uob (ld 256, zeros below the diagonal), from which they are copied into F afterwards
 // (the V_kj of F are still being read by the other workgroups).
+// The steps of a block column form a chain of 64^3 products, so what counts is the latency of a step:
+// the finished blocks U_jl stay in LDS (slot j; they are the right operands of all later steps), and the
+// left operand of the next product (V_kj or Winv_k, known in advance) is fetched into registers while
+// the current product runs.
+constexpr int TRINV_LDS = 4 * NB * LDT * 8;      // the staged left operand + slots 1..3
 __global__ __launch_bounds__(256) void trinv_kernel(Sweep a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   double* As = reinterpret_cast<double*>(smem_raw);
-  double* Bs = As + NB * LDT;
+  auto slot = [&](int j) { return As + j * NB * LDT; };           // j = 1..3
   const int l = blockIdx.x, kb0 = a.o0 / NB, wo = a.o1 - a.o0;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int nbi = (wo + NB - 1) / NB;
   // blocks below the diagonal of this block column are zero
   for (int k = l + 1; k < nbi; ++k)
     for (int idx = threadIdx.x; idx < NB * NB; idx += 256) a.Uob[(int64_t)(k * NB + (idx >> 6)) * 256 + l * NB + (idx & 63)] = 0.0;
-  for (int k = l; k >= 0; --k) {
-    double acc[4][4];
-    if (k == l) {
-      const double* D = a.Dinv + (int64_t)(kb0 + l) * NB * NB;
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) acc[p][q] = D[(4 * ty + p) * NB + tx + 16 * q];
-    } else {
-      double sum[4][4];
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) sum[p][q] = 0.0;
-      for (int j = k + 1; j <= l; ++j) {
-        __syncthreads();
-        stage_tile(As, a.F, a.ldf, a.o0 + k * NB, a.o0 + j * NB, a.n, a.n, false);   // A[i][m] = V_kj[i][m]
-        stage_tile(Bs, a.Uob, 256, j * NB, l * NB, 256, 256, true);                  // B[m][c] = U_jl[m][c]
-        __syncthreads();
-        mm64(As, Bs, acc);
-#pragma unroll
-        for (int p = 0; p < 4; ++p)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) sum[p][q] += acc[p][q];
-      }
-      __syncthreads();
-      stage_tile(As, a.Dinv + (int64_t)(kb0 + k) * NB * NB, NB, 0, 0, NB, NB, false);  // A[i][m] = Winv_k[i][m]
-#pragma unroll
-      for (int p = 0; p < 4; ++p)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) Bs[(4 * ty + p) * LDT + tx + 16 * q] = -sum[p][q];  // B[m][c] = -S[m][c]
-      __syncthreads();
-      mm64(As, Bs, acc);
-    }
+  auto put_global = [&](int k, const double (&v)[4][4]) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) a.Uob[(int64_t)(k * NB + 4 * ty + p) * 256 + l * NB + tx + 16 * q] = acc[p][q];
-    __threadfence();          // the next k of this workgroup reads these values back from memory
+      for (int q = 0; q < 4; ++q) a.Uob[(int64_t)(k * NB + 4 * ty + p) * 256 + l * NB + tx + 16 * q] = v[p][q];
+  };
+  auto put_slot = [&](double* dst, const double (&v)[4][4], double sign) {    // right-operand layout: dst[m * LDT + c]
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + tx + 16 * q] = sign * v[p][q];
+  };
+  double acc[4][4];
+  {
+    const double* D = a.Dinv + (int64_t)(kb0 + l) * NB * NB;
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[p][q] = D[(4 * ty + p) * NB + tx + 16 * q];
+  }
+  put_global(l, acc);
+  if (l == 0) return;
+  put_slot(slot(l), acc, 1.0);
+
+  // the left operands in the order they are used: for k = l-1 .. 0: V_k,k+1 .. V_k,l, then Winv_k
+  const int c = threadIdx.x & 63, rb = threadIdx.x >> 6;
+  double nxt[16];
+  auto fetch = [&](int t) {
+    int k = l - 1, j = -1;
+    bool found = false;
+    for (; k >= 0; --k) {
+      const int cnt = l - k + 1;
+      if (t < cnt) { j = t < l - k ? k + 1 + t : -1; found = true; break; }
+      t -= cnt;
+    }
+    if (!found) return;
+    const double* src = j >= 0 ? a.F : a.Dinv + (int64_t)(kb0 + k) * NB * NB;
+    const int64_t ld = j >= 0 ? a.ldf : NB;
+    const int r0 = j >= 0 ? a.o0 + k * NB : 0, c0 = j >= 0 ? a.o0 + j * NB : 0, lim = j >= 0 ? a.n : NB;
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+      const int r = rb + 4 * p;
+      nxt[p] = (r0 + r < lim && c0 + c < lim) ? src[(int64_t)(r0 + r) * ld + c0 + c] : 0.0;
+    }
+  };
+  auto stage_next = [&]() {                       // left-operand layout: As[m * LDT + i] = A[i][m]
+#pragma unroll
+    for (int p = 0; p < 16; ++p) As[c * LDT + rb + 4 * p] = nxt[p];
+  };
+  int t = 0;
+  fetch(t++);
+  for (int k = l - 1; k >= 0; --k) {
+    double sum[4][4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) sum[p][q] = 0.0;
+    for (int j = k + 1; j <= l; ++j) {
+      __syncthreads();                            // the product before is done with As; slot writes are visible
+      stage_next();
+      fetch(t++);
+      __syncthreads();
+      mm64(As, slot(j), acc);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sum[p][q] += acc[p][q];
+    }
+    // U_kl = Winv_k (-sum); -sum goes where U_kl will live (for k = 0, which no later step reads, into
+    // slot l, whose block has just been used for the last time)
+    double* tmp = k >= 1 ? slot(k) : slot(l);
+    __syncthreads();
+    stage_next();
+    fetch(t++);
+    put_slot(tmp, sum, -1.0);
+    __syncthreads();
+    mm64(As, tmp, acc);
+    put_global(k, acc);
+    if (k >= 1) {
+      __syncthreads();                            // everyone has read -sum
+      put_slot(tmp, acc, 1.0);
+    }
   }
 }
 
@@ -489,7 +537,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   if (!g_prep_attr) {
     const void* fns[3] = {(const void*)&panel_kernel, (const void*)&inner_update_kernel, (const void*)&trinv_kernel};
     for (const void* f : fns) {
-      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, MM_LDS);
+      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, f == fns[2] ? TRINV_LDS : MM_LDS);
       if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
     }
     g_prep_attr = true;
@@ -573,7 +621,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       chk(hipEventRecord(side->events[2 * nob + ob], sb));
       double* FJ = F + (int64_t)o0 * ldf + o1;                  // block row OB right of the diagonal block
       chk(launch_slice_i8(FJ, 1, ldf, ni - o1, wo, RJs, sb));   // R_OB,J (digits per column of it)
-      hipLaunchKernelGGL(trinv_kernel, dim3((wo + NB - 1) / NB), dim3(256), MM_LDS, sb, a);
+      hipLaunchKernelGGL(trinv_kernel, dim3((wo + NB - 1) / NB), dim3(256), TRINV_LDS, sb, a);
       copy(sb, Uob, 256, F + (int64_t)o0 * ldf + o0, ldf, wo, wo, 1);         // U_OB,OB into F
       chk(launch_slice_i8(Uob, 256, 1, wo, wo, Urow, sb));
       chk(launch_slice_i8(Uob, 1, 256, wo, wo, Ucol, sb));
