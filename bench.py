@@ -151,6 +151,10 @@ def main() -> int:
     prof = {name: B.gptaq_profile_read(i) for i, name in enumerate(B.PROFILE_TAGS)}
     B.gptaq_profile_enable(0)
 
+    # what the matrix cores of this machine sustain on nothing but MFMAs (all-ones and random operands), measured here
+    peak_ones, clk_ones = B.gptaq_measure_mfma_peak(False, 50)
+    peak_rand, clk_rand = B.gptaq_measure_mfma_peak(True, 50)
+
     ms_per_step = elapsed * 1e3 / args.steps
     n_layers = len(wl.layers)
     # dominant kernel: the accumulate MFMA GEMM.  Algorithmic flop per launch = n(n+1)c [H, upper half]
@@ -190,7 +194,14 @@ def main() -> int:
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel<256> (accumulate: H and dXXT)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
-                     "launches": launches, "avg_launch_ms": gemm_ms / max(1, launches)},
+                     "launches": launches, "avg_launch_ms": gemm_ms / max(1, launches),
+                     "executed": achieved * 5.0 / 3.0,
+                     "measured_mfma_loop": {"ones_tflops": peak_ones, "ones_clock_ghz": clk_ones,
+                                            "random_tflops": peak_rand, "random_clock_ghz": clk_rand,
+                                            "executed_frac_of_random": achieved * 5.0 / 3.0 / peak_rand,
+                                            "note": "pure bf16 MFMA loop on all CUs for 50 ms (power-limited clock); "
+                                                    "executed = 5 n^2 c flop (exact hi/lo split of dX) against "
+                                                    "3 n^2 c algorithmic"}},
         "other_kernels": other,
         "stages_ms_per_step": stage_ms,
         "kernels_ms_per_step": {k: v[1] for k, v in prof.items()},

@@ -203,6 +203,17 @@ int gptaq_pack_codes(const uint8_t* codes, int64_t m, int64_t n, int64_t ldc, in
 int gptaq_profile_enable(int mask);
 int gptaq_profile_read(int tag, int64_t* launches, double* total_ms);
 
+/* Measurement aid: the rate the bf16 matrix cores of this GPU sustain when they do nothing else - a loop of
+ * independent 32x32x16 bf16 MFMAs on every compute unit, operands in registers - for about `millis`
+ * milliseconds (1..2000), after one untimed launch of the same length.  The chip is power-limited, so the
+ * rate depends on the operand data: random_data = 0 multiplies all-ones (the least switching activity),
+ * 1 multiplies random signs and mantissas (the fair ceiling for a product of real data).
+ *   ws     : >= 1 MiB of device memory, 256-byte aligned (scratch).
+ *   tflops, clock_ghz : HOST pointers, out: the measured rate and the core clock during the loop.
+ * Synchronous: returns after the measurement. */
+int gptaq_measure_mfma_peak(int random_data, int millis, void* ws, size_t ws_bytes, double* tflops,
+                            double* clock_ghz, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

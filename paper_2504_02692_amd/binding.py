@@ -54,6 +54,8 @@ _SIGS = {
     "gptaq_pack_codes": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_int, _c.c_void_p, _c.c_void_p]),
     "gptaq_profile_enable": (_c.c_int, [_c.c_int]),
     "gptaq_profile_read": (_c.c_int, [_c.c_int, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_double)]),
+    "gptaq_measure_mfma_peak": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.POINTER(_c.c_double),
+                                           _c.POINTER(_c.c_double), _c.c_void_p]),
 }
 EXPORTS = tuple(_SIGS)
 PROFILE_TAGS = ("accumulate_gemm", "accumulate_split", "factor_sweep", "p_gemm", "column_loop", "trailing_gemm",
@@ -195,6 +197,15 @@ def gptaq_profile_read(tag: int):
     n, ms = _c.c_int64(0), _c.c_double(0.0)
     _check(load().gptaq_profile_read(int(tag), _c.byref(n), _c.byref(ms)), "gptaq_profile_read")
     return n.value, ms.value
+
+
+def gptaq_measure_mfma_peak(random_data: bool, millis: int = 50):
+    """(TFLOP/s, core clock in GHz) of a pure bf16 MFMA loop on every CU, on all-ones or on random operands."""
+    ws = workspace(1 << 20)
+    tf, ghz = _c.c_double(0.0), _c.c_double(0.0)
+    _check(load().gptaq_measure_mfma_peak(int(bool(random_data)), int(millis), _ptr(ws), ws.numel() * ws.element_size(),
+                                          _c.byref(tf), _c.byref(ghz), _stream()), "gptaq_measure_mfma_peak")
+    return tf.value, ghz.value
 
 
 def gptaq_act_order(H: torch.Tensor) -> torch.Tensor:

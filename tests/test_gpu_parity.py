@@ -279,3 +279,13 @@ def test_activation_quantiser_and_packing_on_gpu():
         c = rng.integers(0, 2 ** bits, (300, n)).astype(np.uint8)
         p = B.gptaq_pack_codes(torch.from_numpy(c).cuda(), bits)
         assert np.array_equal(p.cpu().numpy().view(np.uint32), O.pack_codes(c, bits))
+
+
+def test_mfma_peak_measurement_is_sane():
+    # the measured ceiling bench.py quotes beside the vendor peak: a finite loop of MFMAs, a plausible rate and clock
+    from paper_2504_02692_amd import binding as B
+    tf1, ghz1 = B.gptaq_measure_mfma_peak(False, 5)
+    tf2, ghz2 = B.gptaq_measure_mfma_peak(True, 5)
+    print(f"pure MFMA loop: all-ones {tf1:.0f} TFLOP/s at {ghz1:.2f} GHz, random operands {tf2:.0f} TFLOP/s at {ghz2:.2f} GHz")
+    assert 500.0 < tf2 <= tf1 * 1.05 < 2700.0
+    assert 1.0 < ghz2 < 2.6 and 1.0 < ghz1 < 2.6
