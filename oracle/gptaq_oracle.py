@@ -9,7 +9,7 @@ Orientation.  The paper writes X as n x k (neurons x tokens).  Activations arriv
 here token-major, shape (k, n), as bfloat16 bit patterns (uint16); Xk below is that
 array widened exactly to float64, so the paper's X is Xk.T.
 
-Readings taken where the paper is silent (each is listed in the design doc):
+Readings taken where the paper is silent:
   * H and dXXT are plain sums over tokens (Algorithm 1, line 2).
   * the W_{:,j} that multiplies P_{j,:} is the current, error-compensated value of
     column j *before* it is quantised (the W_{:,q} of Eq. 15), both inside the block
