@@ -289,3 +289,37 @@ def test_mfma_peak_measurement_is_sane():
     print(f"pure MFMA loop: all-ones {tf1:.0f} TFLOP/s at {ghz1:.2f} GHz, random operands {tf2:.0f} TFLOP/s at {ghz2:.2f} GHz")
     assert 500.0 < tf2 <= tf1 * 1.05 < 2700.0
     assert 1.0 < ghz2 < 2.6 and 1.0 < ghz1 < 2.6
+
+
+def test_stacked_layers_equal_separate_calls(c1):
+    """Layers that share an input share U and P and their rows are independent (Step 1): quantising them as one
+    stacked matrix, as bench.py does for q/k/v and gate/up, gives bit for bit what separate calls give."""
+    wl = c1["wl"]
+    U32, P32 = dev(c1["U"].astype(np.float32)), dev(c1["P"].astype(np.float32))
+    W1, W2 = c1["W"][:300], synth.make_weights(212, 512, 3, "second")
+    one = PU.gpu_quantize(np.concatenate([W1, W2]), U32, P32, 4, 128, False, 128)
+    a, b = PU.gpu_quantize(W1, U32, P32, 4, 128, False, 128), PU.gpu_quantize(W2, U32, P32, 4, 128, False, 128)
+    for key in ("codes", "scales", "zeros", "What"):
+        assert np.array_equal(one[key], np.concatenate([a[key], b[key]])), key
+
+
+def test_bench_line_on_the_small_workload():
+    """bench.py end to end on the 512 x 512 layer: one JSON line with the fields the contract names."""
+    import json, os, subprocess, sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "c1", "--steps", "2", "--warmup", "1",
+                          "--no-cpu-baseline"], capture_output=True, text=True, timeout=110, cwd=root)
+    assert out.returncode == 0, out.stderr[-2000:]
+    line = json.loads(out.stdout.strip().splitlines()[-1])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline"):
+        assert key in line, key
+    assert line["n_gpus"] == 1 and line["steps"] == 2 and line["higher_is_better"] is False and line["value"] > 0
+    r = line["roofline"]
+    assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0 < r["frac"] < 1
+    assert "workload" in line["config"]
+    # more than one GPU is refused with a message
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=60, cwd=root)
+    assert out.returncode != 0 and "one GPU" in out.stderr
