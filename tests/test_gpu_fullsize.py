@@ -97,9 +97,12 @@ def test_llama7b_attention_input_4096():
     eu, ep = PU.rel_fro(H.cpu().numpy(), U64), PU.rel_fro(A.cpu().numpy(), P64)
     print(f"[{iid}] U rel. Frobenius {eu:.3e}; P rel. Frobenius {ep:.3e}")
     assert eu <= 1e-6 and ep <= 5e-5
-    layer = [l for l in wl.layers if l.name == "q_proj"][0]
-    W0 = synth.make_weights_device(layer.m, layer.n, wl.seed, layer.name, "cuda")
-    quantize_rows_check(wl, layer, W0, H, A, U64, P64, X, Xt, "q_proj 4096x4096, oracle factors")
+    # q, k and v share this input and are quantised as one stacked 12288 x 4096 matrix, as bench.py does
+    from types import SimpleNamespace
+    qkv = [l for l in wl.layers if l.input_id == iid]
+    W0 = torch.cat([synth.make_weights_device(l.m, l.n, wl.seed, l.name, "cuda") for l in qkv], dim=0)
+    quantize_rows_check(wl, SimpleNamespace(m=W0.shape[0], n=n), W0, H, A, U64, P64, X, Xt,
+                        "q/k/v stacked 12288x4096, oracle factors")
 
 
 def test_llama7b_mlp_down_input_11008():
