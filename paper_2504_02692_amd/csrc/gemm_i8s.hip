@@ -380,15 +380,18 @@ static hipError_t launch_shape(const I8Operand& A, int a_row0, const I8Operand& 
   return hipGetLastError();
 }
 
-// Measured on the shapes of the sweep (K = 256): 64-row tiles 193 us against 220 for a 5376^2 update, 461 against
-// 505 for the upper half of a 10752^2 one, 25.7 against 32.7 for a 10752 x 256 one.
-constexpr int kI8TileRows = 64;
+// Which shape: measured with K = 256, 64-row tiles against 128-row tiles: 25.7 / 32.7 us for a 10752 x 256 update,
+// 193 / 220 for 5376^2, 461 / 505 for the upper half of 10752^2, 3040 / 3038 for the upper half of 26624^2,
+// 3245 / 3046 for 40960 x 8192.  The small tiles win while latencies matter and lose a little once the product is
+// large enough to be bound by its traffic.
+constexpr int64_t kI8SmallProduct = (int64_t)1 << 28;     // M * N up to here: 64-row tiles
 
 hipError_t launch_gemm_i8s(const I8Operand& A, int a_row0, const I8Operand& B, int b_row0, double* C, int64_t ldc, int M,
                            int N, int K, double alpha, int beta, int upper_only, hipStream_t s) {
   if (M <= 0 || N <= 0 || K <= 0) return hipSuccess;
   if (K > kI8MaxK || (a_row0 % 128) || (b_row0 % BN)) return hipErrorInvalidValue;
-  return launch_shape<kI8TileRows>(A, a_row0, B, b_row0, C, ldc, M, N, K, alpha, beta, upper_only, s);
+  return (int64_t)M * N <= kI8SmallProduct ? launch_shape<64>(A, a_row0, B, b_row0, C, ldc, M, N, K, alpha, beta, upper_only, s)
+                                           : launch_shape<128>(A, a_row0, B, b_row0, C, ldc, M, N, K, alpha, beta, upper_only, s);
 }
 
 }  // namespace gptaq
