@@ -323,3 +323,30 @@ def test_bench_line_on_the_small_workload():
     out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                          timeout=60, cwd=root)
     assert out.returncode != 0 and "one GPU" in out.stderr
+
+
+def test_path_is_bit_reproducible(c1):
+    """No atomics and a fixed summation order everywhere: two runs of the whole path give identical bits (the sweep of
+    gptaq_prepare runs on two streams; a missing dependency between them would show up here as a difference)."""
+    wl = c1["wl"]
+    runs = []
+    for rep in range(3):
+        Hd, Ad = PU.gpu_accumulate(c1["Xb"], c1["Xtb"], chunks=[0, 1500, 4096])
+        h0, a0 = Hd.clone(), Ad.clone()
+        dead, info = PU.gpu_prepare(Hd, Ad, wl.damp)
+        got = PU.gpu_quantize(c1["W"], Hd, Ad, wl.bits, 128, wl.sym, wl.blocksize)
+        runs.append((h0.cpu().numpy(), a0.cpu().numpy(), Hd.cpu().numpy(), Ad.cpu().numpy(), got["codes"], got["What"],
+                     got["scales"], got["zeros"]))
+    for other in runs[1:]:
+        for x, y in zip(runs[0], other):
+            assert np.array_equal(x, y)
+    # and at a size whose sweep has several outer blocks on both streams
+    rng = np.random.default_rng(9)
+    Z = rng.standard_normal((3000, 1160))
+    H, A = Z.T @ Z, 0.05 * rng.standard_normal((3000, 1160)).T @ Z
+    outs = []
+    for rep in range(3):
+        Ud, Pd, dead, info = run_prepare(H, A, 0.01)
+        outs.append((Ud.cpu().numpy(), Pd.cpu().numpy()))
+    for u, p in outs[1:]:
+        assert np.array_equal(u, outs[0][0]) and np.array_equal(p, outs[0][1])
