@@ -156,8 +156,8 @@ int gptaq_quantize_layer_ex(float* W, int64_t m, int64_t n, int64_t ldw,
  *
  * gptaq_act_order: perm[r] = index of the input with the r-th largest H[i][i]; equal diagonals keep
  *   their index order.  perm: n x int32 (device).
- * gptaq_permute_hessian: in place H[i][j] <- H[perm[i]][perm[j]] (upper triangle in, upper triangle
- *   out) and dXXT[i][j] <- dXXT[perm[i]][perm[j]];  ws: gptaq_permute_hessian_workspace_bytes(n).
+ * gptaq_permute_hessian: in place H[i][j] <- H[perm[i]][perm[j]] (upper triangle in; the whole symmetric
+ *   matrix out) and dXXT[i][j] <- dXXT[perm[i]][perm[j]];  ws: gptaq_permute_hessian_workspace_bytes(n).
  * gptaq_permute_columns_{f32,u8}: inverse == 0: out[r][i] = in[r][perm[i]];
  *   inverse != 0: out[r][perm[i]] = in[r][i].  in and out must not overlap.
  */

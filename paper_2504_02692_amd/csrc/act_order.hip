@@ -26,14 +26,12 @@ __global__ __launch_bounds__(256) void rank_diag_kernel(const float* H, int64_t 
   if (i < n) perm[rank] = i;
 }
 
-// out[i][j] = in[perm[i]][perm[j]];  upper != 0: `in` holds a symmetric matrix in its upper triangle.
+// out[i][j] = in[perm[i]][perm[j]]: a workgroup gathers within one source row (the row stays in L2).
 __global__ __launch_bounds__(256) void permute_square_kernel(const float* in, float* out, int n, int64_t ldin,
-                                                             int64_t ldout, const int32_t* perm, int upper) {
+                                                             int64_t ldout, const int32_t* perm) {
   const int j = blockIdx.x * 256 + threadIdx.x, i = blockIdx.y;
   if (j >= n) return;
-  int pi = perm[i], pj = perm[j];
-  if (upper && pi > pj) { const int t = pi; pi = pj; pj = t; }
-  out[(int64_t)i * ldout + j] = in[(int64_t)pi * ldin + pj];
+  out[(int64_t)i * ldout + j] = in[(int64_t)perm[i] * ldin + perm[j]];
 }
 
 __global__ void copy2d_kernel(const float* in, float* out, int n, int64_t ldin, int64_t ldout) {
@@ -77,9 +75,12 @@ extern "C" int gptaq_permute_hessian(float* H, float* dXXT, int64_t n, int64_t l
   hipStream_t s = (hipStream_t)stream;
   float* tmp = (float*)ws;
   const dim3 grid((unsigned)((n + 255) / 256), (unsigned)n);
+  // H arrives as its upper triangle: mirror it first, so that the gather never has to read a column
+  const int st = gptaq_symmetrize(H, n, ldh, stream);
+  if (st != GPTAQ_OK) return st;
   for (int which = 0; which < 2; ++which) {
     float* M = which ? dXXT : H;
-    hipLaunchKernelGGL(permute_square_kernel, grid, dim3(256), 0, s, M, tmp, (int)n, ldh, n, perm, which ? 0 : 1);
+    hipLaunchKernelGGL(permute_square_kernel, grid, dim3(256), 0, s, M, tmp, (int)n, ldh, n, perm);
     GPTAQ_LAUNCH_CHECK();
     hipLaunchKernelGGL(copy2d_kernel, grid, dim3(256), 0, s, tmp, M, (int)n, n, ldh);
     GPTAQ_LAUNCH_CHECK();
