@@ -147,7 +147,7 @@ __device__ __forceinline__ void wave_publish() {
 }
 
 __global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
-  __shared__ double T[NB * LDT];
+  __shared__ __attribute__((aligned(16))) double T[NB * (NB + 2)];   // rows of LDT doubles, later of NB + 2
   __shared__ __attribute__((aligned(16))) double colb[2][NB];
   __shared__ double dsh[NB];
   const int lane = threadIdx.x;
@@ -213,28 +213,31 @@ __global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
     nci = nci_next;
   }
   // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j; 1 / V[j][j] is the same factor.  All columns of V are
-  // published at once: Vt[c][l] = V[l][c] (entries below the diagonal are garbage and are not read).
+  // published at once: Vt[c][l] = V[l][c] (entries below the diagonal are garbage and are not read), with an
+  // even row stride so that a column is read two entries at a time.
+  constexpr int LDV = NB + 2;
+  double* Vt = T;
   dsh[lane] = piv > 0.0 ? 1.0 / sqrt(piv) : 1.0;
   wave_publish();
 #pragma unroll
-  for (int c = 0; c < NB; ++c) T[c * LDT + lane] = s[c] * dsh[c];
+  for (int c = 0; c < NB; ++c) Vt[c * LDV + lane] = s[c] * dsh[c];
   wave_publish();
   double wv[NB];
 #pragma clang loop unroll(full)
   for (int c = 0; c < NB; ++c) {
     double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
     {
-      double q[NB];
+      f64x2 q[NB / 2];
 #pragma unroll
-      for (int l = 0; l < NB; ++l)
-        if (l < c) q[l] = T[c * LDT + l];
+      for (int u = 0; u < NB / 2; ++u)
+        if (2 * u < c) q[u] = *reinterpret_cast<const f64x2*>(Vt + c * LDV + 2 * u);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int l = 0; l < NB; l += 4) {
-        if (l < c) p0 = fma(wv[l], q[l], p0);
-        if (l + 1 < c) p1 = fma(wv[l + 1], q[l + 1], p1);
-        if (l + 2 < c) p2 = fma(wv[l + 2], q[l + 2], p2);
-        if (l + 3 < c) p3 = fma(wv[l + 3], q[l + 3], p3);
+        if (l < c) p0 = fma(wv[l], q[l / 2][0], p0);
+        if (l + 1 < c) p1 = fma(wv[l + 1], q[l / 2][1], p1);
+        if (l + 2 < c) p2 = fma(wv[l + 2], q[l / 2 + 1][0], p2);
+        if (l + 3 < c) p3 = fma(wv[l + 3], q[l / 2 + 1][1], p3);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
