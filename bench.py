@@ -7,7 +7,7 @@ U, P <- prepare; then for every layer that reads that input  quantize_layer.
 Inputs are synthetic (paper_2504_02692_amd/synth.py) and resident in HBM before the timed
 region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 32768]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 32768] [--staged]
 """
 from __future__ import annotations
 
@@ -67,6 +67,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="llama7b")
     ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptaq_accumulate call")
+    ap.add_argument("--staged", action="store_true",
+                    help="hand the chunks to gptaq_accumulate_staged (products per 32768 pending tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -97,7 +99,7 @@ def main() -> int:
     Wwork = {iid: [W0[iid].clone() for _ in range(rounds)] for iid in inputs}
     HA = {iid: (torch.empty((n, n), device=dev), torch.empty((n, n), device=dev)) for iid, n in inputs.items()}
     nmax, mmax = max(inputs.values()), max(w.shape[0] for w in W0.values())
-    ws_acc = B.workspace(B.gptaq_accumulate_workspace_bytes(args.chunk, nmax))
+    ws_acc = B.workspace(B.gptaq_accumulate_workspace_bytes(32768 if args.staged else args.chunk, nmax))
     ws_prep = B.workspace(B.gptaq_prepare_workspace_bytes(nmax))
     ws_q = B.workspace(B.gptaq_quantize_workspace_bytes(mmax, nmax))
     outs = {iid: (torch.empty(tuple(w.shape), dtype=torch.uint8, device=dev),
@@ -114,9 +116,13 @@ def main() -> int:
             H, A = HA[iid]
             if ev: ev[0].record()
             H.zero_(); A.zero_()
+            pending = 0
             for t0 in range(0, wl.tokens, args.chunk):
                 t1 = min(wl.tokens, t0 + args.chunk)
-                B.gptaq_accumulate(X[t0:t1], Xt[t0:t1], H, A, ws_acc)
+                if args.staged:
+                    pending = B.gptaq_accumulate_staged(X[t0:t1], Xt[t0:t1], H, A, ws_acc, pending, flush=t1 == wl.tokens)
+                else:
+                    B.gptaq_accumulate(X[t0:t1], Xt[t0:t1], H, A, ws_acc)
             if ev: ev[1].record()
             B.gptaq_prepare(H, A, wl.damp, ws_prep, dead=dead[iid], info=info[iid])
             if ev: ev[2].record()
@@ -188,7 +194,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: " + ", ".join(f"{l.name} {l.m}x{l.n}" for l in wl.layers) +
                                f"; {wl.tokens} tokens; W{wl.bits} g{wl.group} {'sym' if wl.sym else 'asym'} "
-                               f"B{wl.blocksize}; accumulate chunk {args.chunk}; layers with a common input (q/k/v, gate/up) "
+                               f"B{wl.blocksize}; accumulate chunk {args.chunk}{' (staged)' if args.staged else ''}; layers with a common input (q/k/v, gate/up) "
                                f"quantised as one stacked matrix",
                    "layers_per_step": n_layers},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel<256> (accumulate: H and dXXT)",

@@ -66,6 +66,22 @@ int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, 
                      int64_t ldx, float* H, float* dXXT, int64_t ldh,
                      void* ws, size_t ws_bytes, void* stream);
 
+/* The same sums for callers that hand over small chunks, e.g. one 2048-token calibration sample at a time
+ * (Section 5.1): a product launch has a fixed cost (its read-modify-write of H and dXXT, its last round of
+ * tiles), so the chunk's operands are only appended to the workspace, and the products run once 32768
+ * tokens are pending, or when `flush` is set.
+ *   pending : HOST pointer, in/out: tokens staged in `ws` and not yet added to H and dXXT.  Start a series
+ *             with 0 and keep passing the same workspace; H and dXXT are complete after a call with
+ *             flush != 0 (which may bring tokens = 0), when *pending is 0 again.
+ *   tokens  : a multiple of 64, except in the call with flush != 0.
+ *   ws      : >= gptaq_accumulate_workspace_bytes(32768, n) bytes, 256-byte aligned; its contents belong
+ *             to the series between calls.
+ * Other arguments as for gptaq_accumulate.  A ragged chunk without flush, or *pending not a multiple of 64
+ * in [0, 32768), is GPTAQ_EDIM. */
+int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                            int64_t ldx, float* H, float* dXXT, int64_t ldh,
+                            void* ws, size_t ws_bytes, int64_t* pending, int flush, void* stream);
+
 /* Copies the upper triangle of the n x n fp32 matrix H onto its lower triangle. */
 int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
 

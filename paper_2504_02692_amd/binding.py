@@ -23,6 +23,9 @@ _SIGS = {
     "gptaq_accumulate_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64]),
     "gptaq_accumulate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
                                     _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "gptaq_accumulate_staged": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p,
+                                           _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.POINTER(_c.c_int64),
+                                           _c.c_int, _c.c_void_p]),
     "gptaq_symmetrize": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p]),
     "gptaq_prepare_workspace_bytes": (_c.c_size_t, [_c.c_int64]),
     "gptaq_prepare": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_float,
@@ -128,6 +131,27 @@ def gptaq_accumulate(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXX
         raise GptaqError("gptaq_accumulate: shape mismatch")
     _check(load().gptaq_accumulate(_ptr(X), _ptr(Xtilde), tokens, n, X.stride(0), _ptr(H), _ptr(dXXT),
                                    H.stride(0), _ptr(ws), ws.numel(), _stream()), "gptaq_accumulate")
+
+
+def gptaq_accumulate_staged(X: Optional[torch.Tensor], Xtilde: Optional[torch.Tensor], H: torch.Tensor, dXXT: torch.Tensor,
+                            ws: torch.Tensor, pending: int, flush: bool = False) -> int:
+    """Appends a chunk to the staged operands in `ws` (products run per 32768 pending tokens or on flush);
+    returns the new number of pending tokens.  X, Xtilde may be None with flush=True."""
+    _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
+    n = H.shape[0]
+    tokens, ldx = 0, n
+    if X is not None:
+        _need(X, torch.bfloat16, "X"); _need(Xtilde, torch.bfloat16, "Xtilde")
+        if X.shape != Xtilde.shape or X.shape[1] != n or X.stride(0) != Xtilde.stride(0) or X.stride(1) != 1:
+            raise GptaqError("gptaq_accumulate_staged: shape mismatch")
+        tokens, ldx = X.shape[0], X.stride(0)
+    if dXXT.shape != (n, n) or H.stride(0) != dXXT.stride(0):
+        raise GptaqError("gptaq_accumulate_staged: shape mismatch")
+    p = _c.c_int64(int(pending))
+    _check(load().gptaq_accumulate_staged(_ptr(X), _ptr(Xtilde), tokens, n, ldx, _ptr(H), _ptr(dXXT), H.stride(0),
+                                          _ptr(ws), ws.numel() * ws.element_size(), _c.byref(p), int(bool(flush)),
+                                          _stream()), "gptaq_accumulate_staged")
+    return p.value
 
 
 def gptaq_symmetrize(H: torch.Tensor) -> None:

@@ -22,7 +22,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 __global__ __launch_bounds__(256) void split_transpose_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xt, int64_t ldx,
     int tokens, int n, uint16_t* __restrict__ oX, uint16_t* __restrict__ oHi,
-    uint16_t* __restrict__ oLo, int64_t ldo /* padded rows */) {
+    uint16_t* __restrict__ oLo, int64_t ldo /* padded rows */, int tile0 /* first 64-token tile of the output */) {
   constexpr int LS = 72;                                  // padded LDS row, 144 bytes
   __shared__ __attribute__((aligned(16))) uint16_t sx[64 * LS], sh[64 * LS], sl[64 * LS];
   const int n0 = blockIdx.x * 64, t0 = blockIdx.y * 64;
@@ -52,7 +52,7 @@ __global__ __launch_bounds__(256) void split_transpose_kernel(
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     const int nl = r + 32 * p;
-    const int64_t g = (((int64_t)blockIdx.y * 2 + (c >> 2)) * ldo + n0 + nl) * 32 + (c & 3) * 8;   // k-tile-major
+    const int64_t g = (((int64_t)(blockIdx.y + tile0) * 2 + (c >> 2)) * ldo + n0 + nl) * 32 + (c & 3) * 8;   // k-tile-major
     *reinterpret_cast<u32x4*>(oX + g) = *reinterpret_cast<const u32x4*>(sx + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oHi + g) = *reinterpret_cast<const u32x4*>(sh + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oLo + g) = *reinterpret_cast<const u32x4*>(sl + nl * LS + c * 8);
@@ -82,6 +82,26 @@ extern "C" size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n) {
   return (size_t)(3 * padded_n(n) * c * 2);
 }
 
+// H += X X^T (upper tiles) and dXXT += (hi + lo) X^T over cp tokens of split operands, as one launch.
+static hipError_t launch_products(const uint16_t* oX, const uint16_t* oHi, const uint16_t* oLo, int64_t np, int64_t cp,
+                                  int64_t n, float* H, float* dXXT, int64_t ldh, hipStream_t s) {
+  const int tile = gemm_tile_for(n, n);
+  GemmBatch b{};
+  b.nprob = 2;
+  b.tile = tile;
+  GemmProblem& a = b.p[0];
+  a.C = dXXT; a.ldc = ldh; a.M = (int)n; a.N = (int)n; a.K = (int)cp;
+  a.tiles_m = a.tiles_n = (int)(np / tile);
+  a.kind = 1; a.nterm = 1; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
+  a.term[0] = {{oHi, oLo}, {oX, oX}, 32, 32, np * 32, np * 32};
+  GemmProblem& h = b.p[1];
+  h = a;
+  h.C = H; h.kind = 0; h.tile_mode = 2;
+  h.term[0] = {{oX, oX}, {oX, oX}, 32, 32, np * 32, np * 32};
+  ProfScope ps(kProfAccumGemm, s);
+  return launch_gemm(b, s);
+}
+
 extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens,
                                 int64_t n, int64_t ldx, float* H, float* dXXT, int64_t ldh,
                                 void* ws, size_t ws_bytes, void* stream) {
@@ -93,7 +113,6 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
   if ((uintptr_t)ws & 255) return GPTAQ_EWORKSPACE;
   if (tokens == 0) return GPTAQ_OK;
   hipStream_t s = (hipStream_t)stream;
-  const int tile = gemm_tile_for(n, n);
   const int64_t np = padded_n(n);
   int64_t cmax = (int64_t)(ws_bytes / (size_t)(6 * np)) / 64 * 64;
   if (cmax < 64) return GPTAQ_EWORKSPACE;
@@ -108,28 +127,52 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
       ProfScope ps(kProfAccumSplit, s);
       hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)),
                          dim3(256), 0, s, X + t0 * ldx, Xtilde + t0 * ldx, ldx, (int)c, (int)n,
-                         oX, oHi, oLo, np);
+                         oX, oHi, oLo, np, 0);
     }
     GPTAQ_LAUNCH_CHECK();
-    GemmBatch b{};
-    b.nprob = 2;
-    b.tile = tile;
-    GemmProblem& a = b.p[0];
-    a.C = dXXT; a.ldc = ldh; a.M = (int)n; a.N = (int)n; a.K = (int)cp;
-    a.tiles_m = a.tiles_n = (int)(np / tile);
-    a.kind = 1; a.nterm = 1; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
-    a.term[0] = {{oHi, oLo}, {oX, oX}, 32, 32, np * 32, np * 32};
-    GemmProblem& h = b.p[1];
-    h = a;
-    h.C = H; h.kind = 0; h.tile_mode = 2;
-    h.term[0] = {{oX, oX}, {oX, oX}, 32, 32, np * 32, np * 32};
-    hipError_t e;
-    {
-      ProfScope ps(kProfAccumGemm, s);
-      e = launch_gemm(b, s);
-    }
+    hipError_t e = launch_products(oX, oHi, oLo, np, cp, n, H, dXXT, ldh, s);
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   }
+  return GPTAQ_OK;
+}
+
+extern "C" int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx,
+                                       float* H, float* dXXT, int64_t ldh, void* ws, size_t ws_bytes, int64_t* pending,
+                                       int flush, void* stream) {
+  constexpr int64_t CAP = 32768;                 // tokens per product launch
+  if (!H || !dXXT || !ws || !pending || (tokens > 0 && (!X || !Xtilde))) return GPTAQ_ENULL;
+  if (tokens < 0 || n <= 0 || n % 8 || ldx < n || ldx % 8 || ldh < n || n > (1 << 20) || tokens > (int64_t)1 << 30 ||
+      *pending < 0 || *pending >= CAP || *pending % 64 || (!flush && tokens % 64))
+    return GPTAQ_EDIM;
+  if (tokens > 0 && (((uintptr_t)X | (uintptr_t)Xtilde) & 15)) return GPTAQ_EDIM;
+  const int64_t np = padded_n(n);
+  if (((uintptr_t)ws & 255) || ws_bytes < (size_t)(6 * np * CAP)) return GPTAQ_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  uint16_t *oX = (uint16_t*)ws, *oHi = oX + np * CAP, *oLo = oHi + np * CAP;
+  auto products = [&](int64_t cp) { return launch_products(oX, oHi, oLo, np, cp, n, H, dXXT, ldh, s); };
+  int64_t done = 0, pend = *pending;
+  while (done < tokens) {
+    const int64_t take = tokens - done < CAP - pend ? tokens - done : CAP - pend, cp = round_up(take, 64);
+    {
+      ProfScope ps(kProfAccumSplit, s);
+      hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)), dim3(256), 0, s,
+                         X + done * ldx, Xtilde + done * ldx, ldx, (int)take, (int)n, oX, oHi, oLo, np, (int)(pend / 64));
+    }
+    GPTAQ_LAUNCH_CHECK();
+    done += take;
+    pend += cp;                                    // (only the chunk that comes with flush may be ragged: it is the last)
+    if (pend >= CAP) {
+      hipError_t e = products(CAP);
+      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+      pend = 0;
+    }
+  }
+  if (flush && pend > 0) {
+    hipError_t e = products(pend);
+    if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+    pend = 0;
+  }
+  *pending = pend;
   return GPTAQ_OK;
 }
 

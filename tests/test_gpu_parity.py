@@ -50,6 +50,32 @@ def test_accumulate_ragged_shapes(tokens, n):
     assert PU.rel_fro(Ad.cpu().numpy(), A) <= 1e-5
 
 
+def test_accumulate_staged_small_chunks():
+    # 2048-token samples (Section 5.1) staged into 32768-token product launches: 34 samples + a ragged
+    # tail cross one launch boundary and leave a partial launch for the flush
+    from paper_2504_02692_amd import binding as B
+    n, chunk, tokens = 200, 2048, 34 * 2048 + 77
+    Xb, Xtb = synth.make_activations(tokens, n, 6, "staged", 3, 20.0)
+    H, A = O.accumulate(Xb, Xtb)
+    X, Xt = PU.to_dev_bf16(Xb), PU.to_dev_bf16(Xtb)
+    Hd = torch.zeros((n, n), device="cuda"); Ad = torch.zeros_like(Hd)
+    ws = B.workspace(B.gptaq_accumulate_workspace_bytes(32768, n))
+    pending, seen = 0, []
+    for t0 in range(0, tokens, chunk):
+        last = t0 + chunk >= tokens
+        pending = B.gptaq_accumulate_staged(X[t0:t0 + chunk], Xt[t0:t0 + chunk], Hd, Ad, ws, pending, flush=last)
+        seen.append(pending)
+    assert seen[:16] == [2048 * (i + 1) % 32768 for i in range(16)] and seen[-1] == 0
+    assert PU.rel_fro(upper_to_full(Hd), H) <= 1e-5
+    assert PU.rel_fro(Ad.cpu().numpy(), A) <= 1e-5
+    # the same launches as direct calls on 32768-token chunks: bit-identical sums
+    H2, A2 = PU.gpu_accumulate(Xb, Xtb, chunks=[0, 32768, 65536, tokens])
+    assert torch.equal(Hd, H2) and torch.equal(Ad, A2)
+    # a flush with nothing to add changes nothing
+    assert B.gptaq_accumulate_staged(None, None, Hd, Ad, ws, 0, flush=True) == 0
+    assert torch.equal(Hd, H2)
+
+
 def test_symmetrize(c1):
     from paper_2504_02692_amd import binding as B
     Hd, _ = PU.gpu_accumulate(c1["Xb"], c1["Xtb"])
