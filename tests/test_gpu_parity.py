@@ -71,6 +71,10 @@ def test_accumulate_staged_small_chunks():
     # the same launches as direct calls on 32768-token chunks: bit-identical sums
     H2, A2 = PU.gpu_accumulate(Xb, Xtb, chunks=[0, 32768, 65536, tokens])
     assert torch.equal(Hd, H2) and torch.equal(Ad, A2)
+    # one call with everything (it crosses two launch boundaries inside the call)
+    H3 = torch.zeros_like(Hd); A3 = torch.zeros_like(Hd)
+    assert B.gptaq_accumulate_staged(X, Xt, H3, A3, ws, 0, flush=True) == 0
+    assert torch.equal(H3, H2) and torch.equal(A3, A2)
     # a flush with nothing to add changes nothing
     assert B.gptaq_accumulate_staged(None, None, Hd, Ad, ws, 0, flush=True) == 0
     assert torch.equal(Hd, H2)
