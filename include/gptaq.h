@@ -37,6 +37,7 @@ extern "C" {
 #define GPTAQ_EUNSUPPORTED  -3   /* bits/group/blocksize combination not supported         */
 #define GPTAQ_EWORKSPACE    -4   /* workspace too small or misaligned (needs 256 B)        */
 #define GPTAQ_ELAUNCH       -5   /* the HIP runtime refused a launch; see gptaq_last_hip_error */
+#define GPTAQ_ETOOLARGE     -6   /* beyond the fixed capacity of an entry point that allocates nothing */
 
 /* Human-readable text for a status code. */
 const char* gptaq_status_string(int status);
@@ -65,6 +66,18 @@ size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n);
 int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
                      int64_t ldx, float* H, float* dXXT, int64_t ldh,
                      void* ws, size_t ws_bytes, void* stream);
+
+/* gptaq_accumulate for callers that cannot allocate device memory or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same sums, same kernels; the
+ * split operands go to a 32 MiB scratch array that is part of the library's code object (one copy per GPU,
+ * held until the process ends), and the call makes no hipMalloc, hipFree or other allocating call.
+ * The chunk is processed in passes of as many tokens as fit:
+ * floor(32 MiB / (6 * round_up(n, tile))) rounded down to 64 (1344 tokens at n = 4096).
+ *   n > 16384 returns GPTAQ_ETOOLARGE before anything is launched; other argument errors as gptaq_accumulate.
+ *   Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two streams, two
+ *   host threads) race.  Nothing in the array has to be cleared between calls. */
+int gptaq_accumulate_noalloc(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                             int64_t ldx, float* H, float* dXXT, int64_t ldh, void* stream);
 
 /* The same sums for callers that hand over small chunks, e.g. one 2048-token calibration sample at a time
  * (Section 5.1): a product launch has a fixed cost (its read-modify-write of H and dXXT, its last round of

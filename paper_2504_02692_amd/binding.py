@@ -23,6 +23,8 @@ _SIGS = {
     "gptaq_accumulate_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64]),
     "gptaq_accumulate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
                                     _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "gptaq_accumulate_noalloc": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
+                                            _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gptaq_accumulate_staged": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p,
                                            _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.POINTER(_c.c_int64),
                                            _c.c_int, _c.c_void_p]),
@@ -131,6 +133,18 @@ def gptaq_accumulate(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXX
         raise GptaqError("gptaq_accumulate: shape mismatch")
     _check(load().gptaq_accumulate(_ptr(X), _ptr(Xtilde), tokens, n, X.stride(0), _ptr(H), _ptr(dXXT),
                                    H.stride(0), _ptr(ws), ws.numel(), _stream()), "gptaq_accumulate")
+
+
+def gptaq_accumulate_noalloc(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXXT: torch.Tensor) -> None:
+    """gptaq_accumulate on the library's built-in scratch array (no workspace, no allocation; n <= 16384)."""
+    _need(X, torch.bfloat16, "X"); _need(Xtilde, torch.bfloat16, "Xtilde")
+    _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
+    tokens, n = X.shape
+    if Xtilde.shape != X.shape or Xtilde.stride(0) != X.stride(0) or H.shape != (n, n) or dXXT.shape != (n, n) \
+            or H.stride(0) != dXXT.stride(0):
+        raise GptaqError("gptaq_accumulate_noalloc: shape mismatch")
+    _check(load().gptaq_accumulate_noalloc(_ptr(X), _ptr(Xtilde), tokens, n, X.stride(0), _ptr(H), _ptr(dXXT),
+                                           H.stride(0), _stream()), "gptaq_accumulate_noalloc")
 
 
 def gptaq_accumulate_staged(X: Optional[torch.Tensor], Xtilde: Optional[torch.Tensor], H: torch.Tensor, dXXT: torch.Tensor,

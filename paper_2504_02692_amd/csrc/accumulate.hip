@@ -8,8 +8,14 @@
 // (2) One launch of the MFMA GEMM computes dXXT += hi X^T + lo X^T on all tiles and
 // H += X X^T on the tiles that touch the upper triangle.
 #include "common.h"
+#include <mutex>
 
 namespace gptaq {
+
+// Workspace of gptaq_accumulate_noalloc: one copy per GPU, owned by the code object, never freed.
+constexpr size_t kScratchBytes = (size_t)32 << 20;
+constexpr int64_t kScratchMaxN = 16384;                   // 6 * 16384 * 320 tokens still fit
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
@@ -102,9 +108,8 @@ static hipError_t launch_products(const uint16_t* oX, const uint16_t* oHi, const
   return launch_gemm(b, s);
 }
 
-extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens,
-                                int64_t n, int64_t ldx, float* H, float* dXXT, int64_t ldh,
-                                void* ws, size_t ws_bytes, void* stream) {
+static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx, float* H,
+                           float* dXXT, int64_t ldh, void* ws, size_t ws_bytes, void* stream) {
   if (!X || !Xtilde || !H || !dXXT || !ws) return GPTAQ_ENULL;
   if (tokens < 0 || n <= 0 || n % 8 || ldx < n || ldx % 8 || ldh < n || n > (1 << 20) ||
       tokens > (int64_t)1 << 30)
@@ -134,6 +139,39 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   }
   return GPTAQ_OK;
+}
+
+extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens,
+                                int64_t n, int64_t ldx, float* H, float* dXXT, int64_t ldh,
+                                void* ws, size_t ws_bytes, void* stream) {
+  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, ws, ws_bytes, stream);
+}
+
+// Device address of this GPU's copy of `scratch`, looked up once per device (with that device current).
+// In host code the array's name is only a handle for this lookup, never an address to hand to a kernel.
+static void* scratch_of_current_device() {
+  static std::mutex mu;
+  static void* ptr[64] = {nullptr};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) { set_last_hip_error(e); return nullptr; }
+    ptr[dev] = p;
+  }
+  return ptr[dev];
+}
+
+extern "C" int gptaq_accumulate_noalloc(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                                        int64_t ldx, float* H, float* dXXT, int64_t ldh, void* stream) {
+  if (n > kScratchMaxN) return GPTAQ_ETOOLARGE;
+  void* ws = scratch_of_current_device();
+  if (!ws) return GPTAQ_ELAUNCH;
+  // every pass overwrites the part of the scratch it reads (zero padding included), so nothing of the last
+  // call's contents is ever read and nothing has to be cleared
+  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, ws, kScratchBytes, stream);
 }
 
 extern "C" int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx,

@@ -60,6 +60,7 @@ extern "C" const char* gptaq_status_string(int status) {
     case GPTAQ_EUNSUPPORTED: return "unsupported bits/group/blocksize combination";
     case GPTAQ_EWORKSPACE: return "workspace too small or not 256-byte aligned";
     case GPTAQ_ELAUNCH: return "HIP launch failed";
+    case GPTAQ_ETOOLARGE: return "problem larger than the library's built-in scratch buffer allows";
     default: return "unknown status";
   }
 }
