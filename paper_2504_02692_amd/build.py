@@ -9,7 +9,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgptaq.so")
-SOURCES = ["status.hip", "gemm_bf16.hip", "gemm_i8s.hip", "accumulate.hip", "prepare.hip", "quantize.hip", "act_order.hip", "upstream.hip", "peaks.hip"]
+SOURCES = ["status.hip", "gemm_bf16.hip", "gemm_i8s.hip", "accumulate.hip", "prepare.hip", "quantize.hip", "quantize_sb.hip", "act_order.hip", "upstream.hip", "peaks.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

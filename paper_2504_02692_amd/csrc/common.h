@@ -88,6 +88,25 @@ hipError_t launch_slice_i8(const double* src, int64_t sr, int64_t sk, int R, int
 hipError_t launch_gemm_i8s(const I8Operand& A, int a_row0, const I8Operand& B, int b_row0, double* C, int64_t ldc, int M,
                            int N, int K, double alpha, int beta, int upper_only, hipStream_t s);
 
+// Column loop + in-super-block updates of a whole super-block in one launch (quantize_sb.hip).
+constexpr int kSbCols = 1024;       // columns per super-block
+struct SbArgs {
+  float* W; int64_t ldw; int m, n;
+  int sb0, sbw;                      // first column and width (<= kSbCols) of the super-block
+  const float* U; const float* P; int64_t ldh;
+  const uint16_t* Nop[4];            // launch_near_operands output: U hi, U lo, P hi, P lo
+  const uint8_t* dead;
+  float maxq; int group, sym, G, terms;
+  float* scales; float* zeros; uint8_t* codes;
+  uint16_t *Eh, *El, *Vh, *Vl;       // -E and V of the super-block as bf16 hi/lo, row stride ldev (NULL: not wanted)
+  int64_t ldev;
+  int fast_rows;                     // rows of W and of codes may be stored 16 bytes at a time
+};
+// N4: four buffers of (kSbCols / 16) * kSbCols * 16 bf16 each.
+hipError_t launch_near_operands(const float* U, const float* P, int64_t ldh, int n, int sb0, int sbw, uint16_t* const* N4,
+                                hipStream_t s);
+hipError_t launch_quant_sb(const SbArgs& a, hipStream_t s);
+
 void set_last_hip_error(hipError_t e);
 
 // Optional per-kernel timing with HIP events (gptaq_profile_* in the public header).

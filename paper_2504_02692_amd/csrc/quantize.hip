@@ -327,8 +327,9 @@ QLayout q_layout(int64_t m, int64_t n) {
   for (int i = 0; i < 12; ++i) {
     L.off[i] = o;
     // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of its updates (all columns from the
-    // super-block's first on, plus a tile of padding rows); 8-11: unused
-    o += (size_t)(i < 4 ? L.mp * KS * 2 : i < 8 ? (L.np + 256) * KS * 2 : (int64_t)256);
+    // super-block's first on, plus a tile of padding rows); 8-11: left operands of the updates inside a
+    // super-block (quantize_sb.hip)
+    o += (size_t)(i < 4 ? L.mp * KS * 2 : i < 8 ? (L.np + 256) * KS * 2 : (int64_t)(kSbCols / 16) * kSbCols * 16 * 2);
   }
   L.total = o;
   return L;
@@ -371,6 +372,95 @@ extern "C" size_t gptaq_quantize_workspace_bytes(int64_t m, int64_t n) {
   return q_layout(m, n).total;
 }
 
+namespace gptaq {
+// Dead inputs (zero Hessian diagonal): their columns of W count as 0 (GPTQ's rule, which the paper defers to).
+// grid: one workgroup per 64 columns; it returns at once unless one of its columns is dead.
+__global__ __launch_bounds__(256) void zero_dead_columns_kernel(float* W, int64_t ldw, int m, int n, const uint8_t* dead) {
+  __shared__ int any;
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const bool d = c < n && dead[c];
+  if (threadIdx.x == 0) any = 0;
+  __syncthreads();
+  if (d) any = 1;
+  __syncthreads();
+  if (!any) return;
+  for (int r = threadIdx.x >> 6; r < m; r += 4)
+    if (d) W[(int64_t)r * ldw + c] = 0.f;
+}
+}  // namespace gptaq
+
+// Algorithm 1, lines 5-13 with one launch of quant_sb_kernel per super-block (column steps and every update
+// inside the super-block) followed by one GEMM for the columns after it.  The result does not depend on the
+// blocking (Eq. 18 only re-associates sums), so the caller's blocksize is not used here.
+static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P, int64_t ldh,
+                             const uint8_t* dead, int bits, int group, int sym, uint8_t* codes, float* scales,
+                             float* zeros, uint16_t* const* buf, hipStream_t s, int terms) {
+  constexpr int64_t LDE = kSbCols;               // row stride of the -E / V buffers and of the far right operands
+  if (dead) {
+    hipLaunchKernelGGL(zero_dead_columns_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, s, W, ldw, (int)m, (int)n, dead);
+    GPTAQ_LAUNCH_CHECK();
+  }
+  SbArgs a;
+  a.W = W; a.ldw = ldw; a.m = (int)m; a.n = (int)n;
+  a.U = U; a.P = (terms & 2) ? P : U; a.ldh = ldh;
+  for (int i = 0; i < 4; ++i) a.Nop[i] = buf[8 + i];
+  a.dead = dead;
+  a.maxq = (float)((1 << bits) - 1); a.group = group; a.sym = sym; a.terms = terms;
+  a.G = group > 0 ? (int)(n / group) : 1;
+  a.scales = scales; a.zeros = zeros; a.codes = codes;
+  a.ldev = LDE;
+  a.fast_rows = (ldw % 4 == 0) && (((uintptr_t)W & 15) == 0) && (n % 16 == 0) && (((uintptr_t)codes & 15) == 0);
+  if (group <= 0) {
+    hipLaunchKernelGGL(row_params_kernel, dim3((unsigned)((m + 3) / 4)), dim3(256), 0, s, W, ldw, (int)m, (int)n,
+                       (const uint8_t*)nullptr, a.maxq, sym, 0, 0, scales, zeros);
+    GPTAQ_LAUNCH_CHECK();
+  }
+  for (int64_t sb0 = 0; sb0 < n; sb0 += kSbCols) {
+    const int64_t sb_end = n < sb0 + kSbCols ? n : sb0 + kSbCols;
+    const bool far = terms != 0 && sb_end < n;
+    a.sb0 = (int)sb0; a.sbw = (int)(sb_end - sb0);
+    a.Eh = far ? buf[0] : nullptr; a.El = buf[1]; a.Vh = buf[2]; a.Vl = buf[3];
+    if (terms != 0) {
+      ProfScope ps(kProfTrailSplit, s);
+      hipError_t e = launch_near_operands(U, (terms & 2) ? P : nullptr, ldh, (int)n, (int)sb0, a.sbw, buf + 8, s);
+      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+      if (far) {
+        // right operands of the far update: rows of U and P of this super-block, columns after it, transposed
+        // to (column x K) and split; a GEMM reads whole tiles of rows, hence the zero rows past n
+        const int64_t rows = round_up(n - sb_end, 256) + 256;
+        hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(rows / 64), 2, (unsigned)(kSbCols / QB)), dim3(256),
+                           0, s, U, (terms & 2) ? P : U, ldh, (int)n, (int)sb0, QB, (int)sb_end, (int)n, buf[4], buf[5],
+                           buf[6], buf[7], LDE);
+        GPTAQ_LAUNCH_CHECK();
+      }
+    }
+    {
+      ProfScope ps(kProfColumnLoop, s);
+      hipError_t e = launch_quant_sb(a, s);
+      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+    }
+    if (far) {
+      const int64_t nt = n - sb_end;
+      const int tile = gemm_tile_for(m, nt);
+      GemmBatch b{};
+      b.nprob = 1; b.tile = tile;
+      GemmProblem& g = b.p[0];
+      g.C = W + sb_end; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = kSbCols;
+      g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(round_up(nt, tile) / tile);
+      g.kind = 2; g.nterm = 0; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
+      if (terms & 1) g.term[g.nterm++] = {{buf[0], buf[1]}, {buf[4], buf[5]}, LDE, LDE, 32, 32};
+      if (terms & 2) g.term[g.nterm++] = {{buf[2], buf[3]}, {buf[6], buf[7]}, LDE, LDE, 32, 32};
+      hipError_t e;
+      {
+        ProfScope ps(kProfTrailGemm, s);
+        e = launch_gemm(b, s);
+      }
+      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+    }
+  }
+  return GPTAQ_OK;
+}
+
 static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
                                int64_t ldh, const uint8_t* dead, int bits, int group, int sym, int blocksize,
                                uint8_t* codes, float* scales, float* zeros, void* ws, size_t ws_bytes,
@@ -388,6 +478,11 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
   unsigned char* base = (unsigned char*)ws;
   uint16_t* buf[12];
   for (int i = 0; i < 12; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
+
+  // The super-block kernel takes groups that tile its 16/32/128-column pieces; the clip-range search and other
+  // group sizes go through the block-by-block kernels below.
+  if (mse_steps == 0 && (group <= 0 || group == 16 || group == 32 || group == 64 || group == 128))
+    return quantize_layer_sb(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, codes, scales, zeros, buf, s, terms);
 
   QuantArgs a;
   a.W = W; a.ldw = ldw; a.m = (int)m; a.n = (int)n;
