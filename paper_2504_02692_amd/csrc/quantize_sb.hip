@@ -16,16 +16,18 @@
 //   * the columns after the super-block: one GEMM per super-block, outside this kernel, from the
 //     -E and V this kernel leaves behind in the GEMM's operand format.
 //
-// Register layout.  Wave w of the workgroup holds, for every 128-column block b of the super-block,
-// the 32 columns 128 b + 32 w .. + 31 of all 64 rows as two 32 x 32 MFMA accumulator tiles of the
-// TRANSPOSED product  W^T += [U; P]^T [-E | V]^T :  lane l, register v of tile rh holds row
-// 32 rh + l % 32, column 8 (v / 4) + 4 (l / 32) + v % 4 of the 32.  v_permlane32_swap of the
-// registers of the two tiles turns that into "lane = row" for the sequential steps.
-// After the last sub-block of a 128-column block every wave moves its tiles down by one, so the block being
-// worked on always sits in the same registers (the code has one copy of everything, no 7-way switches).
-// The wave that holds a sub-block's columns runs its 16 column steps while the others wait (they
-// fetch the next diagonal pieces); then every wave applies the sub-block's update to its own
-// later columns.  One workgroup barrier per sub-block.
+// Who holds what.  The super-block is eight blocks of 128 columns; wave w holds blocks w and w + 4, each as
+// four 32-column pieces of two 32 x 32 MFMA accumulator tiles (rows 0-31 and 32-63) of the TRANSPOSED
+// product  W^T += [U; P]^T [-E | V]^T :  lane l, register v of a tile holds row l % 32 of the tile,
+// column 8 (v / 4) + 4 (l / 32) + v % 4 of the piece.  v_permlane32_swap of the registers of the two
+// tiles turns that into "one row per lane" for the sequential steps.
+// While block b is worked on, the wave that holds it (the owner) runs the column steps of its eight
+// sub-blocks and updates the rest of the block; the other three waves have no sequential work in
+// that time: they apply each sub-block's update to the later blocks they hold, under the owner's next
+// column steps.  One workgroup barrier per sub-block publishes its -E and V.
+// The pieces are kept in a fixed place: the owner moves its pieces down by one when a piece is
+// finished and its second block into the first one's registers when the block is finished, so every
+// register index in the code is static.
 #include "common.h"
 #include <mutex>
 
@@ -90,31 +92,17 @@ __global__ __launch_bounds__(256) void near_operands_kernel(const float* U, cons
 }
 
 // ---------------------------------------------------------------------------------------------------
-// Left operands of a sub-block's update, staged per wave: piece i (32 columns) x {U hi, U lo, P hi, P lo} x 1 KB,
+// Left operands of a sub-block's update, staged per wave: piece (32 columns) x {U hi, U lo, P hi, P lo} x 1 KB,
 // written by global -> LDS loads one sub-block ahead of their use and read back by the lane that requested them.
-constexpr int kSbStage = kSbBlocks * 4 * 1024;
+constexpr int kSbPieces = 8;                     // per wave: 2 blocks x 4 pieces
+constexpr int kSbStage = kSbPieces * 4 * 1024;
+static_assert(kSbBlocks == 8, "two blocks per wave, four waves");
 struct SbShared {
   // operands [-E | V]^T of a sub-block's update, in MFMA fragment order: [buffer][term][hi/lo][row half][k chunk][row]
   u32x4 frag[2][2][2][2][2][32];
   float Ud[2][kSub][kSub], Pd[2][kSub][kSub];     // diagonal pieces of U and P (fp32), double-buffered
   float dinv[2][kSub];                            // 1 / U_jj
-  float mn[4][64], mx[4][64];                     // per wave, per row: range of its columns of the group
-  float sc[64], zr[64];                           // the current group's grid, per row
 };
-
-template <int HALF>
-__device__ __forceinline__ void sb_extract(const f32x16 (&acc)[kSbBlocks][2], float (&w)[kSub]) {
-  // registers 8 HALF .. 8 HALF + 7 of the current block's two tiles -> the 16 columns of the sub-block, one row per lane
-#pragma unroll
-  for (int vv = 0; vv < 8; ++vv) {
-    const float a0 = acc[0][0][8 * HALF + vv];
-    const float a1 = acc[0][1][8 * HALF + vv];
-    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a1), false, false);
-    const int c = 8 * (vv >> 2) + (vv & 3);
-    w[c] = __uint_as_float(r[0]);          // lanes 0-31: tile 0, lanes 32-63: tile 1, columns of lane half 0
-    w[c + 4] = __uint_as_float(r[1]);      // the columns lane half 1 held
-  }
-}
 
 // 1 KB per wavefront from global memory straight into LDS: lane l's 16 bytes land at lds + 16 l.
 __device__ __forceinline__ void sb_load_lds(const uint16_t* src, unsigned char* lds) {
@@ -129,6 +117,57 @@ __device__ __forceinline__ void sb_barrier() {
   asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
   __builtin_amdgcn_s_barrier();
   asm volatile("" ::: "memory");
+}
+
+// Where this wave's pieces are while sub-block x is worked on.
+struct SbGeo {
+  int b, r, half, owner;      // block of the sub-block, finished pieces of that block, first/second half of a piece, owning wave
+  int cur0;                   // block in slot 0 (the wave's first block until it has finished it, then its second)
+  bool two;                   // slot 1 still holds the second block
+  uint32_t active;            // bit 4 s + i: piece i of slot s takes the update of sub-block x
+};
+__device__ __forceinline__ SbGeo sb_geo(int x, int wave, int sbw, int nev, int terms) {
+  SbGeo g;
+  const int eb = x & 7;
+  g.b = x >> 3; g.r = eb >> 1; g.half = eb & 1; g.owner = g.b & 3;
+  g.cur0 = g.b > wave ? wave + 4 : wave;
+  g.two = g.b <= wave;
+  g.active = 0;
+  if (terms != 0 && x + 1 < nev) {
+    // pieces of block B that exist (the super-block may be narrower than 1024 columns)
+    auto pieces_in = [&](int B) { return max(0, min(4, (sbw - 128 * B + 31) >> 5)); };
+    uint32_t m0;
+    if (g.cur0 == g.b) {
+      // the block being worked on: its first g.r pieces are finished and have made room, so piece i is the block's
+      // piece i + g.r; the piece the sub-block lies in takes the update of its second half only
+      const int cnt = pieces_in(g.b) - g.r;
+      m0 = cnt > 0 ? ((1u << cnt) - 1u) & ~(uint32_t)g.half : 0u;
+    } else {
+      m0 = g.cur0 > g.b ? (1u << pieces_in(g.cur0)) - 1u : 0u;
+    }
+    const uint32_t m1 = g.two ? (1u << pieces_in(wave + 4)) - 1u : 0u;     // (wave + 4 > b whenever slot 1 is in use)
+    g.active = m0 | (m1 << 4);
+  }
+  return g;
+}
+// first super-block column of piece i of slot s
+__device__ __forceinline__ int sb_piece_col(const SbGeo& g, int wave, int s, int i) {
+  const int B = s == 0 ? g.cur0 : wave + 4;
+  return 128 * B + 32 * (B == g.b ? i + g.r : i);
+}
+
+template <int HALF>
+__device__ __forceinline__ void sb_extract(const f32x16 (&acc)[2][4][2], float (&w)[kSub]) {
+  // registers 8 HALF .. 8 HALF + 7 of the current piece's two tiles -> the 16 columns of the sub-block, one row per lane
+#pragma unroll
+  for (int vv = 0; vv < 8; ++vv) {
+    const float a0 = acc[0][0][0][8 * HALF + vv];
+    const float a1 = acc[0][0][1][8 * HALF + vv];
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(a0), __float_as_uint(a1), false, false);
+    const int c = 8 * (vv >> 2) + (vv & 3);
+    w[c] = __uint_as_float(r[0]);          // lanes 0-31: tile 0, lanes 32-63: tile 1, columns of lane half 0
+    w[c + 4] = __uint_as_float(r[1]);      // the columns lane half 1 held
+  }
 }
 
 // FAST: rows of W and of the codes are 16-byte aligned and n is a multiple of 16 (vector loads and stores).
@@ -146,45 +185,36 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
 
   // ---- W -> accumulators.  Out-of-range elements read a clamped (valid) address and are replaced by 0,
   // so the loads need no branches.  Dead inputs were zeroed in W before this kernel.
-  f32x16 acc[kSbBlocks][2];
-  if (FAST) {
+  f32x16 acc[2][4][2];
 #pragma unroll
-    for (int b = 0; b < kSbBlocks; ++b)
+  for (int s = 0; s < 2; ++s)
 #pragma unroll
-      for (int rh = 0; rh < 2; ++rh) {
-        const int row = row0 + 32 * rh + l32;
-        const float* src = a.W + (int64_t)min(row, a.m - 1) * a.ldw + a.sb0;
-#pragma unroll
-        for (int vq = 0; vq < 4; ++vq) {
-          const int c = 128 * b + 32 * wave + 8 * vq + 4 * lh;            // super-block column of element 0
-          const bool ok = row < a.m && c < sbw;
-          const f32x4 x = *reinterpret_cast<const f32x4*>(src + min(c, sbw - 4));
-#pragma unroll
-          for (int i = 0; i < 4; ++i) acc[b][rh][4 * vq + i] = ok ? x[i] : 0.f;
-        }
-        __builtin_amdgcn_sched_barrier(0);                // (all 64 loads in flight at once would need 256 registers)
-      }
-  } else {
-#pragma unroll
-    for (int b = 0; b < kSbBlocks; ++b)
+    for (int i = 0; i < 4; ++i) {
 #pragma unroll
       for (int rh = 0; rh < 2; ++rh) {
         const int row = row0 + 32 * rh + l32;
         const float* src = a.W + (int64_t)min(row, a.m - 1) * a.ldw + a.sb0;
 #pragma unroll
         for (int vq = 0; vq < 4; ++vq) {
-          const int c = 128 * b + 32 * wave + 8 * vq + 4 * lh;
+          const int c = 128 * (wave + 4 * s) + 32 * i + 8 * vq + 4 * lh;    // super-block column of element 0
+          if (FAST) {
+            const bool ok = row < a.m && c < sbw;
+            const f32x4 x = *reinterpret_cast<const f32x4*>(src + min(c, sbw - 4));
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const float x = src[min(c + i, sbw - 1)];
-            acc[b][rh][4 * vq + i] = (row < a.m && c + i < sbw) ? x : 0.f;
+            for (int q = 0; q < 4; ++q) acc[s][i][rh][4 * vq + q] = ok ? x[q] : 0.f;
+          } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const float x = src[min(c + q, sbw - 1)];
+              acc[s][i][rh][4 * vq + q] = (row < a.m && c + q < sbw) ? x : 0.f;
+            }
           }
         }
-        __builtin_amdgcn_sched_barrier(0);
       }
-  }
+      __builtin_amdgcn_sched_barrier(0);                  // (all 64 loads in flight at once would need 256 registers)
+    }
 
-  // ---- per-row grid
+  // ---- per-row grid (one row per lane); for grouped grids it is renewed by the owner at every group start
   float sc = 1.f, zr = 0.f, isc = 1.f;
   if (a.group <= 0) {
     const int row = row0 + lane;
@@ -211,21 +241,15 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
       sh.dinv[x & 1][j] = d != 0.f ? 1.f / d : 0.f;
     }
   };
-  if (wave == 1) load_diag(0, 0);
-  if (wave == 2) load_diag(0, 1);
-  __syncthreads();
 
   // Requests the left operands of sub-block x's update for this wave's pieces: they depend on U and P only, so
   // they are fetched a whole sub-block ahead (global -> LDS, no registers) and have the column steps' time to land.
-  auto request_left = [&](int x) {
-    if (a.terms == 0 || x + 1 >= nev) return;
-    const int bx = x >> 3;
-    const int lo = 128 * bx + 32 * wave + 32 > kSub * (x + 1) ? 0 : 1;
-    const int hi = min(kSbBlocks - 1, (sbw - 32 * wave + 127) / 128 - 1) - bx;
+  auto request_left = [&](int x, const SbGeo& g) {
     const uint32_t lane_off = (uint32_t)(l32 * kSub + 8 * lh);
-    for (int i = lo; i <= hi; ++i) {
-      const int64_t o = ((int64_t)x * kSbCols + 128 * (bx + i) + 32 * wave) * kSub + lane_off;
-      unsigned char* dst = stage + i * 4096;
+    for (uint32_t rest = g.active; rest; rest &= rest - 1) {
+      const int p = __builtin_ctz(rest);
+      const int64_t o = ((int64_t)x * kSbCols + sb_piece_col(g, wave, p >> 2, p & 3)) * kSub + lane_off;
+      unsigned char* dst = stage + p * 4096;
       if (useE) {
         sb_load_lds(a.Nop[0] + o, dst);
         sb_load_lds(a.Nop[1] + o, dst + 1024);
@@ -236,69 +260,55 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
       }
     }
   };
-  request_left(0);
+  SbGeo g_next = sb_geo(0, wave, sbw, nev, a.terms);
+  request_left(0, g_next);
+  if (wave == 1) load_diag(0, 0);
+  if (wave == 2) load_diag(0, 1);
+  __syncthreads();
 
   for (int e = 0; e < nev; ++e) {
     // (the lane number is re-read every iteration: addresses derived from it are then formed where they are
     // used instead of occupying registers through the whole loop, which has none to spare)
     int lane_v = lane;
     asm volatile("" : "+v"(lane_v));
-    const int b = e >> 3, eb = e & 7, owner = eb >> 1, half = eb & 1;
+    const SbGeo g = g_next;
     const int buf = e & 1;
     const int colg = a.sb0 + kSub * e;                    // first column of the sub-block
-    const bool group_start = a.group > 0 && (kSub * e) % a.group == 0;
-
-    // This wave's part of the sub-block's update: its 32-column pieces i_lo .. i_hi, counted from the current
-    // block (piece i = super-block columns 128 (b + i) + 32 wave .., held in acc[i]).
-    const int done = kSub * (e + 1);                      // super-block columns below this are final after this sub-block
-    const int i_lo = 128 * b + 32 * wave + 32 > done ? 0 : 1;
-    const int i_hi = min(kSbBlocks - 1, (sbw - 32 * wave + 127) / 128 - 1) - b;
-    const bool upd = a.terms != 0 && e + 1 < nev && i_lo <= i_hi;
-
-    // ---- group range over the current (error-compensated) weights, when the group spans tiles or waves
-    if (group_start && a.group >= 32) {
-      const int g0 = kSub * eb, g1 = g0 + a.group;        // block-local columns of the group
-      if (32 * wave < g1 && 32 * wave + 32 > g0) {
-#pragma unroll
-        for (int rh = 0; rh < 2; ++rh) {
-          float mn = acc[0][rh][0], mx = mn;
-#pragma unroll
-          for (int v = 1; v < 16; ++v) { mn = fminf(mn, acc[0][rh][v]); mx = fmaxf(mx, acc[0][rh][v]); }
-          const u32x2 r0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(mn), __float_as_uint(mn), false, false);
-          const u32x2 r1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-          mn = fminf(__uint_as_float(r0[0]), __uint_as_float(r0[1]));
-          mx = fmaxf(__uint_as_float(r1[0]), __uint_as_float(r1[1]));
-          if (lh == 0) { sh.mn[wave][32 * rh + l32] = mn; sh.mx[wave][32 * rh + l32] = mx; }
-        }
-      }
-      sb_barrier();
-      if (wave == owner) {
-        float mn = 0.f, mx = 0.f;
-        for (int w2 = g0 / 32; w2 < g1 / 32; ++w2) { mn = fminf(mn, sh.mn[w2][lane]); mx = fmaxf(mx, sh.mx[w2][lane]); }
-        float s, z;
-        sb_grid_params(mn, mx, a.maxq, a.sym, s, z);
-        sh.sc[lane] = s;
-        sh.zr[lane] = z;
-        const int row = row0 + lane;
-        if (row < a.m) {
-          const int64_t o = (int64_t)row * a.G + colg / a.group;
-          a.scales[o] = s;
-          a.zeros[o] = z;
-        }
-      }
-    }
+    const bool is_owner = wave == g.owner;
 
     // results of the 16 steps (owner only): W^ and the codes, packed one byte each as they are produced
     float wh[kSub];
     uint32_t cw[4] = {0u, 0u, 0u, 0u};
-    if (wave == owner) {
+    if (is_owner) {
+      const int row = row0 + lane_v;
+      // ---- group range over the current (error-compensated) weights: the group's pieces are all in this wave
+      if (a.group >= 32 && (kSub * e) % a.group == 0) {
+        float mn[2], mx[2];
+#pragma unroll
+        for (int rh = 0; rh < 2; ++rh) {
+          float lo = 0.f, hi = 0.f;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (32 * i < a.group) {
+#pragma unroll
+              for (int v = 0; v < 16; ++v) { lo = fminf(lo, acc[0][i][rh][v]); hi = fmaxf(hi, acc[0][i][rh][v]); }
+            }
+          const u32x2 r0 = __builtin_amdgcn_permlane32_swap(__float_as_uint(lo), __float_as_uint(lo), false, false);
+          const u32x2 r1 = __builtin_amdgcn_permlane32_swap(__float_as_uint(hi), __float_as_uint(hi), false, false);
+          mn[rh] = fminf(__uint_as_float(r0[0]), __uint_as_float(r0[1]));
+          mx[rh] = fmaxf(__uint_as_float(r1[0]), __uint_as_float(r1[1]));
+        }
+        sb_grid_params(lh ? mn[1] : mn[0], lh ? mx[1] : mx[0], a.maxq, a.sym, sc, zr);
+        isc = 1.f / sc;
+        if (row < a.m) {
+          const int64_t o = (int64_t)row * a.G + colg / a.group;
+          a.scales[o] = sc;
+          a.zeros[o] = zr;
+        }
+      }
       // ================= the 16 column steps of this sub-block (lines 7-10), one row per lane
       float w[kSub];
-      if (half) sb_extract<1>(acc, w); else sb_extract<0>(acc, w);
-      if (a.group >= 32) {
-        sc = sh.sc[lane]; zr = sh.zr[lane]; isc = 1.f / sc;          // written by the group's first owner (this wave or, a barrier ago, another)
-      }
-      const int row = row0 + lane_v;
+      if (g.half) sb_extract<1>(acc, w); else sb_extract<0>(acc, w);
       uint32_t peh[8], pel[8], pvh[8], pvl[8];             // -E and V as bf16 hi + lo pairs (operands of the updates)
       if (a.group == kSub) {                               // the group is this sub-block: its grid comes from the registers
         float mn = 0.f, mx = 0.f;
@@ -314,30 +324,35 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
       }
       const float* Ud = &sh.Ud[buf][0][0];
       const float* Pd = &sh.Pd[buf][0][0];
-      // the pieces of row j of U and P right of the diagonal, fetched one step ahead of their use
-      f32x4 un[4], pn[4];
+      // the pieces of row j of U and P right of the diagonal (and 1 / U_jj), fetched two steps ahead of their use: a
+      // wait for "everything but the latest reads" then never waits for reads that have only just been issued
+      f32x4 ub[3][4], pb[3][4];
+      float db[3];
       auto fetch = [&](int j) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
           if (4 * q + 3 > j) {
-            un[q] = *reinterpret_cast<const f32x4*>(Ud + j * kSub + 4 * q);
-            pn[q] = *reinterpret_cast<const f32x4*>(Pd + j * kSub + 4 * q);
+            ub[j % 3][q] = *reinterpret_cast<const f32x4*>(Ud + j * kSub + 4 * q);
+            pb[j % 3][q] = *reinterpret_cast<const f32x4*>(Pd + j * kSub + 4 * q);
           }
+        db[j % 3] = sh.dinv[buf][j];
       };
       fetch(0);
+      fetch(1);
 #pragma unroll
       for (int j = 0; j < kSub; ++j) {
-        f32x4 uc[4], pc[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) { uc[q] = un[q]; pc[q] = pn[q]; }
-        if (j + 1 < kSub) fetch(j + 1);
-        const float dj = sh.dinv[buf][j];
+        if (j + 2 < kSub) fetch(j + 2);
+        const f32x4(&uc)[4] = ub[j % 3];
+        const f32x4(&pc)[4] = pb[j % 3];
+        const float dj = db[j % 3];
         const float v = w[j];
-        const float q = fminf(fmaxf(rintf(v * isc) + zr, 0.f), a.maxq);
-        const float x = sc * (q - zr);
+        // code - zero = clamp(rint(v / scale), -zero, maxq - zero): the same integers as clamp(rint(.) + zero, 0, maxq)
+        // - zero, with a shorter dependency chain in front of the updates (one median instead of add, max, min, sub)
+        const float d = __builtin_amdgcn_fmed3f(rintf(v * isc), -zr, a.maxq - zr);
+        const float x = sc * d;
         const float e1 = (x - v) * dj;                    // -E_j
         wh[j] = x;
-        cw[j >> 2] |= (uint32_t)q << (8 * (j & 3));
+        cw[j >> 2] |= (uint32_t)(d + zr) << (8 * (j & 3));
         {
           const uint32_t h1 = sb_bf16_rne(e1), l1 = sb_bf16_rne(e1 - sb_bf16_f32((uint16_t)h1));
           const uint32_t h2 = sb_bf16_rne(v), l2 = sb_bf16_rne(v - sb_bf16_f32((uint16_t)h2));
@@ -346,7 +361,6 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
         }
 #pragma unroll
         for (int c = j + 1; c < kSub; ++c) w[c] = fmaf(e1, uc[c >> 2][c & 3], fmaf(v, pc[c >> 2][c & 3], w[c]));
-        __builtin_amdgcn_sched_barrier(0);
       }
       {
         const int rh = lane >> 5;
@@ -360,16 +374,16 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
       }
       sb_barrier();
     } else {
-      // the waves that wait fetch the next sub-block's diagonal pieces
+      // the waves that hold later blocks fetch the next sub-block's diagonal pieces while they wait
       if (e + 1 < nev) {
-        if (wave == ((owner + 1) & 3)) load_diag(e + 1, 0);
-        if (wave == ((owner + 2) & 3)) load_diag(e + 1, 1);
+        if (wave == ((g.owner + 1) & 3)) load_diag(e + 1, 0);
+        if (wave == ((g.owner + 2) & 3)) load_diag(e + 1, 1);
       }
       sb_barrier();
     }
 
     // ================= every wave: this sub-block's update of its own later columns (Eq. 18 inside the super-block)
-    if (upd) {
+    if (g.active) {
       bf16x8 fe[2][2], fv[2][2];                          // [hi/lo][row half]
 #pragma unroll
       for (int hl = 0; hl < 2; ++hl)
@@ -382,40 +396,42 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
       const unsigned char* mine = stage + lane_v * 16;
       // one piece at a time, the next piece's operands read from LDS under this piece's MFMAs
       u32x4 cur[4];
-      auto read_left = [&](int i, u32x4 (&dst)[4]) {
+      auto read_left = [&](int p, u32x4 (&dst)[4]) {
 #pragma unroll
         for (int q = 0; q < 4; ++q)
-          if (q < 2 ? useE : useP) dst[q] = *reinterpret_cast<const u32x4*>(mine + i * 4096 + q * 1024);
+          if (q < 2 ? useE : useP) dst[q] = *reinterpret_cast<const u32x4*>(mine + p * 4096 + q * 1024);
       };
-      read_left(i_lo, cur);
+      read_left(__builtin_ctz(g.active), cur);
 #pragma unroll
-      for (int i = 0; i < kSbBlocks; ++i) {
-        if (i >= i_lo && i <= i_hi) {
+      for (int p = 0; p < kSbPieces; ++p) {
+        if ((g.active >> p) & 1u) {
           u32x4 nxt[4];
-          if (i + 1 <= i_hi) read_left(i + 1, nxt);
-          if (i == 0) {
-            // the current block's piece: the columns of the sub-block itself (and those before it) take no update
-            const bool keep = 128 * b + 32 * wave + l32 >= done;
+          const uint32_t rest = g.active >> (p + 1);
+          if (rest) read_left(p + 1 + __builtin_ctz(rest), nxt);
+          if (p == 0 && is_owner) {
+            // the piece the sub-block lies in: the sub-block's own columns (its first half) take no update
+            const bool keep = l32 >= kSub;
             const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int q = 0; q < 4; ++q) cur[q] = keep ? cur[q] : z;
           }
+          f32x16(&t)[2] = acc[p >> 2][p & 3];
           if (useE) {
             const bf16x8 ah = __builtin_bit_cast(bf16x8, cur[0]), al = __builtin_bit_cast(bf16x8, cur[1]);
 #pragma unroll
             for (int rh = 0; rh < 2; ++rh) {
-              acc[i][rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fe[0][rh], acc[i][rh], 0, 0, 0);
-              acc[i][rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fe[1][rh], acc[i][rh], 0, 0, 0);
-              acc[i][rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, fe[0][rh], acc[i][rh], 0, 0, 0);
+              t[rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fe[0][rh], t[rh], 0, 0, 0);
+              t[rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fe[1][rh], t[rh], 0, 0, 0);
+              t[rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, fe[0][rh], t[rh], 0, 0, 0);
             }
           }
           if (useP) {
             const bf16x8 ah = __builtin_bit_cast(bf16x8, cur[2]), al = __builtin_bit_cast(bf16x8, cur[3]);
 #pragma unroll
             for (int rh = 0; rh < 2; ++rh) {
-              acc[i][rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fv[0][rh], acc[i][rh], 0, 0, 0);
-              acc[i][rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fv[1][rh], acc[i][rh], 0, 0, 0);
-              acc[i][rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, fv[0][rh], acc[i][rh], 0, 0, 0);
+              t[rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fv[0][rh], t[rh], 0, 0, 0);
+              t[rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, fv[1][rh], t[rh], 0, 0, 0);
+              t[rh] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, fv[0][rh], t[rh], 0, 0, 0);
             }
           }
 #pragma unroll
@@ -424,11 +440,29 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
         }
       }
     }
+    // the owner keeps its pieces in a fixed place: a finished piece makes room for the next, a finished block for
+    // the wave's second block
+    if (is_owner) {
+      if ((e & 7) == 7) {
+        if (g.two) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int rh = 0; rh < 2; ++rh) acc[0][i][rh] = acc[1][i][rh];
+        }
+      } else if (g.half) {
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+#pragma unroll
+          for (int rh = 0; rh < 2; ++rh) acc[0][i][rh] = acc[0][i + 1][rh];
+      }
+    }
     // the staging area is free again (its reads have returned): request the next sub-block's operands, then let
     // this sub-block's results leave for memory
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    request_left(e + 1);
-    if (wave == owner) {
+    g_next = sb_geo(e + 1, wave, sbw, nev, a.terms);
+    request_left(e + 1, g_next);
+    if (is_owner) {
       const int row = row0 + lane_v;
       if (row < a.m) {
         float* wdst = a.W + (int64_t)row * a.ldw + colg;
@@ -445,7 +479,7 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
         }
       }
     }
-    if (a.Eh && wave == ((owner + 3) & 3)) {
+    if (a.Eh && wave == ((g.owner + 3) & 3)) {
       // -E and V for the update of the columns after the super-block: copied to memory from the LDS fragments by
       // a wave that has nothing else to do now (they stay valid until the sub-block after next is published)
 #pragma unroll
@@ -459,12 +493,6 @@ __global__ __launch_bounds__(256) void quant_sb_kernel(SbArgs a) {
           *reinterpret_cast<u32x4*>(a.Vl + o) = sh.frag[buf][1][1][r >> 5][ch][r & 31];
         }
       }
-    }
-    if (eb == 7) {                                        // block finished: the next one becomes acc[0]
-#pragma unroll
-      for (int i = 0; i + 1 < kSbBlocks; ++i)
-#pragma unroll
-        for (int rh = 0; rh < 2; ++rh) acc[i][rh] = acc[i + 1][rh];
     }
   }
 }
