@@ -8,6 +8,7 @@ Inputs are synthetic (paper_2504_02692_amd/synth.py) and resident in HBM before 
 region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 32768] [--staged]
+    python bench.py --extras      (timing table of act_order, packing, activation quantiser, clip-range search)
 """
 from __future__ import annotations
 
@@ -60,6 +61,71 @@ def cpu_baseline(wl, budget_s: float = 20.0):
                       f"its operation count (n^2 k, n^3, m n^2) to the workload's layer set: extrapolated"}
 
 
+def time_ms(fn, reps=5):
+    import torch
+    fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def extras():
+    """Timings of the entry points beside the main path (act_order, clip-range search, activation fake-quantiser,
+    code packing) on Llama-2-7B-shaped inputs: mean of 5 repetitions after one warm-up, HIP events; GB/s = bytes the
+    operation has to move (inputs read once, outputs written once) / time."""
+    import torch
+    from paper_2504_02692_amd import binding as B
+    from paper_2504_02692_amd import synth
+    dev = "cuda"
+    print(f"{'operation':58s} {'size':>22s} {'ms':>9s} {'GB/s':>8s}")
+    for n in (4096, 11008):
+        tokens = 8192
+        X, Xt = synth.make_activations_device(tokens, n, 0, f"extras{n}", dev)
+        H = torch.zeros((n, n), device=dev); A = torch.zeros_like(H)
+        B.gptaq_accumulate(X, Xt, H, A, B.workspace(B.gptaq_accumulate_workspace_bytes(tokens, n)))
+        B.gptaq_symmetrize(H)
+        t = time_ms(lambda: B.gptaq_act_order(H))
+        print(f"{'act_order: rank the diagonal of H':58s} {f'n = {n}':>22s} {t:9.3f} {'':>8s}")
+        perm = B.gptaq_act_order(H)
+        ws = B.workspace(B.gptaq_permute_hessian_workspace_bytes(n))
+        t = time_ms(lambda: B.gptaq_permute_hessian(H, A, perm, ws))
+        print(f"{'act_order: permute H and dXXT (rows and columns)':58s} {f'n = {n}':>22s} {t:9.3f} {4 * n * n * 4 / t / 1e6:8.0f}")
+        m = 4096
+        W = synth.make_weights_device(m, n, 0, f"w{n}", dev)
+        t = time_ms(lambda: B.gptaq_permute_columns_f32(W, perm))
+        print(f"{'act_order: permute the columns of W (fp32)':58s} {f'{m} x {n}':>22s} {t:9.3f} {2 * m * n * 4 / t / 1e6:8.0f}")
+        codes = torch.randint(0, 16, (m, n), dtype=torch.uint8, device=dev)
+        t = time_ms(lambda: B.gptaq_permute_columns_u8(codes, perm, inverse=True))
+        print(f"{'act_order: un-permute the codes (uint8)':58s} {f'{m} x {n}':>22s} {t:9.3f} {2 * m * n / t / 1e6:8.0f}")
+        for bits in (4, 3):
+            t = time_ms(lambda: B.gptaq_pack_codes(codes % (1 << bits), bits))
+            out_bytes = m * B.gptaq_packed_words_per_row(n, bits) * 4
+            print(f"{f'pack {bits}-bit codes into 32-bit words':58s} {f'{m} x {n}':>22s} {t:9.3f} {(m * n + out_bytes) / t / 1e6:8.0f}")
+        Xa = X[:8192]
+        t = time_ms(lambda: B.gptaq_fake_quant_activations(Xa, 4, 0.9))
+        print(f"{'activation fake-quantiser (per token, asym, clip 0.9, A4)':58s} {f'{Xa.shape[0]} x {n}':>22s} {t:9.3f} {2 * Xa.numel() * 2 / t / 1e6:8.0f}")
+        # clip-range search: the column loop with and without the search (prepare once, quantise a fresh copy each time)
+        Hc, Ac = H.clone(), A.clone()
+        B.gptaq_prepare(Hc, Ac, 0.01, B.workspace(B.gptaq_prepare_workspace_bytes(n)))
+        wsq = B.workspace(B.gptaq_quantize_workspace_bytes(m, n))
+        Wc = W.clone()
+
+        def quant(grid, steps):
+            Wc.copy_(W)
+            B.gptaq_quantize_layer(Wc, Hc, Ac, 4, 128, False, 128, wsq, mse_grid=grid, mse_steps=steps)
+        t0 = time_ms(lambda: quant(0, 0))
+        t1 = time_ms(lambda: quant(100, 20))
+        print(f"{'quantize W4 g128, min-max ranges':58s} {f'{m} x {n}':>22s} {t0:9.3f} {'':>8s}")
+        print(f"{'quantize W4 g128, clip-range search (grid 100, 20 steps)':58s} {f'{m} x {n}':>22s} {t1:9.3f} {'':>8s}")
+        del X, Xt, H, A, W, codes, Hc, Ac, Wc
+
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +136,8 @@ def main() -> int:
     ap.add_argument("--staged", action="store_true",
                     help="hand the chunks to gptaq_accumulate_staged (products per 32768 pending tokens)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--extras", action="store_true",
+                    help="print the timing table of the entry points beside the main path and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the solve has no collective step); use --gpus 1",
@@ -83,6 +151,9 @@ def main() -> int:
         print("bench.py: no GPU", file=sys.stderr)
         return 2
     B.load()
+    if args.extras:
+        extras()
+        return 0
     dev = torch.device("cuda:0")
     wl = synth.workload(args.workload)
     inputs = wl.inputs()
@@ -160,6 +231,7 @@ def main() -> int:
     # what the matrix cores of this machine sustain on nothing but MFMAs (all-ones and random operands), measured here
     peak_ones, clk_ones = B.gptaq_measure_mfma_peak(False, 50)
     peak_rand, clk_rand = B.gptaq_measure_mfma_peak(True, 50)
+    hbm_copy = B.gptaq_measure_hbm_copy(1 << 30, 10)          # GB/s of a plain 1 GiB streaming copy (read + written)
 
     ms_per_step = elapsed * 1e3 / args.steps
     n_layers = len(wl.layers)
@@ -170,23 +242,40 @@ def main() -> int:
         flops += (n * (n + 1) + 2 * n * n) * float(wl.tokens)
     flops *= args.steps
     achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
-    # secondary kernels (from the untimed, fully bracketed pass): column loop against HBM with 17 algorithmic bytes
-    # per weight (read W 4, write W^ 4, code 1, -E and V 8), trailing update with 2 m n^2 algorithmic flop per layer
+    # secondary kernels (from the untimed, fully bracketed pass).  The super-block kernel does the column steps and every
+    # update inside a 1024-column super-block: against HBM with 17 algorithmic bytes per weight (read W 4, write W^ 4,
+    # code 1, -E and V 8).  The trailing update has 2 m n^2 algorithmic flop per layer; the part inside the super-blocks
+    # runs in that kernel, the rest in the far-update GEMM.
     wbytes = 17.0 * sum(l.m * l.n for l in wl.layers)
     tflop = 2.0 * sum(l.m * l.n * l.n for l in wl.layers)
+    far_flop = 0.0
+    for l in wl.layers:
+        for sb_end in range(1024, l.n, 1024):
+            far_flop += 2.0 * l.m * 1024 * (l.n - sb_end) * 2
+    t_sb, t_far = prof["column_loop"][1] * 1e-3, prof["trailing_gemm"][1] * 1e-3
     other = {
-        "column_loop": {"bound": "hbm", "achieved": wbytes / (prof["column_loop"][1] * 1e-3) / 1e9, "peak": 8000.0,
-                        "unit": "GB/s", "frac": wbytes / (prof["column_loop"][1] * 1e-3) / 1e9 / 8000.0,
-                        "note": "n sequential column steps per layer bound this kernel, not bandwidth"},
-        "trailing_gemm": {"bound": "mfma", "achieved": tflop / (prof["trailing_gemm"][1] * 1e-3) / 1e12,
-                          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                          "frac": tflop / (prof["trailing_gemm"][1] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-                          "note": "algorithmic 2 m n^2 flop; executed x3 (bf16 hi/lo split for fp32 accuracy)"},
+        "superblock_kernel": {"bound": "hbm", "achieved": wbytes / t_sb / 1e9, "peak": 8000.0, "unit": "GB/s",
+                              "frac": wbytes / t_sb / 1e9 / 8000.0, "frac_of_measured_copy": wbytes / t_sb / 1e9 / hbm_copy,
+                              "mfma_tflops_inside": (tflop - far_flop) / t_sb / 1e12,
+                              "note": "column steps + updates inside 1024-column super-blocks; bound by the chain of "
+                                      "sequential column steps (n per layer), not by bandwidth"},
+        "far_update_gemm": {"bound": "mfma", "achieved": far_flop / t_far / 1e12 if t_far > 0 else 0.0,
+                            "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                            "frac": far_flop / t_far / 1e12 / PEAK_BF16_TFLOPS if t_far > 0 else 0.0,
+                            "note": "algorithmic flop of the updates that leave a super-block; executed x3 (bf16 hi/lo "
+                                    "split of both operands)"},
+        "trailing_update_total": {"bound": "mfma", "achieved": tflop / (t_sb + t_far) / 1e12, "peak": PEAK_BF16_TFLOPS,
+                                  "unit": "TFLOP/s", "frac": tflop / (t_sb + t_far) / 1e12 / PEAK_BF16_TFLOPS,
+                                  "note": "2 m n^2 algorithmic flop over super-block kernel + far GEMM time"},
     }
-    traffic = None
+    # HBM-side bytes per launch of the dominant kernel come from two separate rocprofv3 --pmc runs of this same command
+    # (FETCH_SIZE, WRITE_SIZE); they are quoted only when the committed summary is for this workload and chunk size
+    traffic, traffic_src = None, None
     tpath = os.path.join(ROOT, "profiles", f"{wl.name}_block_hbm_traffic.json")
-    if os.path.exists(tpath):          # HBM bytes per launch from the separate rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
-        traffic = json.load(open(tpath)).get("bytes_per_launch_avg")
+    if os.path.exists(tpath):
+        tj = json.load(open(tpath))
+        if tj.get("workload") == wl.name and tj.get("chunk", 32768) == args.chunk and not args.staged:
+            traffic, traffic_src = tj.get("bytes_per_launch_avg"), "profiles/" + os.path.basename(tpath)
     out = {
         "metric": "ms_per_layer_solve", "value": ms_per_step / n_layers, "unit": "ms/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -199,7 +288,7 @@ def main() -> int:
                    "layers_per_step": n_layers},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel<256> (accumulate: H and dXXT)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
                      "launches": launches, "avg_launch_ms": gemm_ms / max(1, launches),
                      "executed": achieved * 5.0 / 3.0,
                      "measured_mfma_loop": {"ones_tflops": peak_ones, "ones_clock_ghz": clk_ones,
@@ -207,7 +296,8 @@ def main() -> int:
                                             "executed_frac_of_random": achieved * 5.0 / 3.0 / peak_rand,
                                             "note": "pure bf16 MFMA loop on all CUs for 50 ms (power-limited clock); "
                                                     "executed = 5 n^2 c flop (exact hi/lo split of dX) against "
-                                                    "3 n^2 c algorithmic"}},
+                                                    "3 n^2 c algorithmic"},
+                     "measured_hbm_copy_gbps": hbm_copy},
         "other_kernels": other,
         "stages_ms_per_step": stage_ms,
         "kernels_ms_per_step": {k: v[1] for k, v in prof.items()},

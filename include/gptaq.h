@@ -101,7 +101,7 @@ int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
 /* ---------------------------------------------------------------------------------------
  * Algorithm 1, lines 3-4.  Consumes H and dXXT.
  *   dead inputs (H_qq == 0): H_qq <- 1, row q of dXXT <- 0, dead[q] <- 1;
- *   lambda = damp * mean(diag H)  ("dampened by 1% of the average", end of Section 4.2);
+ *   lambda = damp * mean(diag H)  (damping relative to the mean diagonal, end of Section 4.2);
  *   H + lambda I = V V^T with V upper triangular, U = V^-1, so that (H + lambda I)^-1 = L L^T
  *   with L = U^T the lower factor of Step 3 / Lemma 4.1 (factorisation on fp64 data: its 64 x 64 blocks in
  *   fp64, its rank-256 block products in 46-bit row-scaled fixed point, exact in int32);
@@ -110,8 +110,10 @@ int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
  *   H    : in: upper triangle of H.  out: U (upper triangular, zeros below), fp32.
  *   dXXT : in: dXXT.                 out: P (strictly upper triangular, zeros elsewhere).
  *   dead : n bytes, out: 1 for dead inputs else 0.  May be NULL.
- *   info : 2 x int32, out: info[0] = 0, or 1 + index of the first non-positive pivot (U, P are
- *          then garbage); info[1] = number of dead inputs.
+ *   info : 2 x int32, out: info[0] = 0, or 1 + index of the first non-positive pivot, or -(1 + row) of a
+ *          NaN/Inf entry found in H (upper triangle) or dXXT (in both cases U and P are garbage);
+ *          info[1] = number of dead inputs.
+ *   n    : at most 65280.
  * Streams: part of the factor sweep runs on a helper stream that the library creates once per device
  * (default priority, kept until the process ends) and ties to `stream` with events on both ends, so to
  * the caller the call is still one asynchronous operation on `stream`.  Host-side the call takes a
@@ -159,8 +161,8 @@ int gptaq_quantize_layer_terms(float* W, int64_t m, int64_t n, int64_t ldw,
                                uint8_t* codes, float* scales, float* zeros,
                                void* ws, size_t ws_bytes, void* stream, int terms);
 
-/* The same solve with the clip-range search of Section 5.1 for the weight grid ("searched by
- * minimizing mean squared error"): whenever a (scale, zero) pair is taken from a range, the candidates
+/* The same solve with the clip-range search of Section 5.1 for the weight grid (the range that
+ * minimises the squared quantisation error): whenever a (scale, zero) pair is taken from a range, the candidates
  * p = 1 - i / mse_grid, i = 0 .. mse_steps - 1, shrink that range about its zero-point
  * (scale_i = p * scale_0, same zero-point); the candidate with the smallest sum of squared
  * quantisation errors over the row-group is used (the earlier one on ties).  mse_steps = 0 is the
@@ -205,8 +207,9 @@ int gptaq_permute_columns_u8(const uint8_t* in, uint8_t* out, int64_t m, int64_t
  * gptaq_fake_quant_activations: the activation quantiser of Section 5.1 (per token, asymmetric,
  *   clipping ratio `clip`, 0.9 in the paper), used to produce X when activations are quantised before
  *   the weights.  For every token row: range = clip * [min(0, min x), max(0, max x)],
- *   scale = range / (2^bits - 1), zero = rint(-clip*min/scale),
- *   y = bf16(scale * (clamp(rint(x / scale) + zero) - zero)), arithmetic in fp32.
+ *   scale = fp32(range / (2^bits - 1)), zero = rint(-clip*min/scale),
+ *   y = bf16(scale * (clamp(rint(x / scale) + zero) - zero)): rint(x / scale) is the exact rounding for the fp32 scale,
+ *   the product is exact, one rounding to bf16.
  *   X, Y: (tokens x n) bf16, leading dimensions ldx, ldy; Y may equal X.
  * gptaq_pack_codes: packed row r = little-endian bit stream of the row's codes, code j in bits
  *   [j*bits, (j+1)*bits); gptaq_packed_words_per_row(n, bits) = ceil(n*bits/32) uint32 words per row.
@@ -242,6 +245,13 @@ int gptaq_profile_read(int tag, int64_t* launches, double* total_ms);
  * Synchronous: returns after the measurement. */
 int gptaq_measure_mfma_peak(int random_data, int millis, void* ws, size_t ws_bytes, double* tflops,
                             double* clock_ghz, void* stream);
+
+/* Measurement aid: what a plain streaming copy reaches on this GPU, the practical HBM ceiling quoted beside the
+ * nominal 8 TB/s.  Copies `bytes` (a multiple of 16, >= 4096) from the first half of `ws` to the second, `reps`
+ * times after one untimed pass; *gbps = bytes read + bytes written per second, in GB/s (HOST pointer).
+ *   ws : >= 2 * bytes of device memory, 256-byte aligned (contents are scratch).
+ * Synchronous: returns after the measurement. */
+int gptaq_measure_hbm_copy(size_t bytes, int reps, void* ws, size_t ws_bytes, double* gbps, void* stream);
 
 #ifdef __cplusplus
 }

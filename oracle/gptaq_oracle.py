@@ -55,8 +55,8 @@ def accumulate(X_bits: np.ndarray, Xtilde_bits: np.ndarray):
 
 # ------------------------------------- Algorithm 1, line 3: damping, H^-1 = L L^T
 def dampen(H: np.ndarray, dXXT: np.ndarray, damp: float):
-    """H + lambda I with lambda = damp * mean(diag H) ("dampened by 1% of the average
-    values", end of Section 4.2), after the dead-input rule."""
+    """H + lambda I with lambda = damp * mean(diag H) (damping relative to the mean
+    diagonal, end of Section 4.2), after the dead-input rule."""
     H = np.array(H, dtype=np.float64, copy=True)
     A = np.array(dXXT, dtype=np.float64, copy=True)
     dead = np.diag(H) == 0.0
@@ -117,8 +117,8 @@ def quant_params(xmin: np.ndarray, xmax: np.ndarray, bits: int, sym: bool):
 
 def quant_params_mse(block: np.ndarray, bits: int, sym: bool, grid: int, steps: int,
                      hint_scales=None, rel_tol=0.0):
-    """Clip-range search of Section 5.1 ("the weight clipping range is searched by minimizing mean
-    squared error"), read as: the candidates p = 1 - i/grid, i = 0..steps-1, shrink the min-max range
+    """Clip-range search of Section 5.1 (the clipping range of the weights is the one that minimises the
+    squared quantisation error), read as: the candidates p = 1 - i/grid, i = 0..steps-1, shrink the min-max range
     of each row of `block` about its zero-point (scale_i = fp32(p * (xmax - xmin)/maxq), zero-point of
     the full range); the candidate with the smallest sum of squared errors wins, the earlier on ties.
     With `hint_scales`, a hinted scale is accepted for a row if it is (to 1e-5) one of the row's
@@ -293,25 +293,60 @@ def quantize_layer_blocked(W, U, P, bits, group=0, sym=False, blocksize=128, dea
 
 
 # ------------------------------------- neighbours of the solve in Algorithm 2 (Section 5.1)
-def fake_quant_activations(X_bits: np.ndarray, bits: int, clip: float = 0.9):
-    """Per-token asymmetric activation quantiser with a clipping ratio (Section 5.1), in fp32 like the
-    library (the paper fixes no precision; the decision is taken in the kernel's).  Returns the
-    dequantised activations as bf16 bit patterns and the pre-rounding values x/scale."""
-    x = (np.ascontiguousarray(X_bits, np.uint16).astype(np.uint32) << 16).view(np.float32)
-    maxq = np.float32(2 ** bits - 1)
-    mn = np.minimum(x.min(axis=1), np.float32(0)) * np.float32(clip)
-    mx = np.maximum(x.max(axis=1), np.float32(0)) * np.float32(clip)
-    flat = (mn == 0) & (mx == 0)
-    mn = np.where(flat, np.float32(-1), mn).astype(np.float32)
-    mx = np.where(flat, np.float32(1), mx).astype(np.float32)
-    scale = ((mx - mn) / maxq).astype(np.float32)
-    zero = np.rint(-mn / scale).astype(np.float32)
-    t = (x / scale[:, None]).astype(np.float32)
-    q = np.clip(np.rint(t) + zero[:, None], 0, maxq).astype(np.float32)
-    y = (scale[:, None] * (q - zero[:, None])).astype(np.float32)
-    u = y.view(np.uint32).astype(np.uint64)
-    yb = ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)      # fp32 -> bf16, round to nearest even
-    return yb, t
+def fake_quant_activations(X_bits: np.ndarray, bits: int, clip: float = 0.9, hint_bits=None, tau: float = 0.0):
+    """Per-token asymmetric activation quantiser with a clipping ratio (Section 5.1), in float64.
+
+    For every token (row): range = clip * [min(0, min x), max(0, max x)]; scale = range / (2^bits - 1),
+    rounded to fp32 once (the grid is the one a user rebuilds from an fp32 scale, as for the weights);
+    zero = rint(-clip * min / scale); y = scale * (clamp(rint(x / scale) + zero) - zero), which is exact in
+    float64 (24-bit scale times a small integer), rounded once to bfloat16 (nearest, ties to even).
+    `clip` is taken as the fp32 number the library receives.
+    `hint_bits` / `tau`: near-tie protocol as in quantize_layer: where x / scale lies within tau of a rounding
+    boundary and the hinted output is the dequantised neighbouring integer, that integer is taken.
+    Returns (y as bf16 bit patterns, t = x / scale before rounding, number of hints used)."""
+    x = bf16_bits_to_f64(X_bits)
+    maxq = float(2 ** bits - 1)
+    c = float(np.float32(clip))
+    mn = np.minimum(x.min(axis=1), 0.0) * c
+    mx = np.maximum(x.max(axis=1), 0.0) * c
+    flat = (mn == 0.0) & (mx == 0.0)
+    mn = np.where(flat, -1.0, mn)
+    mx = np.where(flat, 1.0, mx)
+    scale = ((mx - mn) / maxq).astype(np.float32).astype(np.float64)
+    zero = np.rint(-mn / scale)
+    t = x / scale[:, None]
+    q = np.clip(np.rint(t) + zero[:, None], 0.0, maxq)
+    hints = 0
+    if hint_bits is not None:
+        hy = bf16_bits_to_f64(hint_bits)
+        frac = t - np.floor(t)
+        near = np.abs(frac - 0.5) < tau
+        for dq in (-1.0, 1.0):
+            qa = q + dq
+            ya = _f64_to_bf16_bits(scale[:, None] * (qa - zero[:, None]))
+            take = near & (qa >= 0.0) & (qa <= maxq) & (ya == np.asarray(hint_bits, np.uint16)) & \
+                (_f64_to_bf16_bits(scale[:, None] * (q - zero[:, None])) != np.asarray(hint_bits, np.uint16))
+            hints += int(take.sum())
+            q = np.where(take, qa, q)
+        del hy
+    y = scale[:, None] * (q - zero[:, None])
+    return _f64_to_bf16_bits(y), t, hints
+
+
+def _f64_to_bf16_bits(y: np.ndarray) -> np.ndarray:
+    """float64 -> bfloat16 bit patterns with ONE rounding (nearest, ties to even).  Going through float32 would
+    round twice; the float32 value is therefore first made 'sticky' (round to odd), after which the second rounding
+    cannot go wrong: bfloat16 keeps 8 significand bits, float32 24."""
+    y = np.asarray(y, np.float64)
+    f = y.astype(np.float32)                                # nearest
+    u = f.view(np.uint32).copy()
+    back = f.astype(np.float64)
+    inexact = back != y
+    # turn the nearest float32 into the truncated one where it was rounded away from zero, then set the sticky bit
+    away = inexact & (np.abs(back) > np.abs(y))
+    u = np.where(away, u - 1, u)
+    u = np.where(inexact, u | 1, u).astype(np.uint64)
+    return ((u + 0x7FFF + ((u >> 16) & 1)) >> 16).astype(np.uint16)
 
 
 def pack_codes(codes: np.ndarray, bits: int) -> np.ndarray:

@@ -61,6 +61,8 @@ _SIGS = {
     "gptaq_profile_read": (_c.c_int, [_c.c_int, _c.POINTER(_c.c_int64), _c.POINTER(_c.c_double)]),
     "gptaq_measure_mfma_peak": (_c.c_int, [_c.c_int, _c.c_int, _c.c_void_p, _c.c_size_t, _c.POINTER(_c.c_double),
                                            _c.POINTER(_c.c_double), _c.c_void_p]),
+    "gptaq_measure_hbm_copy": (_c.c_int, [_c.c_size_t, _c.c_int, _c.c_void_p, _c.c_size_t, _c.POINTER(_c.c_double),
+                                          _c.c_void_p]),
 }
 EXPORTS = tuple(_SIGS)
 PROFILE_TAGS = ("accumulate_gemm", "accumulate_split", "factor_sweep", "p_gemm", "column_loop", "trailing_gemm",
@@ -244,6 +246,15 @@ def gptaq_measure_mfma_peak(random_data: bool, millis: int = 50):
     _check(load().gptaq_measure_mfma_peak(int(bool(random_data)), int(millis), _ptr(ws), ws.numel() * ws.element_size(),
                                           _c.byref(tf), _c.byref(ghz), _stream()), "gptaq_measure_mfma_peak")
     return tf.value, ghz.value
+
+
+def gptaq_measure_hbm_copy(nbytes: int = 1 << 30, reps: int = 10) -> float:
+    """GB/s (read + written) of a plain streaming copy of `nbytes`."""
+    ws = workspace(2 * nbytes)
+    g = _c.c_double(0.0)
+    _check(load().gptaq_measure_hbm_copy(int(nbytes), int(reps), _ptr(ws), ws.numel() * ws.element_size(), _c.byref(g),
+                                         _stream()), "gptaq_measure_hbm_copy")
+    return g.value
 
 
 def gptaq_act_order(H: torch.Tensor) -> torch.Tensor:

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <mutex>
 #include "../../include/gptaq.h"
 
 namespace gptaq {
@@ -108,6 +109,17 @@ hipError_t launch_near_operands(const float* U, const float* P, int64_t ldh, int
 hipError_t launch_quant_sb(const SbArgs& a, hipStream_t s);
 
 void set_last_hip_error(hipError_t e);
+
+// Raises a kernel's dynamic LDS limit exactly once per process, whichever host thread comes first; every caller
+// gets the result of that one attempt.
+struct LdsLimitOnce {
+  std::once_flag once;
+  hipError_t result = hipSuccess;
+  hipError_t ensure(const void* kernel, int bytes) {
+    std::call_once(once, [&] { result = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes); });
+    return result;
+  }
+};
 
 // Optional per-kernel timing with HIP events (gptaq_profile_* in the public header).
 enum ProfTag { kProfAccumGemm = 0, kProfAccumSplit = 1, kProfFactor = 2, kProfPGemm = 3, kProfColumnLoop = 4,

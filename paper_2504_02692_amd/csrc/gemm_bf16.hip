@@ -2,8 +2,8 @@
 //
 // Every dense contraction of the solve goes through this kernel (Algorithm 1 line 2: H and
 // dXXT; line 4: the two products of Theorem 4.2; lines 11-12: the lazy trailing update of
-// Eq. 18).  fp32-accurate products are obtained by splitting an fp32 operand into bf16
-// hi + lo and summing the cross products hi*hi + hi*lo + lo*hi.
+// Eq. 18).  Where fp32 operands need more than bf16's 8 bits, an operand is split into bf16
+// hi + lo (about 2^-17 relative) and the cross products hi*hi + hi*lo + lo*hi are summed in fp32.
 //
 // Tiling: a 256-thread workgroup owns a BT x BT tile of C (BT = 256 or 128); its four
 // wavefronts sit 2 x 2 and each accumulates a (BT/2)^2 sub-tile with
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
   }
 }
 
-static bool g_attr_set = false;
+static LdsLimitOnce g_lds256, g_lds128;
 hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
   GemmBatch bb = b;
   int total = 0;
@@ -349,15 +349,9 @@ hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
     total += bb.ntiles[i];
   }
   if (total == 0) return hipSuccess;
-  if (!g_attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<256>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kLds256);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gemm_nt_kernel<128>),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, kLds128);
-    if (e != hipSuccess) return e;
-    g_attr_set = true;
-  }
+  hipError_t e = g_lds256.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<256>), kLds256);
+  if (e == hipSuccess) e = g_lds128.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<128>), kLds128);
+  if (e != hipSuccess) return e;
   if (b.tile == 256)
     hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3(total), dim3(256), kLds256, s, bb);
   else

@@ -350,16 +350,14 @@ template <int BM>
 static hipError_t launch_shape(const I8Operand& A, int a_row0, const I8Operand& B, int b_row0, double* C, int64_t ldc, int M,
                                int N, int K, double alpha, int beta, int upper_only, hipStream_t s) {
   using S = Shape<BM>;
-  static bool attr = false;                      // per instantiation
+  static LdsLimitOnce lds_once;                  // per instantiation
   I8Gemm g;
   g.tiles_m = (M + BM - 1) / BM;
   g.tiles_n = (N + BN - 1) / BN;
   if (a_row0 + g.tiles_m * BM > A.rows_pad || b_row0 + g.tiles_n * BN > B.rows_pad) return hipErrorInvalidValue;
-  if (!attr) {
-    hipError_t e = hipFuncSetAttribute((const void*)&gemm_i8s_kernel<BM>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       S::NSTAGE * S::STAGE);
+  {
+    const hipError_t e = lds_once.ensure((const void*)&gemm_i8s_kernel<BM>, S::NSTAGE * S::STAGE);
     if (e != hipSuccess) return e;
-    attr = true;
   }
   g.A = A.planes + (int64_t)a_row0 * KC; g.a_plane = A.plane_stride(); g.a_chunk = A.chunk_stride(); g.sa = A.scale + a_row0;
   g.B = B.planes + (int64_t)b_row0 * KC; g.b_plane = B.plane_stride(); g.b_chunk = B.chunk_stride(); g.sb = B.scale + b_row0;

@@ -43,6 +43,12 @@ __global__ __launch_bounds__(256) void mfma_peak_kernel(int iters, int random_da
   if (blockIdx.x == 0 && threadIdx.x == 0) { clk[0] = c1 - c0; clk[1] = w1 - w0; }
 }
 
+// Streaming copy: every thread moves 16-byte pieces a whole grid apart, reads and writes fully coalesced.
+__global__ __launch_bounds__(256) void stream_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
 }  // namespace gptaq
 
 using namespace gptaq;
@@ -81,5 +87,28 @@ extern "C" int gptaq_measure_mfma_peak(int random_data, int millis, void* ws, si
   const double flop = (double)wgs * 4 * iters * 32 * (32.0 * 32 * 16 * 2);
   *tflops = flop / (ms * 1e-3) / 1e12;
   *clock_ghz = (double)h[0] / ((double)h[1] * 10.0);      // shader clocks per 100 MHz real-time tick
+  return GPTAQ_OK;
+}
+
+extern "C" int gptaq_measure_hbm_copy(size_t bytes, int reps, void* ws, size_t ws_bytes, double* gbps, void* stream) {
+  if (!ws || !gbps) return GPTAQ_ENULL;
+  if (bytes < 4096 || bytes % 16 || reps <= 0 || reps > 1000) return GPTAQ_EDIM;
+  if (((uintptr_t)ws & 255) || ws_bytes < 2 * bytes) return GPTAQ_EWORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  const u32x4* src = (const u32x4*)ws;
+  u32x4* dst = (u32x4*)((unsigned char*)ws + bytes);
+  hipEvent_t e0, e1;
+  if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) return GPTAQ_ELAUNCH;
+  const size_t n16 = bytes / 16;
+  const unsigned grid = (unsigned)((n16 + 256 * 8 - 1) / (256 * 8) < 65536 * 16 ? (n16 + 256 * 8 - 1) / (256 * 8) : 65536 * 16);
+  float ms = 0.f;
+  hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(256), 0, s, src, dst, n16);      // untimed
+  hipEventRecord(e0, s);
+  for (int r = 0; r < reps; ++r) hipLaunchKernelGGL(stream_copy_kernel, dim3(grid), dim3(256), 0, s, src, dst, n16);
+  hipEventRecord(e1, s);
+  const bool ok = hipEventSynchronize(e1) == hipSuccess && hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+  hipEventDestroy(e0); hipEventDestroy(e1);
+  if (!ok || hipGetLastError() != hipSuccess) { set_last_hip_error(hipGetLastError()); return GPTAQ_ELAUNCH; }
+  *gbps = 2.0 * (double)bytes * reps / (ms * 1e-3) / 1e9;
   return GPTAQ_OK;
 }

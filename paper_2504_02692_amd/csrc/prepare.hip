@@ -13,10 +13,10 @@
 //       diag   : F_KK = V_KK V_KK^T,  Winv_K = V_KK^-1                       (one workgroup, LDS)
 //       panel  : V_iK = F_iK Winv_K^T  for all rows i above K
 //       inner  : F_ij -= V_iK V_jK^T   for the column blocks j of OB left of K (rank 64)
-//     syrk   : F_II  -= V_I,OB V_I,OB^T                (rank 256, fp64 MFMA)  } the n^3 * 2/3 bulk
-//     trinv  : U_OB,OB = V_OB,OB^-1  from the Winv_K and the V_kj inside OB
-//     rowblk : U_OB,J  = U_OB,OB R_OB,J
-//     rupd   : R_I,J  -= V_I,OB U_OB,J                 (rank 256, fp64 MFMA)  }
+//     syrk   : F_II  -= V_I,OB V_I,OB^T                (rank 256)  } the n^3 * 2/3 bulk: digit-sliced operands,
+//     trinv  : U_OB,OB = V_OB,OB^-1  from the Winv_K and the V_kj inside OB          exact int8 MFMA products,
+//     rowblk : U_OB,J  = U_OB,OB R_OB,J                                              fp64 recombination
+//     rupd   : R_I,J  -= V_I,OB U_OB,J                 (rank 256)  }                 (gemm_i8s.hip)
 //     close  : R_I,OB  = -V_I,OB U_OB,OB
 //
 // Theorem 4.2's two products then run on the bf16 MFMA GEMM with fp32 operands split into
@@ -74,10 +74,13 @@ __global__ __launch_bounds__(1024) void diag_stats_kernel(const float* H, int64_
 }
 
 // F (upper triangle, fp64) = H + lambda I with the dead-input rule applied.
-__global__ void build_F_kernel(const float* H, int64_t ldh, int n, const double* lam, double* F, int64_t ldf) {
+// A NaN or Inf in the upper triangle of H is reported as info[0] = -(1 + row of the entry) (smallest row wins).
+__global__ void build_F_kernel(const float* H, int64_t ldh, int n, const double* lam, double* F, int64_t ldf, int32_t* info) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x, i = blockIdx.y;
   if (j >= n || j < i) return;
-  double v = (double)H[(int64_t)i * ldh + j];
+  const float h = H[(int64_t)i * ldh + j];
+  if (!__builtin_isfinite(h)) atomicMin(info, -(1 + i));
+  double v = (double)h;
   if (i == j) { if (v == 0.0) v = 1.0; v += *lam; }
   F[(int64_t)i * ldf + j] = v;
 }
@@ -453,12 +456,14 @@ __global__ __launch_bounds__(256) void extract_U_kernel(const double* F, int64_t
 }
 
 // bf16 hi/lo split of an fp32 matrix (rows flagged in `zero_rows` read as 0), padded to np x np.
+// `info` (may be NULL): a NaN or Inf among the entries read is reported as info[0] = -(1 + row of the entry).
 __global__ __launch_bounds__(256) void split_rows_kernel(const float* A, int64_t lda, int n, const uint8_t* zero_rows,
-                                                         uint16_t* Ah, uint16_t* Al, int64_t np) {
+                                                         uint16_t* Ah, uint16_t* Al, int64_t np, int32_t* info) {
   const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x, r = blockIdx.y;
   if (c >= np) return;
   float v = 0.f;
   if (r < n && c < n && !(zero_rows && zero_rows[r])) v = A[r * lda + c];
+  if (info && !__builtin_isfinite(v)) atomicMin(info, -(1 + (int)r));
   const uint16_t h = bf16_rne(v);
   Ah[r * np + c] = h;
   Al[r * np + c] = bf16_rne(v - bf16_f32(h));
@@ -498,7 +503,6 @@ PrepLayout prep_layout(int64_t n) {
   L.total = o;
   return L;
 }
-bool g_prep_attr = false;
 
 // The sweep runs as two chains (see gptaq_prepare): the factorisation on the caller's stream, the inverse on
 // a helper stream of the library, tied together with events.  One helper stream and one growing pool of
@@ -532,18 +536,18 @@ extern "C" size_t gptaq_prepare_workspace_bytes(int64_t n) {
 extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, float damp, uint8_t* dead,
                              int32_t* info, void* ws, size_t ws_bytes, void* stream) {
   if (!H || !dXXT || !info || !ws) return GPTAQ_ENULL;
-  if (n <= 0 || ldh < n || n > 65535 * NB / 2 || !(damp >= 0.f)) return GPTAQ_EDIM;
+  // (several kernels put a row index in gridDim.y, which ends at 65535: rows of the padded n x n buffers)
+  if (n <= 0 || ldh < n || n > 65280 || !(damp >= 0.f)) return GPTAQ_EDIM;
   if ((uintptr_t)ws & 255) return GPTAQ_EWORKSPACE;
   const PrepLayout L = prep_layout(n);
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
-  if (!g_prep_attr) {
-    const void* fns[3] = {(const void*)&panel_kernel, (const void*)&inner_update_kernel, (const void*)&trinv_kernel};
-    for (const void* f : fns) {
-      hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, f == fns[2] ? TRINV_LDS : MM_LDS);
-      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
-    }
-    g_prep_attr = true;
+  {
+    static LdsLimitOnce once_panel, once_inner, once_trinv;
+    hipError_t e = once_panel.ensure((const void*)&panel_kernel, MM_LDS);
+    if (e == hipSuccess) e = once_inner.ensure((const void*)&inner_update_kernel, MM_LDS);
+    if (e == hipSuccess) e = once_trinv.ensure((const void*)&trinv_kernel, TRINV_LDS);
+    if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   }
   unsigned char* base = (unsigned char*)ws;
   double* lam = (double*)(base + L.off_lam);
@@ -563,7 +567,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   hipLaunchKernelGGL(diag_stats_kernel, dim3(1), dim3(1024), 0, s, H, ldh, ni, damp, deadbuf, lam, info);
   GPTAQ_LAUNCH_CHECK();
   hipLaunchKernelGGL(build_F_kernel, dim3((unsigned)((n + 255) / 256), (unsigned)n), dim3(256), 0, s, H, ldh, ni,
-                     lam, F, ldf);
+                     lam, F, ldf, info);
   GPTAQ_LAUNCH_CHECK();
 
   // The sweep is two chains of kernels over the outer blocks OB = nob-1 .. 0 (I: rows above, J: columns right):
@@ -636,9 +640,18 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       chk(hipEventRecord(ev_inverted, sb));
     }
     // join: everything after the sweep runs on the caller's stream (blocks 0 and 1 have not been waited for yet)
-    chk(hipStreamWaitEvent(s, side->events[1], 0));
-    if (nob > 1) chk(hipStreamWaitEvent(s, side->events[3], 0));
-    if (!ok) return GPTAQ_ELAUNCH;
+    if (ok) {
+      chk(hipStreamWaitEvent(s, side->events[1], 0));
+      if (nob > 1) chk(hipStreamWaitEvent(s, side->events[3], 0));
+    }
+    if (!ok) {
+      // a launch or an event call failed part-way: whatever the helper stream was given so far must still be behind
+      // the caller's stream when the call returns, so the join is made with a fresh record of the helper stream
+      const hipError_t keep = (hipError_t)gptaq_last_hip_error();
+      if (hipEventRecord(ev_fork, sb) == hipSuccess) hipStreamWaitEvent(s, ev_fork, 0);
+      set_last_hip_error(keep);
+      return GPTAQ_ELAUNCH;
+    }
   }
   // U -> H (fp32) and the bf16 splits; dXXT (dead rows zeroed) split.
   const int64_t np = L.np;
@@ -647,7 +660,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
                      ldh, Uh, Ul, Uth, Utl, np);
   GPTAQ_LAUNCH_CHECK();
   hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)np), dim3(256), 0, s, dXXT, ldh,
-                     ni, deadbuf, Ah, Al, np);
+                     ni, deadbuf, Ah, Al, np, info);
   GPTAQ_LAUNCH_CHECK();
 
   const int tile = gemm_tile_for(n, n);
@@ -667,7 +680,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   // split O (reuses the dXXT split buffers), then P = O U: P[i][j] = sum_{i < a <= j} O[i][a] U[a][j]
   hipLaunchKernelGGL(split_rows_kernel, dim3((unsigned)((np + 255) / 256), (unsigned)np), dim3(256), 0, s, Obuf, np,
-                     ni, (const uint8_t*)nullptr, Ah, Al, np);
+                     ni, (const uint8_t*)nullptr, Ah, Al, np, (int32_t*)nullptr);
   GPTAQ_LAUNCH_CHECK();
   g.C = dXXT; g.ldc = ldh; g.k_mode = 2;
   g.term[0] = {{Ah, Al}, {Uth, Utl}, np, np, 32, 32};

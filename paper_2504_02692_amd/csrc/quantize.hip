@@ -12,7 +12,7 @@
 // columns) split into bf16 hi+lo as the left operand of the trailing GEMM.
 //
 // Trailing update (lines 11-12, Eq. 18):  W[:, i+B:] += [-E | V] [U; P][i:i+B, i+B:] on the
-// MFMA GEMM with three bf16 cross products per term (fp32-accurate).
+// MFMA GEMM with three bf16 cross products per term (operands carried to about 2^-17 relative, fp32 sums).
 #include "common.h"
 
 namespace gptaq {
@@ -53,8 +53,8 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
-// Clip-range search (Section 5.1: "the weight clipping range is searched by minimizing mean squared
-// error"): candidates shrink the min-max range by p = 1 - i / grid, i = 0 .. steps - 1, about its
+// Clip-range search (Section 5.1: the clipping range of the weights is the one with the smallest squared
+// quantisation error): candidates shrink the min-max range by p = 1 - i / grid, i = 0 .. steps - 1, about its
 // zero-point, i.e. scale_i = fp32(p * scale_0 exact) with the zero-point of the full range; the
 // candidate with the smallest sum of squared errors over the group wins, the earlier one on ties.
 struct ClipSearch {
@@ -337,12 +337,10 @@ QLayout q_layout(int64_t m, int64_t n) {
 
 template <int R, int NW>
 hipError_t launch_quant(const QuantArgs& a, hipStream_t s) {
-  static bool attr = false;                      // per instantiation
-  if (!attr) {
-    hipError_t e = hipFuncSetAttribute((const void*)&quant_block_kernel<R, NW>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, Q_LDS);
+  static LdsLimitOnce lds_once;                  // per instantiation
+  {
+    const hipError_t e = lds_once.ensure((const void*)&quant_block_kernel<R, NW>, Q_LDS);
     if (e != hipSuccess) return e;
-    attr = true;
   }
   const int rows_per_wg = NW * R;
   hipLaunchKernelGGL((quant_block_kernel<R, NW>), dim3((a.m + rows_per_wg - 1) / rows_per_wg), dim3(64 * NW), Q_LDS, s, a);

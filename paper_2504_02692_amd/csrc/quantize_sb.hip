@@ -29,7 +29,6 @@
 // finished and its second block into the first one's registers when the block is finished, so every
 // register index in the code is static.
 #include "common.h"
-#include <mutex>
 
 namespace gptaq {
 
@@ -507,14 +506,10 @@ hipError_t launch_near_operands(const float* U, const float* P, int64_t ldh, int
 
 hipError_t launch_quant_sb(const SbArgs& a, hipStream_t s) {
   constexpr int lds = 4 * kSbStage + (int)sizeof(SbShared);
-  static std::once_flag once;
-  static hipError_t attr = hipSuccess;
-  std::call_once(once, [] {
-    attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_sb_kernel<true>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (attr == hipSuccess)
-      attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&quant_sb_kernel<false>), hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  });
-  if (attr != hipSuccess) return attr;
+  static LdsLimitOnce fast_once, slow_once;
+  hipError_t e = fast_once.ensure(reinterpret_cast<const void*>(&quant_sb_kernel<true>), lds);
+  if (e == hipSuccess) e = slow_once.ensure(reinterpret_cast<const void*>(&quant_sb_kernel<false>), lds);
+  if (e != hipSuccess) return e;
   if (a.fast_rows)
     hipLaunchKernelGGL(quant_sb_kernel<true>, dim3((a.m + 63) / 64), dim3(256), lds, s, a);
   else

@@ -22,8 +22,20 @@ __device__ __forceinline__ float up_wave_max(float v) {
   return v;
 }
 
-// One wavefront per token.  range = clip * [min(0, min x), max(0, max x)], scale = range / maxq,
-// zero = rint(-clip*min/scale), x^ = scale * (clamp(rint(x/scale) + zero) - zero), rounded to bf16.
+// double -> bfloat16 with one rounding (nearest, ties to even): truncate to fp32, keep a sticky bit for what was
+// cut off, then round the 24-bit value to 8 bits.
+__device__ __forceinline__ uint16_t up_f64_to_bf16(double p) {
+  const float f = __double2float_rz(p);
+  uint32_t u = __float_as_uint(f);
+  if ((double)f != p) u |= 1u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// One wavefront per token.  range = clip * [min(0, min x), max(0, max x)], scale = fp32(range / maxq) (the few
+// operations per token in fp64, so that the fp32 scale is the correctly rounded quotient),
+// zero = rint(-clip*min/scale), x^ = scale * (clamp(rint(x/scale) + zero) - zero): the rounding of x/scale is decided
+// exactly (see below), the product is exact in fp64 and is rounded once to bf16.
 __global__ __launch_bounds__(256) void fake_quant_tokens_kernel(const uint16_t* X, uint16_t* Y, int tokens, int n,
                                                                 int64_t ldx, int64_t ldy, float maxq, float clip) {
   const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -35,15 +47,21 @@ __global__ __launch_bounds__(256) void fake_quant_tokens_kernel(const uint16_t* 
     mn = fminf(mn, v);
     mx = fmaxf(mx, v);
   }
-  mn = up_wave_min(mn) * clip;
-  mx = up_wave_max(mx) * clip;
-  if (mn == 0.f && mx == 0.f) { mn = -1.f; mx = 1.f; }
-  const float scale = (mx - mn) / maxq;
-  const float zero = rintf(-mn / scale);
+  double lo = (double)up_wave_min(mn) * (double)clip, hi = (double)up_wave_max(mx) * (double)clip;
+  if (lo == 0.0 && hi == 0.0) { lo = -1.0; hi = 1.0; }
+  const float scale = (float)((hi - lo) / (double)maxq);
+  const float zero = (float)rint(-lo / (double)scale);
   for (int c = lane; c < n; c += 64) {
     const float v = up_bf16_f32(x[c]);
-    const float q = fminf(fmaxf(rintf(v / scale) + zero, 0.f), maxq);
-    Y[(int64_t)t * ldy + c] = up_bf16_rne(scale * (q - zero));
+    // rint(v / scale), decided exactly: with few-bit inputs and ranges the quotient sits ON a rounding boundary for
+    // whole families of values, up to the rounding of the scale, and the rounded fp32 quotient alone cannot tell the
+    // side.  The sign of v - (f + 1/2) scale, formed with one rounding by the FMA, can.
+    const float f = floorf(v / scale);
+    const float side = fmaf(-(f + 0.5f), scale, v);
+    const bool odd = ((int)f) & 1;
+    const float r = side > 0.f ? f + 1.f : (side < 0.f ? f : (odd ? f + 1.f : f));
+    const float q = fminf(fmaxf(r + zero, 0.f), maxq);
+    Y[(int64_t)t * ldy + c] = up_f64_to_bf16((double)scale * (double)(q - zero));
   }
 }
 

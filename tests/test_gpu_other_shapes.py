@@ -35,9 +35,12 @@ def layer_of(wl, name):
 
 
 def quantize_rows(wl, layer, U_d, P_d, U64, P64, bits, group, sym, label, nrows=32, Xs=None, Xts=None):
-    """GPU quantize of the whole layer, oracle on sampled rows."""
-    m, n = layer.m, layer.n
-    W0 = synth.make_weights_device(m, n, wl.seed, layer.name, "cuda")
+    """GPU quantize of the whole layer, oracle on sampled rows.  `layer` may be a list of layers that share the
+    input: they are quantised as one stacked matrix, the way bench.py runs q/k/v and gate/up."""
+    layers = layer if isinstance(layer, (list, tuple)) else [layer]
+    n = layers[0].n
+    W0 = torch.cat([synth.make_weights_device(l.m, n, wl.seed, l.name, "cuda") for l in layers], dim=0)
+    m = W0.shape[0]
     Wd = W0.clone()
     ws = B.workspace(B.gptaq_quantize_workspace_bytes(m, n))
     codes, scales, zeros = B.gptaq_quantize_layer(Wd, U_d, P_d, bits, group, sym, wl.blocksize, ws)
@@ -52,8 +55,11 @@ def quantize_rows(wl, layer, U_d, P_d, U64, P64, bits, group, sym, label, nrows=
     assert bool((scales > 0).all()) and bool((zeros == torch.round(zeros)).all())
     if group > 0:                       # the returned grid reproduces the returned weights, whole matrix
         G = n // group
-        rec = (scales[:, :, None] * (codes.view(m, G, group).float() - zeros[:, :, None])).view(m, n)
-        assert torch.allclose(rec, Wd, rtol=1e-6, atol=1e-9)
+        for r0 in range(0, m, 16384):   # (in slabs of rows: the stacked matrices are several GB)
+            r1 = min(m, r0 + 16384)
+            rec = (scales[r0:r1, :, None] * (codes[r0:r1].view(r1 - r0, G, group).float() - zeros[r0:r1, :, None]))
+            assert torch.allclose(rec.view(r1 - r0, n), Wd[r0:r1], rtol=1e-6, atol=1e-9)
+            del rec
 
 
 # ------------------------------------------------------------------------------------- EVA-02 shapes
@@ -78,8 +84,12 @@ def test_eva02_attention_input_whole_oracle(bits, group):
     layer = layer_of(wl, "qkv")
     W = synth.make_weights(layer.m, n, wl.seed, layer.name)
     got = PU.gpu_quantize(W, H, A, bits, group, True, wl.blocksize)
+    # the whole chain (accumulate -> prepare -> quantize on the GPU) against the all-fp64 oracle chain ...
+    PU.check_against_oracle(W, U64, P64, got, bits, group, True, Xb=Xb[::8], Xtb=Xtb[::8],
+                            label=f"eva02 qkv 3072x1024 W{bits} g{group} sym, all-fp64 oracle")
+    # ... and the column loop alone: the oracle's loop fed with the library's own factors
     PU.check_against_oracle(W, H.cpu().numpy().astype(np.float64), A.cpu().numpy().astype(np.float64), got, bits, group,
-                            True, Xb=Xb[::8], Xtb=Xtb[::8], label=f"eva02 qkv 3072x1024 W{bits} g{group} sym")
+                            True, label=f"eva02 qkv 3072x1024 W{bits} g{group} sym, library factors")
 
 
 def test_eva02_mlp_input_4096():
@@ -94,11 +104,11 @@ def test_eva02_mlp_input_4096():
     eu, ep = PU.rel_fro(H.cpu().numpy(), U64), PU.rel_fro(A.cpu().numpy(), P64)
     print(f"[eva02 n={n}] U {eu:.3e} P {ep:.3e}")
     assert eu <= 1e-6 and ep <= 5e-5
-    Uf, Pf = H.cpu().numpy().astype(np.float64), A.cpu().numpy().astype(np.float64)
     tok = torch.arange(0, wl.tokens, 8, device="cuda")
     for bits, group in ((4, 0), (3, 128)):
-        quantize_rows(wl, layer_of(wl, "fc2"), H, A, Uf, Pf, bits, group, True, f"eva02 fc2 W{bits} g{group} sym",
-                      Xs=bits_of(X[tok]), Xts=bits_of(Xt[tok]))
+        # the oracle's loop runs on the fp64 factors (fp64 prepare of the sums checked above), not on the library's
+        quantize_rows(wl, layer_of(wl, "fc2"), H, A, U64, P64, bits, group, True,
+                      f"eva02 fc2 W{bits} g{group} sym, fp64 factors", Xs=bits_of(X[tok]), Xts=bits_of(Xt[tok]))
 
 
 # ----------------------------------------------------------------- large Hessians: reference pieces
@@ -190,6 +200,10 @@ def test_llama70b_attention_input_8192():
     del U, Pd
     quantize_rows(wl, layer_of(wl, "q_proj"), H, A, U64, P64, 3, 128, False, "70b q_proj 8192x8192 W3 g128", Xs=Xs, Xts=Xts)
     quantize_rows(wl, layer_of(wl, "k_proj"), H, A, U64, P64, 2, 64, False, "70b k_proj 1024x8192 W2 g64", Xs=Xs, Xts=Xts)
+    # gate and up (28672 x 8192 each) at full width, stacked to 57344 rows.  Their own input has the same width as this
+    # one and differs from it only in its random draws, so the factors prepared above serve as its U and P here.
+    quantize_rows(wl, [layer_of(wl, "gate_proj"), layer_of(wl, "up_proj")], H, A, U64, P64, 3, 128, False,
+                  "70b gate+up 57344x8192 W3 g128", nrows=20)
 
 
 def test_llama70b_mlp_down_input_28672():
@@ -208,6 +222,31 @@ def test_llama70b_mlp_down_input_28672():
 
 
 # ------------------------------------------------------------------------------ Llama-3-405B shapes
+def test_llama405b_attention_and_mlp_inputs_16384():
+    """The 16384-wide inputs of the Llama-3-405B-shaped set (65536 tokens): accumulate and prepare on the attention
+    input, then q_proj (16384 x 16384), k and v stacked (2048 x 16384) and gate and up stacked (106496 x 16384).
+    The MLP input has the same width and differs only in its random draws, so gate/up are quantised with the same
+    factors (accumulate and prepare at this width are covered by the attention input)."""
+    wl = synth.workload("llama405b")
+    n, iid = 16384, "attn_in"
+    X, Xt, H, A = accumulate_full(wl, iid, n)
+    check_sampled_blocks(wl, iid, n, X, Xt, H, A)
+    rows = rows_of_dxxt(A, [0, n // 3, n - 1100, n - 2])
+    U, Pd = prepare_and_check_large(wl, iid, n, H, A, rows, ncols=4)
+    tok = torch.arange(0, wl.tokens, wl.tokens // 1024, device="cuda")[:1024]
+    Xs, Xts = bits_of(X[tok]), bits_of(Xt[tok])
+    del X, Xt
+    U64, P64 = U.cpu().numpy(), Pd.cpu().numpy()
+    del U, Pd
+    torch.cuda.empty_cache()
+    quantize_rows(wl, layer_of(wl, "q_proj"), H, A, U64, P64, 4, 128, False, "405b q_proj 16384x16384 W4 g128", nrows=14,
+                  Xs=Xs, Xts=Xts)
+    quantize_rows(wl, [layer_of(wl, "k_proj"), layer_of(wl, "v_proj")], H, A, U64, P64, 4, 128, False,
+                  "405b k+v 2048x16384 W4 g128", nrows=14, Xs=Xs, Xts=Xts)
+    quantize_rows(wl, [layer_of(wl, "gate_proj"), layer_of(wl, "up_proj")], H, A, U64, P64, 4, 128, False,
+                  "405b gate+up 106496x16384 W4 g128", nrows=14)
+
+
 def test_llama405b_mlp_down_input_53248():
     wl = synth.workload("llama405b")
     n, iid = 53248, "mlp_mid"

@@ -407,9 +407,79 @@ def test_clip_search_properties():
     assert np.array_equal(out["scales"][:, 0], O.quant_params_mse(w[:, :16], bits, False, grid, steps)[0])
 
 
+def test_scale_hints_cannot_hide_a_wrong_candidate_list(monkeypatch):
+    """The parity protocol lets the oracle take the library's scale when it is one of the oracle's own candidates with
+    an error within 1e-4 of the best (fp32 and fp64 error sums can order two near-equal candidates differently).
+    A planted mistake must not slip through that door: an implementation whose candidate list is off by one
+    (p = 1 - (i + 1) / grid) is rejected, and so is one that searches the right list with the wrong exponent."""
+    from tests import parity_util as PU
+    rng = np.random.default_rng(4)
+    m, n, bits, group, grid, steps = 48, 64, 4, 32, 100, 80
+    W = 0.02 * rng.standard_normal((m, n))
+    X = rng.standard_normal((400, n))
+    H = X.T @ X
+    A = (0.05 * rng.standard_normal((400, n))).T @ X
+    U, P, _ = O.prepare(H, A, 0.01)
+    good = O.quantize_layer(W, U, P, bits, group, False, mse_grid=grid, mse_steps=steps)
+    as_library = lambda r: dict(codes=r["codes"], scales=r["scales"].astype(np.float32), zeros=r["zeros"].astype(np.float32),
+                                What=r["What"].astype(np.float32))
+    PU.check_against_oracle(W, U, P, as_library(good), bits, group, False, label="unchanged oracle", mse=(grid, steps))
+    real = O.quant_params_mse
+
+    def off_by_one(block, bits_, sym, grid_, steps_, hint_scales=None, rel_tol=0.0):
+        # candidates p = 1 - (i + 1) / grid: every scale of this list but the last is also in the right list
+        s, z, _ = real(block * (1.0 - 1.0 / grid_), bits_, sym, grid_, steps_)
+        return s, real(block, bits_, sym, grid_, steps_)[1], 0
+
+    def wrong_exponent(block, bits_, sym, grid_, steps_, hint_scales=None, rel_tol=0.0):
+        # minimises the sum of absolute errors instead of squared errors over the right candidate list
+        maxq = float(2 ** bits_ - 1)
+        lo, hi = np.minimum(block.min(axis=1), 0.0), np.maximum(block.max(axis=1), 0.0)
+        base = (hi - lo) / maxq
+        zero = np.rint(-lo / base.astype(np.float32).astype(np.float64))
+        best_s, best_e = None, None
+        for i in range(steps_):
+            sc = ((1.0 - i / grid_) * base).astype(np.float32).astype(np.float64)
+            q = np.clip(np.rint(block / sc[:, None]) + zero[:, None], 0.0, maxq)
+            e = np.sum(np.abs(sc[:, None] * (q - zero[:, None]) - block), axis=1)
+            if best_e is None:
+                best_s, best_e = sc.copy(), e.copy()
+            else:
+                take = e < best_e
+                best_s, best_e = np.where(take, sc, best_s), np.where(take, e, best_e)
+        return best_s, zero, 0
+
+    for mutant in (off_by_one, wrong_exponent):
+        monkeypatch.setattr(O, "quant_params_mse", mutant)
+        bad = O.quantize_layer(W, U, P, bits, group, False, mse_grid=grid, mse_steps=steps)
+        monkeypatch.setattr(O, "quant_params_mse", real)
+        assert not np.array_equal(bad["scales"], good["scales"])          # the mistake does change the result
+        with pytest.raises(AssertionError):
+            PU.check_against_oracle(W, U, P, as_library(bad), bits, group, False, label=mutant.__name__, mse=(grid, steps))
+
+
+def test_activation_quantiser_hand_worked_example():
+    """Pins fake_quant_activations to values worked out by hand from the definition (tests/golden)."""
+    for line in open(os.path.join(GOLD, "activation_quantiser_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        head, xs, sz, qs, ys = [f.split() for f in line.split("|")]
+        bits, clip = int(head[1]), float(head[2])
+        x = np.array([float(v) for v in xs], np.float32)
+        xb = synth.f32_to_bf16_bits(x)[None, :]
+        assert np.array_equal(synth.bf16_bits_to_f32(xb)[0], x)           # the fixture is exact in bfloat16
+        yb, t, _ = O.fake_quant_activations(xb, bits, clip)
+        scale, zero = float(sz[0]), float(sz[1])
+        y = synth.bf16_bits_to_f32(yb)[0].astype(np.float64)
+        assert np.allclose(y, [float(v) for v in ys], rtol=0, atol=2.0 ** -9 * scale * 4), (head[0], y)
+        assert np.allclose(t[0], x.astype(np.float64) / scale, rtol=1e-7, atol=0)
+        q = np.rint(y / scale + zero)
+        assert np.array_equal(q, [float(v) for v in qs]), (head[0], q)
+
+
 def test_activation_quantiser_and_packing():
     Xb, _ = synth.make_activations(50, 96, 7, "act", 2, 20.0)
-    yb, t = O.fake_quant_activations(Xb, 4, 0.9)
+    yb, t, _ = O.fake_quant_activations(Xb, 4, 0.9)
     x = synth.bf16_bits_to_f32(Xb).astype(np.float64)
     y = synth.bf16_bits_to_f32(yb).astype(np.float64)
     for r in (0, 17, 49):                                  # per token: 16 levels, clipped range, error bound
@@ -419,7 +489,7 @@ def test_activation_quantiser_and_packing():
         assert y[r].min() >= lo - step and y[r].max() <= hi + step
         inside = (x[r] > lo + step) & (x[r] < hi - step)
         assert np.all(np.abs(y[r] - x[r])[inside] <= 0.5 * step * 1.02 + 2.0 ** -8 * np.abs(x[r][inside]))
-    same, _ = O.fake_quant_activations(Xb, 16, 1.0)        # 16 bits, no clipping: (nearly) the identity
+    same, _, _ = O.fake_quant_activations(Xb, 16, 1.0)        # 16 bits, no clipping: (nearly) the identity
     assert np.max(np.abs(synth.bf16_bits_to_f32(same).astype(np.float64) - x)) <= np.abs(x).max() * 2.0 ** -8
     # packing: hand-checked 3-bit stream and a round trip
     assert O.pack_codes(np.array([[1, 2, 3, 4, 5, 6, 7, 0, 1, 2, 3]], np.uint8), 3).tolist() == \
