@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <mutex>
+#include <vector>
 #include "../../include/gptaq.h"
 
 namespace gptaq {
@@ -49,6 +50,7 @@ struct GemmBatch {
   int32_t nprob;
   int32_t tile;          // 128 or 256 (square block tile)
   int32_t ntiles[2];     // filled by launch_gemm
+  int32_t max_wgs;       // 0: one workgroup per tile; else at most this many workgroups, each taking several tiles
   GemmProblem p[2];
 };
 
@@ -109,6 +111,19 @@ hipError_t launch_near_operands(const float* U, const float* P, int64_t ldh, int
 hipError_t launch_quant_sb(const SbArgs& a, hipStream_t s);
 
 void set_last_hip_error(hipError_t e);
+
+// Helper stream of the library: entry points that run two chains of kernels side by side (the factor sweep of
+// gptaq_prepare, the far updates of gptaq_quantize_layer) put one chain on the caller's stream and the other on this
+// stream, tied together with events on both ends, so that to the caller the call is still one asynchronous
+// operation on its own stream.  One stream (default priority) and one growing pool of events per device, created on
+// first use and kept until the process ends.  The mutex serialises the host threads that enqueue through it.
+struct SideStream {
+  hipStream_t stream = nullptr;
+  std::vector<hipEvent_t> events;
+};
+std::mutex& side_stream_mutex();
+// The current device's helper stream with at least `nevents` events; nullptr on failure (call with the mutex held).
+SideStream* side_stream(int nevents);
 
 // Raises a kernel's dynamic LDS limit exactly once per process, whichever host thread comes first; every caller
 // gets the result of that one attempt.

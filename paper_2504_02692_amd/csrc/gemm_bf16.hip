@@ -217,16 +217,16 @@ __device__ __forceinline__ void tile_loop(const GemmProblem& P, unsigned char* s
   wait_vm_and_lds<0>();   // the surplus loads past the last k-tile
 }
 
+// One BT x BT tile of C: tile number `wid` of the batch (see the numbering below).
 template <int BT>
-__global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+__device__ __forceinline__ void gemm_tile(const GemmBatch& b, unsigned char* smem, int wid) {
   constexpr int WT = BT / 2;             // wave tile edge
   constexpr int FR = WT / 32;            // 32x32 MFMA blocks per wave tile edge
 
   // ---- which tile.  Workgroups are dealt round-robin to the 8 XCDs; inside each problem, give every
   // XCD one contiguous run of tiles so that they share operand tiles in that XCD's L2, and so that
   // every XCD gets the same share of each problem (the problems differ in K).
-  int id = blockIdx.x;
+  int id = wid;
   int pi = 0;
   int ntile = b.ntiles[0];
   if (id >= ntile) { pi = 1; id -= ntile; ntile = b.ntiles[1]; }
@@ -339,7 +339,24 @@ __global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
   }
 }
 
-static LdsLimitOnce g_lds256, g_lds128;
+// CAPPED = false: one workgroup per tile.  CAPPED = true: a workgroup takes tiles blockIdx.x, blockIdx.x + gridDim.x,
+// ...: the caller caps the grid to leave compute units to a kernel running beside this one.  The grid is a multiple
+// of 8 then, so a workgroup's tiles all belong to its own XCD's share.
+template <int BT, bool CAPPED>
+__global__ __launch_bounds__(256) void gemm_nt_kernel(GemmBatch b) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  if (!CAPPED) {
+    gemm_tile<BT>(b, smem, blockIdx.x);
+  } else {
+    const int total = b.ntiles[0] + b.ntiles[1];
+    for (int wid = blockIdx.x; wid < total; wid += gridDim.x) {
+      gemm_tile<BT>(b, smem, wid);
+      __syncthreads();                   // the last fragment reads of this tile before the next tile's loads land in LDS
+    }
+  }
+}
+
+static LdsLimitOnce g_lds256, g_lds128, g_lds256c, g_lds128c;
 hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
   GemmBatch bb = b;
   int total = 0;
@@ -349,13 +366,22 @@ hipError_t launch_gemm(const GemmBatch& b, hipStream_t s) {
     total += bb.ntiles[i];
   }
   if (total == 0) return hipSuccess;
-  hipError_t e = g_lds256.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<256>), kLds256);
-  if (e == hipSuccess) e = g_lds128.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<128>), kLds128);
+  hipError_t e = g_lds256.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<256, false>), kLds256);
+  if (e == hipSuccess) e = g_lds128.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<128, false>), kLds128);
+  if (e == hipSuccess) e = g_lds256c.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<256, true>), kLds256);
+  if (e == hipSuccess) e = g_lds128c.ensure(reinterpret_cast<const void*>(&gemm_nt_kernel<128, true>), kLds128);
   if (e != hipSuccess) return e;
-  if (b.tile == 256)
-    hipLaunchKernelGGL(gemm_nt_kernel<256>, dim3(total), dim3(256), kLds256, s, bb);
-  else
-    hipLaunchKernelGGL(gemm_nt_kernel<128>, dim3(total), dim3(256), kLds128, s, bb);
+  if (b.max_wgs > 0 && b.max_wgs < total) {
+    const int grid = b.max_wgs >= 8 ? b.max_wgs / 8 * 8 : 8;
+    if (b.tile == 256)
+      hipLaunchKernelGGL((gemm_nt_kernel<256, true>), dim3(grid), dim3(256), kLds256, s, bb);
+    else
+      hipLaunchKernelGGL((gemm_nt_kernel<128, true>), dim3(grid), dim3(256), kLds128, s, bb);
+  } else if (b.tile == 256) {
+    hipLaunchKernelGGL((gemm_nt_kernel<256, false>), dim3(total), dim3(256), kLds256, s, bb);
+  } else {
+    hipLaunchKernelGGL((gemm_nt_kernel<128, false>), dim3(total), dim3(256), kLds128, s, bb);
+  }
   return hipGetLastError();
 }
 

@@ -504,28 +504,6 @@ PrepLayout prep_layout(int64_t n) {
   return L;
 }
 
-// The sweep runs as two chains (see gptaq_prepare): the factorisation on the caller's stream, the inverse on
-// a helper stream of the library, tied together with events.  One helper stream and one growing pool of
-// events per device, created on first use and kept until the process ends.
-struct SideStream {
-  hipStream_t stream = nullptr;
-  std::vector<hipEvent_t> events;
-};
-std::mutex g_side_mutex;
-SideStream g_side[64];
-// Returns the device's helper stream and makes sure `nevents` events exist; nullptr on failure.
-SideStream* side_stream(int nevents) {
-  int dev = 0;
-  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
-  SideStream& ss = g_side[dev];
-  if (!ss.stream && hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
-  while ((int)ss.events.size() < nevents) {
-    hipEvent_t e;
-    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
-    ss.events.push_back(e);
-  }
-  return &ss;
-}
 }  // namespace
 
 extern "C" size_t gptaq_prepare_workspace_bytes(int64_t n) {
@@ -579,7 +557,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   // factor chain, and it only writes columns >= o0 of F while the factor chain has moved on to columns < o0,
   // so the two overlap: the small sequential kernels of one hide behind the rank-256 products of the other.
   // The V_I,OB digits alternate between two buffers; an event per block and direction orders the streams.
-  std::lock_guard<std::mutex> side_lock(g_side_mutex);
+  std::lock_guard<std::mutex> side_lock(side_stream_mutex());
   const int nob = (int)((n + NBO - 1) / NBO);
   SideStream* side = side_stream(3 * nob + 2);
   if (!side) { set_last_hip_error(hipGetLastError()); return GPTAQ_ELAUNCH; }

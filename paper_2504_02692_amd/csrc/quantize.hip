@@ -14,6 +14,7 @@
 // Trailing update (lines 11-12, Eq. 18):  W[:, i+B:] += [-E | V] [U; P][i:i+B, i+B:] on the
 // MFMA GEMM with three bf16 cross products per term (operands carried to about 2^-17 relative, fp32 sums).
 #include "common.h"
+#include <mutex>
 
 namespace gptaq {
 
@@ -317,19 +318,21 @@ constexpr int SB = 8;                         // column blocks per super-block (
 constexpr int KS = SB * QB;
 struct QLayout {
   int64_t mp, np;
-  size_t off[12], total;
+  size_t off[20], total;
 };
 QLayout q_layout(int64_t m, int64_t n) {
   QLayout L;
   L.mp = round_up(m, 256);
   L.np = round_up(n, 256);
   size_t o = 0;
-  for (int i = 0; i < 12; ++i) {
+  for (int i = 0; i < 20; ++i) {
     L.off[i] = o;
     // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of its updates (all columns from the
     // super-block's first on, plus a tile of padding rows); 8-11: left operands of the updates inside a
-    // super-block (quantize_sb.hip)
-    o += (size_t)(i < 4 ? L.mp * KS * 2 : i < 8 ? (L.np + 256) * KS * 2 : (int64_t)(kSbCols / 16) * kSbCols * 16 * 2);
+    // super-block (quantize_sb.hip); 12-19: a second set of 0-7 (the far update of a super-block runs beside the
+    // next super-block, which writes its own -E, V and right operands)
+    const int k = i < 12 ? i : i - 12;
+    o += (size_t)(k < 4 ? L.mp * KS * 2 : k < 8 ? (L.np + 256) * KS * 2 : (int64_t)(kSbCols / 16) * kSbCols * 16 * 2);
   }
   L.total = o;
   return L;
@@ -388,8 +391,16 @@ __global__ __launch_bounds__(256) void zero_dead_columns_kernel(float* W, int64_
 }  // namespace gptaq
 
 // Algorithm 1, lines 5-13 with one launch of quant_sb_kernel per super-block (column steps and every update
-// inside the super-block) followed by one GEMM for the columns after it.  The result does not depend on the
-// blocking (Eq. 18 only re-associates sums), so the caller's blocksize is not used here.
+// inside the super-block) followed by the update of the columns after it (Eq. 18) on the MFMA GEMM.  The result does
+// not depend on the blocking (Eq. 18 only re-associates sums), so the caller's blocksize is not used here.
+//
+// Two chains.  Super-block k + 1 only needs the far update of super-block k on ITS OWN columns; the update of the
+// columns after it has until super-block k + 2 starts.  So the far update is split by columns: "far1" (the next
+// super-block's columns) stays on the caller's stream, "far2" (everything after) runs on the library's helper stream
+// beside super-block k + 1, which mostly leaves the chip idle (its length is set by the chain of column steps, and a
+// 4096-row layer fills 64 of the 256 CUs).  Every column still receives its updates in super-block order (far1(k)
+// waits for far2(k - 1), which touches the same columns), so results are bit-reproducible.  -E, V and the right
+// operands are double-buffered: far2(k) reads set k & 1 while super-block k + 1 writes the other.
 static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P, int64_t ldh,
                              const uint8_t* dead, int bits, int group, int sym, uint8_t* codes, float* scales,
                              float* zeros, uint16_t* const* buf, hipStream_t s, int terms) {
@@ -413,50 +424,90 @@ static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const 
                        (const uint8_t*)nullptr, a.maxq, sym, 0, 0, scales, zeros);
     GPTAQ_LAUNCH_CHECK();
   }
-  for (int64_t sb0 = 0; sb0 < n; sb0 += kSbCols) {
+  const int nsb = (int)((n + kSbCols - 1) / kSbCols);
+  // (with one or two super-blocks there is no far2; it pays when the super-block kernel leaves most of the chip free:
+  // measured on 4096 x 11008, 6.50 -> 5.77 ms, but 12288 x 4096 with a quarter of the chip for far2, 2.41 -> 2.90 ms)
+  int cus = 256, dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
+  const int sbk_wgs = (int)((m + 63) / 64);
+  const bool two_chains = terms != 0 && nsb >= 3 && sbk_wgs <= cus / 4;
+  std::unique_lock<std::mutex> side_lock(side_stream_mutex(), std::defer_lock);
+  SideStream* side = nullptr;
+  if (two_chains) {
+    side_lock.lock();
+    side = side_stream(2 * nsb + 1);
+    if (!side) { set_last_hip_error(hipGetLastError()); return GPTAQ_ELAUNCH; }
+  }
+  bool ok = true;
+  auto chk = [&](hipError_t e) { if (e != hipSuccess && ok) { ok = false; set_last_hip_error(e); } };
+  auto ev_sbk = [&](int k) { return side->events[2 * k]; };       // super-block k's kernel has finished
+  auto ev_far2 = [&](int k) { return side->events[2 * k + 1]; };  // its far2 update has finished
+  // W[:, c0:c1] += [-E | V] [U; P][super-block rows, c0:c1] from buffer set `set`; the right operands' row 0 is column cbase
+  auto far_update = [&](int set, int64_t c0, int64_t c1, int64_t cbase, hipStream_t st, int max_wgs) {
+    uint16_t* const* ev = buf + (set ? 12 : 0);
+    uint16_t* const* rop = buf + (set ? 16 : 4);
+    const int64_t nt = c1 - c0, ro = (c0 - cbase) * LDE;
+    const int tile = gemm_tile_for(m, nt);
+    GemmBatch b{};
+    b.nprob = 1; b.tile = tile; b.max_wgs = max_wgs;
+    GemmProblem& g = b.p[0];
+    g.C = W + c0; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = kSbCols;
+    g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(round_up(nt, tile) / tile);
+    g.kind = 2; g.nterm = 0; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
+    if (terms & 1) g.term[g.nterm++] = {{ev[0], ev[1]}, {rop[0] + ro, rop[1] + ro}, LDE, LDE, 32, 32};
+    if (terms & 2) g.term[g.nterm++] = {{ev[2], ev[3]}, {rop[2] + ro, rop[3] + ro}, LDE, LDE, 32, 32};
+    ProfScope ps(kProfTrailGemm, st);
+    chk(launch_gemm(b, st));
+  };
+  for (int k = 0; k < nsb && ok; ++k) {
+    const int64_t sb0 = (int64_t)k * kSbCols;
     const int64_t sb_end = n < sb0 + kSbCols ? n : sb0 + kSbCols;
     const bool far = terms != 0 && sb_end < n;
+    const int set = two_chains ? (k & 1) : 0;
+    uint16_t* const* ev = buf + (set ? 12 : 0);
+    uint16_t* const* rop = buf + (set ? 16 : 4);
     a.sb0 = (int)sb0; a.sbw = (int)(sb_end - sb0);
-    a.Eh = far ? buf[0] : nullptr; a.El = buf[1]; a.Vh = buf[2]; a.Vl = buf[3];
+    a.Eh = far ? ev[0] : nullptr; a.El = ev[1]; a.Vh = ev[2]; a.Vl = ev[3];
+    // this super-block's columns must have every earlier update, and its buffer set must be free again
+    if (two_chains && k >= 2) chk(hipStreamWaitEvent(s, ev_far2(k - 2), 0));
     if (terms != 0) {
       ProfScope ps(kProfTrailSplit, s);
-      hipError_t e = launch_near_operands(U, (terms & 2) ? P : nullptr, ldh, (int)n, (int)sb0, a.sbw, buf + 8, s);
-      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+      chk(launch_near_operands(U, (terms & 2) ? P : nullptr, ldh, (int)n, (int)sb0, a.sbw, buf + 8, s));
       if (far) {
         // right operands of the far update: rows of U and P of this super-block, columns after it, transposed
         // to (column x K) and split; a GEMM reads whole tiles of rows, hence the zero rows past n
         const int64_t rows = round_up(n - sb_end, 256) + 256;
         hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(rows / 64), 2, (unsigned)(kSbCols / QB)), dim3(256),
-                           0, s, U, (terms & 2) ? P : U, ldh, (int)n, (int)sb0, QB, (int)sb_end, (int)n, buf[4], buf[5],
-                           buf[6], buf[7], LDE);
-        GPTAQ_LAUNCH_CHECK();
+                           0, s, U, (terms & 2) ? P : U, ldh, (int)n, (int)sb0, QB, (int)sb_end, (int)n, rop[0], rop[1],
+                           rop[2], rop[3], LDE);
+        chk(hipGetLastError());
       }
     }
     {
       ProfScope ps(kProfColumnLoop, s);
-      hipError_t e = launch_quant_sb(a, s);
-      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+      chk(launch_quant_sb(a, s));
     }
-    if (far) {
-      const int64_t nt = n - sb_end;
-      const int tile = gemm_tile_for(m, nt);
-      GemmBatch b{};
-      b.nprob = 1; b.tile = tile;
-      GemmProblem& g = b.p[0];
-      g.C = W + sb_end; g.ldc = ldw; g.M = (int)m; g.N = (int)nt; g.K = kSbCols;
-      g.tiles_m = (int)(round_up(m, tile) / tile); g.tiles_n = (int)(round_up(nt, tile) / tile);
-      g.kind = 2; g.nterm = 0; g.tile_mode = 0; g.k_mode = 0; g.store_mode = 0;
-      if (terms & 1) g.term[g.nterm++] = {{buf[0], buf[1]}, {buf[4], buf[5]}, LDE, LDE, 32, 32};
-      if (terms & 2) g.term[g.nterm++] = {{buf[2], buf[3]}, {buf[6], buf[7]}, LDE, LDE, 32, 32};
-      hipError_t e;
-      {
-        ProfScope ps(kProfTrailGemm, s);
-        e = launch_gemm(b, s);
-      }
-      if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
+    if (!far) continue;
+    const int64_t next_end = n < sb_end + kSbCols ? n : sb_end + kSbCols;
+    if (two_chains && next_end < n) {
+      chk(hipEventRecord(ev_sbk(k), s));
+      chk(hipStreamWaitEvent(side->stream, ev_sbk(k), 0));
+      // far2: beside the next super-block, on the compute units that one leaves free (a 256-tile fills a unit, two
+      // 128-tiles share one)
+      far_update(set, next_end, n, sb_end, side->stream, (cus - sbk_wgs) * (gemm_tile_for(m, n - next_end) == 256 ? 1 : 2));
+      chk(hipEventRecord(ev_far2(k), side->stream));
     }
+    if (two_chains && k >= 1) chk(hipStreamWaitEvent(s, ev_far2(k - 1), 0));   // it adds to the same columns: keep the order
+    far_update(set, sb_end, two_chains ? next_end : n, sb_end, s, 0);   // far1: the next super-block's columns (or all of them)
   }
-  return GPTAQ_OK;
+  if (two_chains) {
+    // whatever was handed to the helper stream is behind the caller's stream when the call returns, error or not
+    const hipError_t keep = (hipError_t)gptaq_last_hip_error();
+    hipEvent_t ev_join = side->events[2 * nsb];
+    if (hipEventRecord(ev_join, side->stream) == hipSuccess) hipStreamWaitEvent(s, ev_join, 0);
+    if (!ok) set_last_hip_error(keep);
+  }
+  return ok ? GPTAQ_OK : GPTAQ_ELAUNCH;
 }
 
 static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P,
@@ -474,8 +525,8 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   unsigned char* base = (unsigned char*)ws;
-  uint16_t* buf[12];
-  for (int i = 0; i < 12; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
+  uint16_t* buf[20];
+  for (int i = 0; i < 20; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
 
   // The super-block kernel takes groups that tile its 16/32/128-column pieces; the clip-range search and other
   // group sizes go through the block-by-block kernels below.

@@ -29,6 +29,26 @@ void prof_mark(int tag, hipStream_t s, bool begin) {
 }
 }  // namespace gptaq
 
+namespace gptaq {
+namespace {
+std::mutex g_side_mutex;
+SideStream g_side[64];
+}  // namespace
+std::mutex& side_stream_mutex() { return g_side_mutex; }
+SideStream* side_stream(int nevents) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+  SideStream& ss = g_side[dev];
+  if (!ss.stream && hipStreamCreateWithFlags(&ss.stream, hipStreamNonBlocking) != hipSuccess) return nullptr;
+  while ((int)ss.events.size() < nevents) {
+    hipEvent_t e;
+    if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
+    ss.events.push_back(e);
+  }
+  return &ss;
+}
+}  // namespace gptaq
+
 extern "C" int gptaq_profile_enable(int mask) {
   using namespace gptaq;
   g_prof.mask = (unsigned)mask;
