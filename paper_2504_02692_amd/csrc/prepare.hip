@@ -9,10 +9,12 @@
 // right-hand side R of the solve V U = I afterwards.  Two block levels:
 //
 //   for every outer block OB of 256 columns, last to first      (I: rows above OB, J: columns right of OB)
-//     for every inner block K of 64 columns in OB, last to first
-//       diag   : F_KK = V_KK V_KK^T,  Winv_K = V_KK^-1                       (one workgroup, LDS)
-//       panel  : V_iK = F_iK Winv_K^T  for all rows i above K
-//       inner  : F_ij -= V_iK V_jK^T   for the column blocks j of OB left of K (rank 64)
+//     for every inner block K of 64 columns in OB, last to first: ONE launch (step_kernel) over the tiles of OB
+//       diag   : F_KK = V_KK V_KK^T                               (by one wavefront of every workgroup, redundantly;
+//                                                                  Winv_K = V_KK^-1 by another, beside the solves)
+//       panel  : V_iK = F_iK V_KK^-T  for the row tiles i of OB above K (triangular solves, one row per lane)
+//       inner  : F_ij -= V_iK V_jK^T   for the tiles (i <= j) of OB left of K (rank 64)
+//     tall   : the same panels and rank-64 updates for the rows above OB, all four inner blocks in one launch
 //     syrk   : F_II  -= V_I,OB V_I,OB^T                (rank 256)  } the n^3 * 2/3 bulk: digit-sliced operands,
 //     trinv  : U_OB,OB = V_OB,OB^-1  from the Winv_K and the V_kj inside OB          exact int8 MFMA products,
 //     rowblk : U_OB,J  = U_OB,OB R_OB,J                                              fp64 recombination
@@ -42,6 +44,7 @@ struct Sweep {
   int32_t* info;
   int o0, o1, jlo;   // current outer block [o0, o1); first inner block of it
   double* Uob;       // 256 x 256 scratch: U_OB,OB
+  double* Vob;       // 256 x 256 scratch: the V_iK with i inside OB (tile row i - jlo, tile column K - jlo)
 };
 
 // ----------------------------------------------------------------------------- statistics
@@ -149,10 +152,15 @@ __device__ __forceinline__ void wave_publish() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-__global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
-  __shared__ __attribute__((aligned(16))) double T[NB * (NB + 2)];   // rows of LDT doubles, later of NB + 2
-  __shared__ __attribute__((aligned(16))) double colb[2][NB];
-  __shared__ double dsh[NB];
+// The two halves are separate functions for one wavefront each, because only the factor is on the critical
+// path of the sweep: the panels inside the outer block are triangular solves with V (solve_wave), and the inverse
+// is made by another wavefront meanwhile.
+// cholesky_wave: LDS T (NB * LDV doubles; rows of LDT doubles while the block is staged, of LDV afterwards),
+// colb (2 * NB), dsh (NB).  Leaves Vt[c * LDV + l] = V[l][c] for l <= c in T and dsh[c] = 1 / V[c][c].
+constexpr int LDV = NB + 2;                   // even row stride: a column of V is read two entries at a time
+constexpr int DIAG_LDS_DOUBLES = NB * LDV + 2 * NB + NB;
+__device__ __forceinline__ void cholesky_wave(const Sweep& a, double* T, double* colb0, double* dsh) {
+  double* colb[2] = {colb0, colb0 + NB};
   const int lane = threadIdx.x;
   const int k0 = a.kb * NB, w = min(NB, a.n - k0);
   // stage the stored (upper) triangle, T[c][r] = F[k0+c][k0+r] for c <= r, then mirror it into rows.
@@ -216,16 +224,18 @@ __global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
     nci = nci_next;
   }
   // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j; 1 / V[j][j] is the same factor.  All columns of V are
-  // published at once: Vt[c][l] = V[l][c] (entries below the diagonal are garbage and are not read), with an
-  // even row stride so that a column is read two entries at a time.
-  constexpr int LDV = NB + 2;
+  // published at once: Vt[c][l] = V[l][c] (entries below the diagonal are garbage and are not read).
   double* Vt = T;
   dsh[lane] = piv > 0.0 ? 1.0 / sqrt(piv) : 1.0;
   wave_publish();
 #pragma unroll
   for (int c = 0; c < NB; ++c) Vt[c * LDV + lane] = s[c] * dsh[c];
   wave_publish();
-  double wv[NB];
+}
+
+// inverse_wave: W = V^-1 from Vt and dsh as cholesky_wave leaves them; lane r gets row r of W in wv.
+__device__ __forceinline__ void inverse_wave(const double* Vt, const double* dsh, double (&wv)[NB]) {
+  const int lane = threadIdx.x & 63;
 #pragma clang loop unroll(full)
   for (int c = 0; c < NB; ++c) {
     double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
@@ -247,69 +257,210 @@ __global__ __launch_bounds__(64) void diag_kernel(Sweep a) {
     const double dc = dsh[c];
     wv[c] = lane == c ? dc : (lane < c ? -dc * ((p0 + p1) + (p2 + p3)) : 0.0);
   }
-  // lane r holds row r of W: through LDS for coalesced stores
-  wave_publish();
-#pragma unroll
-  for (int c = 0; c < NB; ++c) T[lane * LDT + c] = wv[c];
-  wave_publish();
-  double* D = a.Dinv + (int64_t)a.kb * NB * NB;
-#pragma unroll
-  for (int i = 0; i < NB; ++i) D[i * NB + lane] = T[i * LDT + lane];
 }
 
-// ------------------------------------------------------------------------------ panel
-// V_iK = F_iK Winv_K^T for every row tile i above K (in place).  grid: kb workgroups.
-__global__ __launch_bounds__(256) void panel_kernel(Sweep a) {
+// solve_wave: X V^T = Fin for a 64 x 64 tile, V upper triangular as cholesky_wave leaves it (Vt, dsh).  Lane r
+// holds row r: X[r][l] = (Fin[r][l] - sum_{m > l} X[r][m] V[l][m]) / V[l][l], columns from the last to the
+// first; as soon as X[r][l] is known it is taken out of the columns left of l (V[c][l], c < l, is column l of V:
+// broadcast reads of Vt).  Fin is row-major in LDS (row stride LDT) and is only read by this wavefront; the
+// result goes back into the same buffer in the left/right-operand layout of mm64: Xk[l * LDT + r] = X[r][l].
+__device__ __forceinline__ void solve_wave(const double* Vt, const double* dsh, double* buf) {
+  const int lane = threadIdx.x & 63;
+  double f[NB];
+#pragma unroll
+  for (int c = 0; c < NB; ++c) f[c] = buf[lane * LDT + c];
+  wave_publish();                                         // every lane has its row before the buffer is overwritten
+#pragma clang loop unroll(full)
+  for (int l = NB - 1; l >= 0; --l) {
+    const double x = f[l] * dsh[l];
+    buf[l * LDT + lane] = x;
+    // (the reads of a column go out in batches of 16 before the first fma that uses one; one batch of 32 would
+    //  need 128 registers beside the row)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (32 * h >= l) continue;
+      f64x2 q[NB / 4];
+#pragma unroll
+      for (int u = 0; u < NB / 4; ++u)
+        if (32 * h + 2 * u < l) q[u] = *reinterpret_cast<const f64x2*>(Vt + l * LDV + 32 * h + 2 * u);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < NB / 4; ++u) {
+        const int m = 32 * h + 2 * u;
+        if (m < l) f[m] = fma(-x, q[u][0], f[m]);
+        if (m + 1 < l) f[m + 1] = fma(-x, q[u][1], f[m + 1]);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------- step
+// One inner block K = a.kb of the outer block: the factor of F_KK, then the panels and rank-64 updates of the
+// tiles of OB left of K.  With t = K - jlo tiles left of K there is one workgroup per tile pair (i <= j < t)
+// (one workgroup if t == 0): its first wavefront factors F_KK (every workgroup the same arithmetic, so the same
+// bits), two wavefronts solve for V_iK and V_jK, and all four update F_ij.  The workgroups of tile column t-1
+// also store their V_iK (to Vob: the F_iK tiles are still being read by the others); in the last of them a third
+// wavefront inverts V_KK meanwhile (Winv_K, for tall_kernel and trinv_kernel).  One launch per 64 columns, and
+// neither the inverse of V_KK nor a pass of the panel through memory is on the chain from one step to the next.
+constexpr int STEP_LDS = (DIAG_LDS_DOUBLES + 2 * NB * LDT) * 8;
+__global__ __launch_bounds__(256) void step_kernel(Sweep a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  double* As = reinterpret_cast<double*>(smem_raw);
+  double* T = reinterpret_cast<double*>(smem_raw);
+  double* colb = T + NB * LDV;
+  double* dsh = colb + 2 * NB;
+  double* As = dsh + NB;
   double* Bs = As + NB * LDT;
-  const int k0 = a.kb * NB, r0 = blockIdx.x * NB;
-  const double* D = a.Dinv + (int64_t)a.kb * NB * NB;
-  stage_tile(As, a.F, a.ldf, r0, k0, a.n, a.n, false);            // A[i][l] = F[r0+i][k0+l]
-  stage_tile(Bs, D, NB, 0, 0, NB, NB, false);                     // B[l][c] = Winv[c][l]
-  __syncthreads();
-  double acc[4][4];
-  mm64(As, Bs, acc);
+  const int t = a.kb - a.jlo;
+  int li = 0, lj = 0;
+  if (t > 0) {
+    int id = blockIdx.x;
+    while (id > lj) { id -= lj + 1; ++lj; }
+    li = id;
+  }
+  const int k0 = a.kb * NB, ri = (a.jlo + li) * NB, rj = (a.jlo + lj) * NB;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const int c = threadIdx.x & 63, rb = threadIdx.x >> 6;
+  // the tiles this workgroup works on are requested before the factorisation (rows of tiles left of K are all < n)
+  double fij[4][4];
+  if (t > 0) {
+    const bool cok = k0 + c < a.n;
+    double fi[16], fj[16];
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+      fi[p] = cok ? a.F[(int64_t)(ri + rb + 4 * p) * a.ldf + k0 + c] : 0.0;
+      fj[p] = cok ? a.F[(int64_t)(rj + rb + 4 * p) * a.ldf + k0 + c] : 0.0;
+    }
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) fij[p][q] = a.F[(int64_t)(ri + 4 * ty + p) * a.ldf + rj + tx + 16 * q];
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+      As[(rb + 4 * p) * LDT + c] = fi[p];
+      Bs[(rb + 4 * p) * LDT + c] = fj[p];
+    }
+  }
+  if (threadIdx.x < 64) cholesky_wave(a, T, colb, dsh);
+  __syncthreads();
+  if ((t == 0 || (li == t - 1 && lj == t - 1)) && (threadIdx.x >> 6) == 2) {
+    double wv[NB];
+    inverse_wave(T, dsh, wv);
+    const int lane = threadIdx.x & 63;                    // lane r holds row r of Winv: through Bs (not used by a
+#pragma unroll                                            // diagonal pair) for coalesced stores
+    for (int cc = 0; cc < NB; ++cc) Bs[lane * LDT + cc] = wv[cc];
+    wave_publish();
+    double* D = a.Dinv + (int64_t)a.kb * NB * NB;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) D[i * NB + lane] = Bs[i * LDT + lane];
+  }
+  if (t == 0) return;
+  if (threadIdx.x < 64) solve_wave(T, dsh, As);
+  else if (threadIdx.x < 128 && lj != li) solve_wave(T, dsh, Bs);
+  __syncthreads();
+  if (lj == t - 1) {
+#pragma unroll
+    for (int p = 0; p < 16; ++p)
+      a.Vob[(int64_t)(li * NB + rb + 4 * p) * NBO + t * NB + c] = As[c * LDT + rb + 4 * p];
+  }
+  double acc[4][4];
+  mm64(As, lj != li ? Bs : As, acc);                       // A[i][l] = V_iK[i][l], B[l][c] = V_jK[c][l]
 #pragma unroll
   for (int p = 0; p < 4; ++p)
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = r0 + 4 * ty + p, c = k0 + tx + 16 * q;
-      if (r < a.n && c < a.n) a.F[(int64_t)r * a.ldf + c] = acc[p][q];
-    }
+    for (int q = 0; q < 4; ++q) a.F[(int64_t)(ri + 4 * ty + p) * a.ldf + rj + tx + 16 * q] = fij[p][q] - acc[p][q];
 }
 
-// ------------------------------------------------------------------------------ inner
-// F_ij -= V_iK V_jK^T for the column blocks j in [jlo, kb) of the current outer block and the row
-// tiles i <= j.  grid (kb - jlo, kb).
-__global__ __launch_bounds__(256) void inner_update_kernel(Sweep a) {
+// ------------------------------------------------------------------------------- tall
+// The rows above the outer block: for a 64-row tile i, from the last inner block K of OB to the first,
+// V_iK = F_iK Winv_K^T (stored in place) and F_ij -= V_iK V_jK^T for the tiles j of OB left of K, with the
+// V_jK of OB's own rows from Vob.  The four F_i,* tiles stay in registers between the steps; the ten products
+// form a chain, so the right operand of the next one (known in advance) is fetched into registers while the
+// current one runs and goes to the other of two LDS buffers.  grid: jlo workgroups.
+constexpr int TALL_LDS = 3 * NB * LDT * 8;
+__global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
   double* As = reinterpret_cast<double*>(smem_raw);
-  double* Bs = As + NB * LDT;
-  const int I = blockIdx.y, J = a.jlo + blockIdx.x;
-  if (I > J) return;
-  const int k0 = a.kb * NB, r0 = I * NB, c0 = J * NB;
-  stage_tile(As, a.F, a.ldf, r0, k0, a.n, a.n, false);            // A[i][l] = V[r0+i][k0+l]
-  stage_tile(Bs, a.F, a.ldf, c0, k0, a.n, a.n, false);            // B[l][c] = V[c0+c][k0+l]
-  __syncthreads();
-  double acc[4][4];
-  mm64(As, Bs, acc);
+  double* Bs0 = As + NB * LDT;
+  const int r0 = blockIdx.x * NB, nbi = (a.o1 - a.o0 + NB - 1) / NB;
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const int c = threadIdx.x & 63, rb = threadIdx.x >> 6;
+  // right operands in the order of use: for K = nbi-1 .. 0: Winv_K, then V_jK for j = K-1 .. 0
+  double nxt[16];
+  auto fetch = [&](int kl, int j) {                       // j < 0: Winv_kl
+    const double* src = j < 0 ? a.Dinv + (int64_t)(a.jlo + kl) * NB * NB : a.Vob + (int64_t)j * NB * NBO + kl * NB;
+    const int ld = j < 0 ? NB : NBO;
 #pragma unroll
-  for (int p = 0; p < 4; ++p)
+    for (int p = 0; p < 16; ++p) nxt[p] = src[(int64_t)(rb + 4 * p) * ld + c];
+  };
+  auto put_b = [&](double* Bs) {                          // B[l][cc] = src[cc][l]
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int r = r0 + 4 * ty + p, c = c0 + tx + 16 * q;
-      if (r < a.n && c < a.n) a.F[(int64_t)r * a.ldf + c] -= acc[p][q];
+    for (int p = 0; p < 16; ++p) Bs[c * LDT + rb + 4 * p] = nxt[p];
+  };
+  fetch(nbi - 1, -1);
+  double f[4][4][4];
+#pragma unroll
+  for (int b = 0; b < 4; ++b)
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = a.o0 + b * NB + tx + 16 * q;
+        f[b][p][q] = (b < nbi && col < a.n) ? a.F[(int64_t)(r0 + 4 * ty + p) * a.ldf + col] : 0.0;
+      }
+  int flip = 0;
+#pragma unroll
+  for (int kl = 3; kl >= 0; --kl) {
+    if (kl >= nbi) continue;
+    // (the barrier at the end of the product before this one has retired As and the buffer written now)
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) As[(tx + 16 * q) * LDT + 4 * ty + p] = f[kl][p][q];
+    double* Bs = Bs0 + flip * NB * LDT;
+    flip ^= 1;
+    put_b(Bs);
+    if (kl > 0) fetch(kl, kl - 1);
+    __syncthreads();
+    double v[4][4];
+    mm64(As, Bs, v);
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int col = a.o0 + kl * NB + tx + 16 * q;
+        if (col < a.n) a.F[(int64_t)(r0 + 4 * ty + p) * a.ldf + col] = v[p][q];
+      }
+    if (kl == 0) break;
+    __syncthreads();                                      // everyone has read As
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) As[(tx + 16 * q) * LDT + 4 * ty + p] = v[p][q];
+#pragma unroll
+    for (int j = 2; j >= 0; --j) {
+      if (j >= kl) continue;
+      double* Bj = Bs0 + flip * NB * LDT;
+      flip ^= 1;
+      put_b(Bj);
+      if (j > 0) fetch(kl, j - 1); else fetch(kl - 1, -1);
+      __syncthreads();
+      double acc[4][4];
+      mm64(As, Bj, acc);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) f[j][p][q] -= acc[p][q];
     }
+    __syncthreads();                                      // everyone has read As before the next panel overwrites it
+  }
 }
 
 // ------------------------------------------------------------------------------ trinv
 // U_OB,OB = V_OB,OB^-1 from the inner blocks: U_ll = Winv_l and, for k < l,
 // U_kl = -Winv_k sum_{k < j <= l} V_kj U_jl.  One workgroup per block column l; results go to the
 // dense scratch Uob (ld 256, zeros below the diagonal), from which they are copied into F afterwards
-// (the V_kj of F are still being read by the other workgroups).
+// (the other workgroups still read F's block while this one runs).
 // The steps of a block column form a chain of 64^3 products, so what counts is the latency of a step:
 // the finished blocks U_jl stay in LDS (slot j; they are the right operands of all later steps), and the
 // left operand of the next product (V_kj or Winv_k, known in advance) is fetched into registers while
@@ -361,9 +512,9 @@ __global__ __launch_bounds__(256) void trinv_kernel(Sweep a) {
       t -= cnt;
     }
     if (!found) return;
-    const double* src = j >= 0 ? a.F : a.Dinv + (int64_t)(kb0 + k) * NB * NB;
-    const int64_t ld = j >= 0 ? a.ldf : NB;
-    const int r0 = j >= 0 ? a.o0 + k * NB : 0, c0 = j >= 0 ? a.o0 + j * NB : 0, lim = j >= 0 ? a.n : NB;
+    const double* src = j >= 0 ? a.Vob : a.Dinv + (int64_t)(kb0 + k) * NB * NB;
+    const int64_t ld = j >= 0 ? NBO : NB;
+    const int r0 = j >= 0 ? k * NB : 0, c0 = j >= 0 ? j * NB : 0, lim = j >= 0 ? NBO : NB;
 #pragma unroll
     for (int p = 0; p < 16; ++p) {
       const int r = rb + 4 * p;
@@ -477,7 +628,7 @@ namespace {
 struct PrepLayout {
   int64_t np;
   int64_t rp;                      // rows of a sliced operand that spans the whole matrix
-  size_t off_F, off_Dinv, off_lam, off_dead, off_O, off_b[6], off_Uob, off_pl[5], off_sc[5], total;
+  size_t off_F, off_Dinv, off_lam, off_dead, off_O, off_b[6], off_Uob, off_Vob, off_pl[5], off_sc[5], total;
 };
 PrepLayout prep_layout(int64_t n) {
   PrepLayout L;
@@ -492,6 +643,7 @@ PrepLayout prep_layout(int64_t n) {
   L.off_O = take((size_t)L.np * L.np * 4);
   for (int i = 0; i < 6; ++i) L.off_b[i] = take((size_t)L.np * L.np * 2);
   L.off_Uob = take((size_t)NBO * NBO * 8);
+  L.off_Vob = take((size_t)3 * NBO * NBO * 8);      // three in turn: the inverse chain reads a block's while the next two are written
   // sliced operands of the rank-256 products: V_I,OB (two: the helper stream reads one while the next is
   // written), R_OB,J / U_OB,J, and U_OB,OB by rows and by columns
   L.rp = round_up(n, 128);
@@ -521,9 +673,9 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   {
-    static LdsLimitOnce once_panel, once_inner, once_trinv;
-    hipError_t e = once_panel.ensure((const void*)&panel_kernel, MM_LDS);
-    if (e == hipSuccess) e = once_inner.ensure((const void*)&inner_update_kernel, MM_LDS);
+    static LdsLimitOnce once_step, once_tall, once_trinv;
+    hipError_t e = once_step.ensure((const void*)&step_kernel, STEP_LDS);
+    if (e == hipSuccess) e = once_tall.ensure((const void*)&tall_kernel, TALL_LDS);
     if (e == hipSuccess) e = once_trinv.ensure((const void*)&trinv_kernel, TRINV_LDS);
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   }
@@ -538,6 +690,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   const I8Operand &RJs = sl[2], &Urow = sl[3], &Ucol = sl[4];
   const int64_t ldf = round_up(n, 16);
   double* Uob = (double*)(base + L.off_Uob);
+  double* Vob3 = (double*)(base + L.off_Vob);
   uint16_t* bb[6];
   for (int i = 0; i < 6; ++i) bb[i] = (uint16_t*)(base + L.off_b[i]);
   const int ni = (int)n;
@@ -583,12 +736,14 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       a.o0 = o0; a.o1 = o1; a.jlo = o0 / NB;
       // ---- factor chain
       const int kb_hi = (o1 + NB - 1) / NB - 1;
+      // (the inverse chain of block ob + 3, the last reader of this Vob, was waited for before block ob + 1's slices)
+      a.Vob = Vob3 + (size_t)(ob % 3) * NBO * NBO;
       for (int kb = kb_hi; kb >= a.jlo; --kb) {
         a.kb = kb;
-        hipLaunchKernelGGL(diag_kernel, dim3(1), dim3(64), 0, s, a);
-        if (kb > 0) hipLaunchKernelGGL(panel_kernel, dim3(kb), dim3(256), MM_LDS, s, a);
-        if (kb > a.jlo) hipLaunchKernelGGL(inner_update_kernel, dim3(kb - a.jlo, kb), dim3(256), MM_LDS, s, a);
+        const int t = kb - a.jlo;
+        hipLaunchKernelGGL(step_kernel, dim3(t ? t * (t + 1) / 2 : 1), dim3(256), STEP_LDS, s, a);
       }
+      if (a.jlo > 0) hipLaunchKernelGGL(tall_kernel, dim3(a.jlo), dim3(256), TALL_LDS, s, a);
       // this buffer of V_I,OB digits was last read by the inverse chain of block ob + 2
       if (ob + 2 <= nob - 1) chk(hipStreamWaitEvent(s, side->events[2 * (ob + 2) + 1], 0));
       chk(launch_slice_i8(F + o0, ldf, 1, o0, wo, Vs, s));     // V_I,OB, the operand of all four products with it
