@@ -111,6 +111,23 @@ __device__ __forceinline__ void mm64(const double* As, const double* Bs, double 
   }
 }
 
+// acc[i][c] -= sum_l A[i][l] * B[l][c], same layouts (the running tile is the accumulator: no second register tile)
+__device__ __forceinline__ void mm64_sub(const double* As, const double* Bs, double (&acc)[4][4]) {
+  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+#pragma unroll 4
+  for (int l = 0; l < NB; ++l) {
+    double a[4], b[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) a[p] = -As[l * LDT + 4 * ty + p];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) b[q] = Bs[l * LDT + tx + 16 * q];
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[p][q] = fma(a[p], b[q], acc[p][q]);
+  }
+}
+
 // Stage a 64 x 64 tile of a row-major fp64 matrix.  transposed == false: dst[c*LDT + r] = src[r][c]
 // ("k-major A": r is the output row, c the contraction index).  transposed == true:
 // dst[r*LDT + c] = src[r][c].  Out-of-range elements read as 0.
@@ -159,69 +176,87 @@ __device__ __forceinline__ void wave_publish() {
 // colb (2 * NB), dsh (NB).  Leaves Vt[c * LDV + l] = V[l][c] for l <= c in T and dsh[c] = 1 / V[c][c].
 constexpr int LDV = NB + 2;                   // even row stride: a column of V is read two entries at a time
 constexpr int DIAG_LDS_DOUBLES = NB * LDV + 2 * NB + NB;
-__device__ __forceinline__ void cholesky_wave(const Sweep& a, double* T, double* colb0, double* dsh) {
+// On entry T holds the block row-major (row stride LDT; only the upper triangle is read), padded with the
+// identity where the matrix ends; k0 = index of the block's first column (for the report of a bad pivot).
+// Reads of a column of V (LDS, wave-uniform addresses) in inverse_wave and solve_wave go through a ring of RD batches
+// of 8 entries: a batch is requested RD-1 batches before it is used, which covers the LDS latency with the
+// products of the batches in between (one batch ahead did not: 16 products are shorter than a round trip).
+// All indices are compile-time constants once the loops are unrolled.
+constexpr int RQ = 4;                          // f64x2 per batch
+constexpr int RD = 6;                          // ring depth (solve, inverse)
+
+__device__ __forceinline__ double lane_value(double v, int l) {       // v of lane l (l a constant), wave-uniform
+  const uint64_t b = __builtin_bit_cast(uint64_t, v);
+  const uint32_t lo = __builtin_amdgcn_readlane((uint32_t)b, l), hi = __builtin_amdgcn_readlane((uint32_t)(b >> 32), l);
+  return __builtin_bit_cast(double, ((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ void cholesky_wave(const Sweep& a, double* T, double* colb0, double* dsh, int k0) {
   double* colb[2] = {colb0, colb0 + NB};
-  const int lane = threadIdx.x;
-  const int k0 = a.kb * NB, w = min(NB, a.n - k0);
-  // stage the stored (upper) triangle, T[c][r] = F[k0+c][k0+r] for c <= r, then mirror it into rows.
-  // All 64 loads are in flight together (the block was just written by other CUs: ~2 us each way).
-  {
-    double ld[NB];
-#pragma unroll
-    for (int c = 0; c < NB; ++c)
-      ld[c] = (c <= lane && lane < w) ? a.F[(int64_t)(k0 + c) * a.ldf + k0 + lane] : 0.0;
-#pragma unroll
-    for (int c = 0; c < NB; ++c) T[c * LDT + lane] = ld[c];
-  }
-  wave_publish();
+  const int lane = threadIdx.x & 63;
   double s[NB];
 #pragma unroll
-  for (int c = 0; c < NB; ++c) {
-    const double v = c >= lane ? T[lane * LDT + c] : T[c * LDT + lane];
-    s[c] = (lane < w && c < w) ? v : (c == lane ? 1.0 : 0.0);     // identity in the padding
-  }
+  for (int c = 0; c < NB; ++c) s[c] = c >= lane ? T[lane * LDT + c] : T[c * LDT + lane];   // mirrored into rows
+  wave_publish();                                                 // (T is rewritten with another row stride below)
   double piv = 1.0;                                               // S[lane][lane] when its step starts
-  // Step j uses nci = -S[lane][j] / S[j][j] and the published column cb_j.  The column of the next step,
-  // j-1, is downdated and published first, so that its LDS round trip and the reciprocal of the next
-  // pivot overlap with the rest of this step's downdates.
+  // Step j downdates with pivot column j: s[c] += nci * cb[c] for c < j, nci = -S[lane][j] / S[j][j], cb[c] =
+  // S[c][j] = lane c's entry of column j.  The chain from one step to the next is: downdate column j-1, take its
+  // pivot and the entries of lanes j-2 and j-3 out of the registers (v_readlane: no LDS round trip), reciprocal,
+  // next nci.  The other columns [0, j-2) need the whole pivot column in every lane: it is published through LDS
+  // when it is final (one step earlier), read at the top of the step and used around the reciprocal.
+  constexpr int QH = NB / 4;                                      // f64x2 per half column
   colb[(NB - 1) & 1][lane] = s[NB - 1];
-  wave_publish();
-  double nci;
+  double nci, c1, c2;
   {
-    const double sjj = colb[(NB - 1) & 1][NB - 1];
+    const double sjj = lane_value(s[NB - 1], NB - 1);
+    c1 = lane_value(s[NB - 1], NB - 2);
+    c2 = lane_value(s[NB - 1], NB - 3);
     const bool bad = !(sjj > 0.0);
     if (bad && lane == 0) atomicCAS(a.info, 0, k0 + NB);
     piv = lane == NB - 1 ? sjj : piv;
     nci = -(s[NB - 1] * (bad ? 0.0 : fast_rcp(sjj)));
   }
+  wave_publish();
 #pragma clang loop unroll(full)
   for (int j = NB - 1; j >= 1; --j) {
     const double* cb = colb[j & 1];
     double* nb = colb[(j - 1) & 1];
-    s[j - 1] = fma(nci, cb[j - 1], s[j - 1]);
+    const int rest = j - 2;                                       // columns [0, rest) beside the two done first
+    f64x2 q[QH];
+#pragma unroll
+    for (int u = 0; u < QH; ++u)
+      if (2 * u < rest) q[u] = *reinterpret_cast<const f64x2*>(cb + 2 * u);
+    __builtin_amdgcn_sched_barrier(0);
+    s[j - 1] = fma(nci, c1, s[j - 1]);
     nb[lane] = s[j - 1];
-    wave_publish();
-    const double sjj = nb[j - 1];
+    if (j >= 2) s[j - 2] = fma(nci, c2, s[j - 2]);
+    const double sjj = lane_value(s[j - 1], j - 1);
+    if (j >= 2) c1 = lane_value(s[j - 1], j - 2);
+    if (j >= 3) c2 = lane_value(s[j - 1], j - 3);
     const bool bad = !(sjj > 0.0);
     if (bad && lane == 0) atomicCAS(a.info, 0, k0 + j);
     piv = lane == j - 1 ? sjj : piv;
     const double nci_next = -(s[j - 1] * (bad ? 0.0 : fast_rcp(sjj)));
-    // all reads of the published column go out before the first fma that uses one (left to itself the
-    // compiler waits for every single read)
-    {
-      f64x2 q[NB / 2];
 #pragma unroll
-      for (int u = 0; u < NB / 2; ++u)
-        if (2 * u < j - 1) q[u] = *reinterpret_cast<const f64x2*>(cb + 2 * u);
+    for (int u = 0; u < QH; ++u) {
+      if (2 * u < rest) s[2 * u] = fma(nci, q[u][0], s[2 * u]);
+      if (2 * u + 1 < rest) s[2 * u + 1] = fma(nci, q[u][1], s[2 * u + 1]);
+    }
+    if (rest > 2 * QH) {                                          // second half of a long column
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int u = 0; u < NB / 2; ++u) {
-        if (2 * u < j - 1) s[2 * u] = fma(nci, q[u][0], s[2 * u]);
-        if (2 * u + 1 < j - 1) s[2 * u + 1] = fma(nci, q[u][1], s[2 * u + 1]);
+      for (int u = 0; u < QH; ++u)
+        if (2 * QH + 2 * u < rest) q[u] = *reinterpret_cast<const f64x2*>(cb + 2 * QH + 2 * u);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int u = 0; u < QH; ++u) {
+        const int m = 2 * QH + 2 * u;
+        if (m < rest) s[m] = fma(nci, q[u][0], s[m]);
+        if (m + 1 < rest) s[m + 1] = fma(nci, q[u][1], s[m + 1]);
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
     nci = nci_next;
+    wave_publish();                                               // column j-1 is readable from here on
   }
   // V[i][j] = S[i][j] / sqrt(S[j][j]) for i <= j; 1 / V[j][j] is the same factor.  All columns of V are
   // published at once: Vt[c][l] = V[l][c] (entries below the diagonal are garbage and are not read).
@@ -233,142 +268,219 @@ __device__ __forceinline__ void cholesky_wave(const Sweep& a, double* T, double*
   wave_publish();
 }
 
-// inverse_wave: W = V^-1 from Vt and dsh as cholesky_wave leaves them; lane r gets row r of W in wv.
+// inverse_wave: W = V^-1 from Vt and dsh as cholesky_wave leaves them; lane r gets row r of W in wv:
+// W[r][c] = -(sum_{l < c} W[r][l] V[l][c]) / V[c][c] column by column (entries left of the diagonal are zero, so
+// the sum may start at 0).
 __device__ __forceinline__ void inverse_wave(const double* Vt, const double* dsh, double (&wv)[NB]) {
   const int lane = threadIdx.x & 63;
+  f64x2 q[RD][RQ];
+  int pc = 1, ph = 0, pslot = 0;                           // next batch to request: column pc, entries [8 ph, 8 ph + 8)
+  auto request = [&]() {
+    if (pc < NB) {
+#pragma unroll
+      for (int u = 0; u < RQ; ++u)
+        if (2 * RQ * ph + 2 * u < pc) q[pslot][u] = *reinterpret_cast<const f64x2*>(Vt + pc * LDV + 2 * RQ * ph + 2 * u);
+      pslot = (pslot + 1) % RD;
+      if (2 * RQ * (ph + 1) < pc) ++ph; else { ++pc; ph = 0; }
+    }
+  };
+#pragma unroll
+  for (int d = 0; d < RD - 1; ++d) request();
+  int cur = 0;
+  double dc = dsh[0];
 #pragma clang loop unroll(full)
   for (int c = 0; c < NB; ++c) {
     double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
-    {
-      f64x2 q[NB / 2];
+    const double dcur = dc;
+    if (c + 1 < NB) dc = dsh[c + 1];
 #pragma unroll
-      for (int u = 0; u < NB / 2; ++u)
-        if (2 * u < c) q[u] = *reinterpret_cast<const f64x2*>(Vt + c * LDV + 2 * u);
+    for (int h = 0; h < NB / (2 * RQ); ++h) {
+      if (2 * RQ * h >= c) continue;
+      request();
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int l = 0; l < NB; l += 4) {
-        if (l < c) p0 = fma(wv[l], q[l / 2][0], p0);
-        if (l + 1 < c) p1 = fma(wv[l + 1], q[l / 2][1], p1);
-        if (l + 2 < c) p2 = fma(wv[l + 2], q[l / 2 + 1][0], p2);
-        if (l + 3 < c) p3 = fma(wv[l + 3], q[l / 2 + 1][1], p3);
+      for (int u = 0; u < RQ; u += 2) {
+        const int l = 2 * RQ * h + 2 * u;
+        if (l < c) p0 = fma(wv[l], q[cur][u][0], p0);
+        if (l + 1 < c) p1 = fma(wv[l + 1], q[cur][u][1], p1);
+        if (l + 2 < c) p2 = fma(wv[l + 2], q[cur][u + 1][0], p2);
+        if (l + 3 < c) p3 = fma(wv[l + 3], q[cur][u + 1][1], p3);
       }
+      // (the sums are only used by the lanes right of the diagonal; left alone, the compiler moves all the products
+      //  of a column into that branch, behind the reads of all its batches)
+      asm volatile("" : "+v"(p0), "+v"(p1), "+v"(p2), "+v"(p3));
       __builtin_amdgcn_sched_barrier(0);
+      cur = (cur + 1) % RD;
     }
-    const double dc = dsh[c];
-    wv[c] = lane == c ? dc : (lane < c ? -dc * ((p0 + p1) + (p2 + p3)) : 0.0);
+    wv[c] = lane == c ? dcur : (lane < c ? -dcur * ((p0 + p1) + (p2 + p3)) : 0.0);
   }
 }
 
 // solve_wave: X V^T = Fin for a 64 x 64 tile, V upper triangular as cholesky_wave leaves it (Vt, dsh).  Lane r
 // holds row r: X[r][l] = (Fin[r][l] - sum_{m > l} X[r][m] V[l][m]) / V[l][l], columns from the last to the
-// first; as soon as X[r][l] is known it is taken out of the columns left of l (V[c][l], c < l, is column l of V:
-// broadcast reads of Vt).  Fin is row-major in LDS (row stride LDT) and is only read by this wavefront; the
-// result goes back into the same buffer in the left/right-operand layout of mm64: Xk[l * LDT + r] = X[r][l].
+// first; as soon as X[r][l] is known it is taken out of the columns left of l (V[c][l], c < l, is column l of V).
+// Fin is row-major in LDS (row stride LDT) and is only read by this wavefront; the result goes back into the same
+// buffer in the left/right-operand layout of mm64: Xk[l * LDT + r] = X[r][l].
 __device__ __forceinline__ void solve_wave(const double* Vt, const double* dsh, double* buf) {
   const int lane = threadIdx.x & 63;
   double f[NB];
 #pragma unroll
   for (int c = 0; c < NB; ++c) f[c] = buf[lane * LDT + c];
   wave_publish();                                         // every lane has its row before the buffer is overwritten
+  f64x2 q[RD][RQ];
+  int pl = NB - 1, ph = 0, pslot = 0;                      // next batch to request: column pl, entries [8 ph, 8 ph + 8)
+  auto request = [&]() {
+    if (pl >= 1) {
+#pragma unroll
+      for (int u = 0; u < RQ; ++u)
+        if (2 * RQ * ph + 2 * u < pl) q[pslot][u] = *reinterpret_cast<const f64x2*>(Vt + pl * LDV + 2 * RQ * ph + 2 * u);
+      pslot = (pslot + 1) % RD;
+      if (2 * RQ * (ph + 1) < pl) ++ph; else { --pl; ph = 0; }
+    }
+  };
+#pragma unroll
+  for (int d = 0; d < RD - 1; ++d) request();
+  int cur = 0;
+  double dl = dsh[NB - 1];
 #pragma clang loop unroll(full)
   for (int l = NB - 1; l >= 0; --l) {
-    const double x = f[l] * dsh[l];
+    const double x = f[l] * dl;
     buf[l * LDT + lane] = x;
-    // (the reads of a column go out in batches of 16 before the first fma that uses one; one batch of 32 would
-    //  need 128 registers beside the row)
+    if (l > 0) dl = dsh[l - 1];
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      if (32 * h >= l) continue;
-      f64x2 q[NB / 4];
-#pragma unroll
-      for (int u = 0; u < NB / 4; ++u)
-        if (32 * h + 2 * u < l) q[u] = *reinterpret_cast<const f64x2*>(Vt + l * LDV + 32 * h + 2 * u);
+    for (int h = 0; h < NB / (2 * RQ); ++h) {
+      if (2 * RQ * h >= l) continue;
+      request();
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int u = 0; u < NB / 4; ++u) {
-        const int m = 32 * h + 2 * u;
-        if (m < l) f[m] = fma(-x, q[u][0], f[m]);
-        if (m + 1 < l) f[m + 1] = fma(-x, q[u][1], f[m + 1]);
+      for (int u = 0; u < RQ; ++u) {
+        const int m = 2 * RQ * h + 2 * u;
+        if (m < l) f[m] = fma(-x, q[cur][u][0], f[m]);
+        if (m + 1 < l) f[m + 1] = fma(-x, q[cur][u][1], f[m + 1]);
       }
       __builtin_amdgcn_sched_barrier(0);
+      cur = (cur + 1) % RD;
     }
   }
 }
 
-// ------------------------------------------------------------------------------- step
-// One inner block K = a.kb of the outer block: the factor of F_KK, then the panels and rank-64 updates of the
-// tiles of OB left of K.  With t = K - jlo tiles left of K there is one workgroup per tile pair (i <= j < t)
-// (one workgroup if t == 0): its first wavefront factors F_KK (every workgroup the same arithmetic, so the same
-// bits), two wavefronts solve for V_iK and V_jK, and all four update F_ij.  The workgroups of tile column t-1
-// also store their V_iK (to Vob: the F_iK tiles are still being read by the others); in the last of them a third
-// wavefront inverts V_KK meanwhile (Winv_K, for tall_kernel and trinv_kernel).  One launch per 64 columns, and
-// neither the inverse of V_KK nor a pass of the panel through memory is on the chain from one step to the next.
-constexpr int STEP_LDS = (DIAG_LDS_DOUBLES + 2 * NB * LDT) * 8;
-__global__ __launch_bounds__(256) void step_kernel(Sweep a) {
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-  double* T = reinterpret_cast<double*>(smem_raw);
-  double* colb = T + NB * LDV;
-  double* dsh = colb + 2 * NB;
-  double* As = dsh + NB;
-  double* Bs = As + NB * LDT;
-  const int t = a.kb - a.jlo;
-  int li = 0, lj = 0;
-  if (t > 0) {
-    int id = blockIdx.x;
-    while (id > lj) { id -= lj + 1; ++lj; }
-    li = id;
+// ------------------------------------------------------------------------------- outer block
+// The whole factorisation of the 256 x 256 diagonal block of an outer block in ONE workgroup: its ten 64 x 64
+// tiles (upper triangle) are read once and never go back to memory in between.  Eight wavefronts in two groups
+// with separate programs (and so separate register allocations: the tiles fill most of the registers of the
+// first group, a factorisation those of a wavefront of the second); both run the same number of barriers.
+// For K = 3 .. 0 (inner blocks):
+//   wavefront 4 factors tile (K, K) (cholesky_wave);                                             | barrier
+//   wavefronts 4 .. 4+K-1 solve for the panels V_iK, one tile each, wavefront 7 inverts V_KK;    | barrier
+//   wavefronts 0-3 store the V_iK and update the tiles (i <= j < K) they hold in registers:
+//   F_ij -= V_iK V_jK^T (mm64);                                                                  | barrier
+//   wavefronts 0-3 move column K-1 of the tiles to LDS (tile (K-1, K-1) to T, the others to the slots). | barrier
+// Outputs: V_iK to Vob (for tall_kernel and trinv_kernel), Winv_K to Dinv.  Tiles past the end of the matrix are
+// identity / zero padding and are carried along (only the last outer block of a ragged n has any).
+constexpr int OBF_LDS = (DIAG_LDS_DOUBLES + 3 * NB * LDT) * 8;
+struct ObfShared { double *T, *colb, *dsh, *slot0; };
+
+template <int KB>
+__device__ __forceinline__ void obf_seq_step(const Sweep& a, const ObfShared& sh, int nbi) {
+  const int w = (threadIdx.x >> 6) - 4, lane = threadIdx.x & 63;
+  if (w == 0) cholesky_wave(a, sh.T, sh.colb, sh.dsh, (a.jlo + KB) * NB);
+  __syncthreads();
+  if (w == 3 && KB < nbi) {
+    double wv[NB];
+    inverse_wave(sh.T, sh.dsh, wv);
+    double* D = a.Dinv + (int64_t)(a.jlo + KB) * NB * NB;
+#pragma unroll
+    for (int cc = 0; cc < NB; ++cc) D[lane * NB + cc] = wv[cc];
   }
-  const int k0 = a.kb * NB, ri = (a.jlo + li) * NB, rj = (a.jlo + lj) * NB;
+  if constexpr (KB > 0) {
+    if (w < KB) solve_wave(sh.T, sh.dsh, sh.slot0 + w * NB * LDT);
+    __syncthreads();
+    __syncthreads();
+    __syncthreads();
+  }
+}
+
+template <int KB>
+__device__ __forceinline__ void obf_mm_step(const Sweep& a, const ObfShared& sh, double (&tg)[6][4][4]) {
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int c = threadIdx.x & 63, rb = threadIdx.x >> 6;
-  // the tiles this workgroup works on are requested before the factorisation (rows of tiles left of K are all < n)
-  double fij[4][4];
-  if (t > 0) {
-    const bool cok = k0 + c < a.n;
-    double fi[16], fj[16];
-#pragma unroll
-    for (int p = 0; p < 16; ++p) {
-      fi[p] = cok ? a.F[(int64_t)(ri + rb + 4 * p) * a.ldf + k0 + c] : 0.0;
-      fj[p] = cok ? a.F[(int64_t)(rj + rb + 4 * p) * a.ldf + k0 + c] : 0.0;
-    }
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) fij[p][q] = a.F[(int64_t)(ri + 4 * ty + p) * a.ldf + rj + tx + 16 * q];
-#pragma unroll
-    for (int p = 0; p < 16; ++p) {
-      As[(rb + 4 * p) * LDT + c] = fi[p];
-      Bs[(rb + 4 * p) * LDT + c] = fj[p];
-    }
-  }
-  if (threadIdx.x < 64) cholesky_wave(a, T, colb, dsh);
+  auto slot = [&](int i) { return sh.slot0 + i * NB * LDT; };
   __syncthreads();
-  if ((t == 0 || (li == t - 1 && lj == t - 1)) && (threadIdx.x >> 6) == 2) {
-    double wv[NB];
-    inverse_wave(T, dsh, wv);
-    const int lane = threadIdx.x & 63;                    // lane r holds row r of Winv: through Bs (not used by a
-#pragma unroll                                            // diagonal pair) for coalesced stores
-    for (int cc = 0; cc < NB; ++cc) Bs[lane * LDT + cc] = wv[cc];
-    wave_publish();
-    double* D = a.Dinv + (int64_t)a.kb * NB * NB;
+  if constexpr (KB > 0) {
+    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < NB; ++i) D[i * NB + lane] = Bs[i * LDT + lane];
+    for (int i = 0; i < KB; ++i)
+#pragma unroll
+      for (int p = 0; p < 16; ++p)
+        a.Vob[(int64_t)(i * NB + rb + 4 * p) * NBO + KB * NB + c] = slot(i)[c * LDT + rb + 4 * p];
+#pragma unroll
+    for (int j = 0; j < KB; ++j)
+#pragma unroll
+      for (int i = 0; i <= j; ++i) {
+        mm64_sub(slot(i), slot(j), tg[j * (j + 1) / 2 + i]);   // A[r][l] = V_iK[r][l], B[l][cc] = V_jK[cc][l]
+      }
+    __syncthreads();                                          // everyone is done with the slots (T since the solves)
+#pragma unroll
+    for (int i = 0; i < KB; ++i) {
+      double* dst = i == KB - 1 ? sh.T : slot(i);
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + tx + 16 * q] = tg[(KB - 1) * KB / 2 + i][p][q];
+    }
+    __syncthreads();
   }
-  if (t == 0) return;
-  if (threadIdx.x < 64) solve_wave(T, dsh, As);
-  else if (threadIdx.x < 128 && lj != li) solve_wave(T, dsh, Bs);
-  __syncthreads();
-  if (lj == t - 1) {
+}
+
+__global__ __launch_bounds__(512) void ob_factor_kernel(Sweep a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  ObfShared sh;
+  sh.T = reinterpret_cast<double*>(smem_raw);
+  sh.colb = sh.T + NB * LDV;
+  sh.dsh = sh.colb + 2 * NB;
+  sh.slot0 = sh.dsh + NB;
+  const int nbi = (a.o1 - a.o0 + NB - 1) / NB;
+  auto at = [&](int row, int col) {                           // identity where the matrix ends
+    return (row < a.n && col < a.n) ? a.F[(int64_t)row * a.ldf + col] : (row == col ? 1.0 : 0.0);
+  };
+  if (threadIdx.x < 256) {
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    // tile (i, j), i <= j < 3, lives in tg[j * (j + 1) / 2 + i], thread (ty, tx) holding rows 4 ty + p, columns tx + 16 q
+    double tg[6][4][4];
 #pragma unroll
-    for (int p = 0; p < 16; ++p)
-      a.Vob[(int64_t)(li * NB + rb + 4 * p) * NBO + t * NB + c] = As[c * LDT + rb + 4 * p];
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+      for (int i = 0; i <= j; ++i)
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            tg[j * (j + 1) / 2 + i][p][q] = at(a.o0 + i * NB + 4 * ty + p, a.o0 + j * NB + tx + 16 * q);
+    __syncthreads();
+    obf_mm_step<3>(a, sh, tg);
+    obf_mm_step<2>(a, sh, tg);
+    obf_mm_step<1>(a, sh, tg);
+    obf_mm_step<0>(a, sh, tg);
+  } else {
+    const int c = threadIdx.x & 63, rb = (threadIdx.x >> 6) - 4;
+    // column 3 of the tiles: (3, 3) to T, the others to the slots, row-major
+    double ld[4][16];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int p = 0; p < 16; ++p) ld[i][p] = at(a.o0 + i * NB + rb + 4 * p, a.o0 + 3 * NB + c);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      double* dst = i < 3 ? sh.slot0 + i * NB * LDT : sh.T;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) dst[(rb + 4 * p) * LDT + c] = ld[i][p];
+    }
+    __syncthreads();
+    obf_seq_step<3>(a, sh, nbi);
+    obf_seq_step<2>(a, sh, nbi);
+    obf_seq_step<1>(a, sh, nbi);
+    obf_seq_step<0>(a, sh, nbi);
   }
-  double acc[4][4];
-  mm64(As, lj != li ? Bs : As, acc);                       // A[i][l] = V_iK[i][l], B[l][c] = V_jK[c][l]
-#pragma unroll
-  for (int p = 0; p < 4; ++p)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) a.F[(int64_t)(ri + 4 * ty + p) * a.ldf + rj + tx + 16 * q] = fij[p][q] - acc[p][q];
 }
 
 // ------------------------------------------------------------------------------- tall
@@ -673,8 +785,8 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   {
-    static LdsLimitOnce once_step, once_tall, once_trinv;
-    hipError_t e = once_step.ensure((const void*)&step_kernel, STEP_LDS);
+    static LdsLimitOnce once_obf, once_tall, once_trinv;
+    hipError_t e = once_obf.ensure((const void*)&ob_factor_kernel, OBF_LDS);
     if (e == hipSuccess) e = once_tall.ensure((const void*)&tall_kernel, TALL_LDS);
     if (e == hipSuccess) e = once_trinv.ensure((const void*)&trinv_kernel, TRINV_LDS);
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
@@ -735,14 +847,9 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
       hipEvent_t ev_factored = side->events[2 * ob], ev_inverted = side->events[2 * ob + 1];
       a.o0 = o0; a.o1 = o1; a.jlo = o0 / NB;
       // ---- factor chain
-      const int kb_hi = (o1 + NB - 1) / NB - 1;
       // (the inverse chain of block ob + 3, the last reader of this Vob, was waited for before block ob + 1's slices)
       a.Vob = Vob3 + (size_t)(ob % 3) * NBO * NBO;
-      for (int kb = kb_hi; kb >= a.jlo; --kb) {
-        a.kb = kb;
-        const int t = kb - a.jlo;
-        hipLaunchKernelGGL(step_kernel, dim3(t ? t * (t + 1) / 2 : 1), dim3(256), STEP_LDS, s, a);
-      }
+      hipLaunchKernelGGL(ob_factor_kernel, dim3(1), dim3(512), OBF_LDS, s, a);
       if (a.jlo > 0) hipLaunchKernelGGL(tall_kernel, dim3(a.jlo), dim3(256), TALL_LDS, s, a);
       // this buffer of V_I,OB digits was last read by the inverse chain of block ob + 2
       if (ob + 2 <= nob - 1) chk(hipStreamWaitEvent(s, side->events[2 * (ob + 2) + 1], 0));
