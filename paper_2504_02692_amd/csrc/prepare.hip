@@ -31,7 +31,7 @@ namespace gptaq {
 
 constexpr int NB = 64;
 typedef __attribute__((ext_vector_type(2))) double f64x2;
-constexpr int LDT = 65;                       // padded LDS row (doubles)
+constexpr int LDT = 66;                       // padded LDS row (doubles); even, so that two entries are one 16-byte read
 constexpr int MM_LDS = 2 * NB * LDT * 8;      // bytes for two staged tiles
 
 constexpr int NBO = 256;                      // outer block (columns per rank-256 update)
@@ -90,42 +90,59 @@ __global__ void build_F_kernel(const float* H, int64_t ldh, int n, const double*
 
 // ------------------------------------------------------------------- 64 x 64 x 64 in LDS
 // out[i][c] = sum_l A[i][l] * B[l][c] with As[l*LDT + i], Bs[l*LDT + c]; thread (ty, tx)
-// owns rows 4ty..4ty+3 and columns tx + 16q.
-__device__ __forceinline__ void mm64(const double* As, const double* Bs, double acc[4][4]) {
+// owns rows 4ty..4ty+3 and columns 4tx..4tx+3, so that its four entries of a row of As and of Bs are two
+// 16-byte LDS reads each.  Measured: a product takes ~10K clocks on a CU, i.e. a wavefront issues its 16
+// v_fma_f64 of a step in ~150 clocks, with 8- or 16-byte reads, with or without the read-ahead below, with one or
+// two wavefronts per SIMD alike: the fp64 FMA rate is the bound (~30 TFLOP/s chip-wide at this rate).
+// The reads of step l + 1 are issued before the products of step l (two register sets): left to itself the
+// compiler reads into the same registers every step and waits for them before the first product.
+struct MmRegs { f64x2 a0, a1, b0, b1; };
+__device__ __forceinline__ void mm64_read(MmRegs& r, const double* pa, const double* pb) {
+  r.a0 = *reinterpret_cast<const f64x2*>(pa);
+  r.a1 = *reinterpret_cast<const f64x2*>(pa + 2);
+  r.b0 = *reinterpret_cast<const f64x2*>(pb);
+  r.b1 = *reinterpret_cast<const f64x2*>(pb + 2);
+}
+template <bool SUB>
+__device__ __forceinline__ void mm64_mul(const MmRegs& r, double (&acc)[4][4]) {
+  const double a[4] = {SUB ? -r.a0[0] : r.a0[0], SUB ? -r.a0[1] : r.a0[1], SUB ? -r.a1[0] : r.a1[0], SUB ? -r.a1[1] : r.a1[1]};
+  const double b[4] = {r.b0[0], r.b0[1], r.b1[0], r.b1[1]};
+#pragma unroll
+  for (int p = 0; p < 4; ++p)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[p][q] = fma(a[p], b[q], acc[p][q]);
+}
+template <bool SUB>
+__device__ __forceinline__ void mm64_core(const double* As, const double* Bs, double (&acc)[4][4]) {
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+  const double* pa = As + 4 * ty;
+  const double* pb = Bs + 4 * tx;
+  MmRegs r0, r1;
+  mm64_read(r0, pa, pb);
+#pragma clang loop unroll(disable)
+  for (int l = 0; l < NB; l += 2) {
+    mm64_read(r1, pa + (l + 1) * LDT, pb + (l + 1) * LDT);
+    __builtin_amdgcn_sched_barrier(0);
+    mm64_mul<SUB>(r0, acc);
+    __builtin_amdgcn_sched_barrier(0);
+    if (l + 2 < NB) mm64_read(r0, pa + (l + 2) * LDT, pb + (l + 2) * LDT);
+    __builtin_amdgcn_sched_barrier(0);
+    mm64_mul<SUB>(r1, acc);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+}
+
+__device__ __forceinline__ void mm64(const double* As, const double* Bs, double (&acc)[4][4]) {
 #pragma unroll
   for (int p = 0; p < 4; ++p)
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[p][q] = 0.0;
-#pragma unroll 4
-  for (int l = 0; l < NB; ++l) {
-    double a[4], b[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) a[p] = As[l * LDT + 4 * ty + p];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) b[q] = Bs[l * LDT + tx + 16 * q];
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) acc[p][q] = fma(a[p], b[q], acc[p][q]);
-  }
+  mm64_core<false>(As, Bs, acc);
 }
 
 // acc[i][c] -= sum_l A[i][l] * B[l][c], same layouts (the running tile is the accumulator: no second register tile)
 __device__ __forceinline__ void mm64_sub(const double* As, const double* Bs, double (&acc)[4][4]) {
-  const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-#pragma unroll 4
-  for (int l = 0; l < NB; ++l) {
-    double a[4], b[4];
-#pragma unroll
-    for (int p = 0; p < 4; ++p) a[p] = -As[l * LDT + 4 * ty + p];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) b[q] = Bs[l * LDT + tx + 16 * q];
-#pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) acc[p][q] = fma(a[p], b[q], acc[p][q]);
-  }
+  mm64_core<true>(As, Bs, acc);
 }
 
 // Stage a 64 x 64 tile of a row-major fp64 matrix.  transposed == false: dst[c*LDT + r] = src[r][c]
@@ -426,7 +443,7 @@ __device__ __forceinline__ void obf_mm_step(const Sweep& a, const ObfShared& sh,
 #pragma unroll
       for (int p = 0; p < 4; ++p)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + tx + 16 * q] = tg[(KB - 1) * KB / 2 + i][p][q];
+        for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + 4 * tx + q] = tg[(KB - 1) * KB / 2 + i][p][q];
     }
     __syncthreads();
   }
@@ -445,7 +462,7 @@ __global__ __launch_bounds__(512) void ob_factor_kernel(Sweep a) {
   };
   if (threadIdx.x < 256) {
     const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-    // tile (i, j), i <= j < 3, lives in tg[j * (j + 1) / 2 + i], thread (ty, tx) holding rows 4 ty + p, columns tx + 16 q
+    // tile (i, j), i <= j < 3, lives in tg[j * (j + 1) / 2 + i], thread (ty, tx) holding rows 4 ty + p, columns 4 tx + q
     double tg[6][4][4];
 #pragma unroll
     for (int j = 0; j < 3; ++j)
@@ -455,7 +472,7 @@ __global__ __launch_bounds__(512) void ob_factor_kernel(Sweep a) {
         for (int p = 0; p < 4; ++p)
 #pragma unroll
           for (int q = 0; q < 4; ++q)
-            tg[j * (j + 1) / 2 + i][p][q] = at(a.o0 + i * NB + 4 * ty + p, a.o0 + j * NB + tx + 16 * q);
+            tg[j * (j + 1) / 2 + i][p][q] = at(a.o0 + i * NB + 4 * ty + p, a.o0 + j * NB + 4 * tx + q);
     __syncthreads();
     obf_mm_step<3>(a, sh, tg);
     obf_mm_step<2>(a, sh, tg);
@@ -517,7 +534,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
     for (int p = 0; p < 4; ++p)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = a.o0 + b * NB + tx + 16 * q;
+        const int col = a.o0 + b * NB + 4 * tx + q;
         f[b][p][q] = (b < nbi && col < a.n) ? a.F[(int64_t)(r0 + 4 * ty + p) * a.ldf + col] : 0.0;
       }
   int flip = 0;
@@ -528,7 +545,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) As[(tx + 16 * q) * LDT + 4 * ty + p] = f[kl][p][q];
+      for (int q = 0; q < 4; ++q) As[(4 * tx + q) * LDT + 4 * ty + p] = f[kl][p][q];
     double* Bs = Bs0 + flip * NB * LDT;
     flip ^= 1;
     put_b(Bs);
@@ -540,7 +557,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
     for (int p = 0; p < 4; ++p)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = a.o0 + kl * NB + tx + 16 * q;
+        const int col = a.o0 + kl * NB + 4 * tx + q;
         if (col < a.n) a.F[(int64_t)(r0 + 4 * ty + p) * a.ldf + col] = v[p][q];
       }
     if (kl == 0) break;
@@ -548,7 +565,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) As[(tx + 16 * q) * LDT + 4 * ty + p] = v[p][q];
+      for (int q = 0; q < 4; ++q) As[(4 * tx + q) * LDT + 4 * ty + p] = v[p][q];
 #pragma unroll
     for (int j = 2; j >= 0; --j) {
       if (j >= kl) continue;
@@ -592,13 +609,13 @@ __global__ __launch_bounds__(256) void trinv_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) a.Uob[(int64_t)(k * NB + 4 * ty + p) * 256 + l * NB + tx + 16 * q] = v[p][q];
+      for (int q = 0; q < 4; ++q) a.Uob[(int64_t)(k * NB + 4 * ty + p) * 256 + l * NB + 4 * tx + q] = v[p][q];
   };
   auto put_slot = [&](double* dst, const double (&v)[4][4], double sign) {    // right-operand layout: dst[m * LDT + c]
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + tx + 16 * q] = sign * v[p][q];
+      for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + 4 * tx + q] = sign * v[p][q];
   };
   double acc[4][4];
   {
@@ -606,7 +623,7 @@ __global__ __launch_bounds__(256) void trinv_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) acc[p][q] = D[(4 * ty + p) * NB + tx + 16 * q];
+      for (int q = 0; q < 4; ++q) acc[p][q] = D[(4 * ty + p) * NB + 4 * tx + q];
   }
   put_global(l, acc);
   if (l == 0) return;
