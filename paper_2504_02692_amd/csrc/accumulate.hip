@@ -108,13 +108,21 @@ static hipError_t launch_products(const uint16_t* oX, const uint16_t* oHi, const
   return launch_gemm(b, s);
 }
 
-static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx, float* H,
-                           float* dXXT, int64_t ldh, void* ws, size_t ws_bytes, void* stream) {
-  if (!X || !Xtilde || !H || !dXXT || !ws) return GPTAQ_ENULL;
+// the argument checks that need no workspace
+static int accumulate_args(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx, float* H,
+                           float* dXXT, int64_t ldh) {
+  if (!X || !Xtilde || !H || !dXXT) return GPTAQ_ENULL;
   if (tokens < 0 || n <= 0 || n % 8 || ldx < n || ldx % 8 || ldh < n || n > (1 << 20) ||
       tokens > (int64_t)1 << 30)
     return GPTAQ_EDIM;
   if (((uintptr_t)X | (uintptr_t)Xtilde) & 15) return GPTAQ_EDIM;
+  return GPTAQ_OK;
+}
+
+static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx, float* H,
+                           float* dXXT, int64_t ldh, void* ws, size_t ws_bytes, void* stream) {
+  if (!ws) return GPTAQ_ENULL;
+  if (const int rc = accumulate_args(X, Xtilde, tokens, n, ldx, H, dXXT, ldh)) return rc;
   if ((uintptr_t)ws & 255) return GPTAQ_EWORKSPACE;
   if (tokens == 0) return GPTAQ_OK;
   hipStream_t s = (hipStream_t)stream;
@@ -166,7 +174,9 @@ static void* scratch_of_current_device() {
 
 extern "C" int gptaq_accumulate_noalloc(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
                                         int64_t ldx, float* H, float* dXXT, int64_t ldh, void* stream) {
+  if (const int rc = accumulate_args(X, Xtilde, tokens, n, ldx, H, dXXT, ldh)) return rc;
   if (n > kScratchMaxN) return GPTAQ_ETOOLARGE;
+  if (tokens == 0) return GPTAQ_OK;
   void* ws = scratch_of_current_device();
   if (!ws) return GPTAQ_ELAUNCH;
   // every pass overwrites the part of the scratch it reads (zero padding included), so nothing of the last
