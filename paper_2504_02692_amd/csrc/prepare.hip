@@ -90,18 +90,21 @@ __global__ void build_F_kernel(const float* H, int64_t ldh, int n, const double*
 
 // ------------------------------------------------------------------- 64 x 64 x 64 in LDS
 // out[i][c] = sum_l A[i][l] * B[l][c] with As[l*LDT + i], Bs[l*LDT + c]; thread (ty, tx)
-// owns rows 4ty..4ty+3 and columns 4tx..4tx+3, so that its four entries of a row of As and of Bs are two
-// 16-byte LDS reads each.  Measured: a product takes ~10K clocks on a CU, i.e. a wavefront issues its 16
-// v_fma_f64 of a step in ~150 clocks, with 8- or 16-byte reads, with or without the read-ahead below, with one or
-// two wavefronts per SIMD alike: the fp64 FMA rate is the bound (~30 TFLOP/s chip-wide at this rate).
+// owns rows 4ty..4ty+3 and columns 2tx, 2tx+1, 32+2tx, 33+2tx (mm_col), so that its four entries of a row of
+// As and of Bs are two 16-byte LDS reads each and the 16 threads tx of a row read 16 consecutive 16-byte pieces
+// (no bank conflicts; four consecutive columns per thread would put tx and tx+8 on the same banks).
+// Measured: a product takes ~10K clocks on a CU (a wavefront's 16 v_fma_f64 of a step in ~150 clocks; the same
+// FMAs alone issue in ~75), with 8- or 16-byte reads, reads one or three steps ahead, one or two wavefronts per
+// SIMD alike: the four wavefronts' operand reads (32 KB per two steps) keep the CU's LDS port busy for about that long.
 // The reads of step l + 1 are issued before the products of step l (two register sets): left to itself the
 // compiler reads into the same registers every step and waits for them before the first product.
+__device__ __forceinline__ constexpr int mm_col(int tx, int q) { return (q >> 1) * 32 + 2 * tx + (q & 1); }
 struct MmRegs { f64x2 a0, a1, b0, b1; };
 __device__ __forceinline__ void mm64_read(MmRegs& r, const double* pa, const double* pb) {
   r.a0 = *reinterpret_cast<const f64x2*>(pa);
   r.a1 = *reinterpret_cast<const f64x2*>(pa + 2);
   r.b0 = *reinterpret_cast<const f64x2*>(pb);
-  r.b1 = *reinterpret_cast<const f64x2*>(pb + 2);
+  r.b1 = *reinterpret_cast<const f64x2*>(pb + 32);
 }
 template <bool SUB>
 __device__ __forceinline__ void mm64_mul(const MmRegs& r, double (&acc)[4][4]) {
@@ -116,7 +119,7 @@ template <bool SUB>
 __device__ __forceinline__ void mm64_core(const double* As, const double* Bs, double (&acc)[4][4]) {
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const double* pa = As + 4 * ty;
-  const double* pb = Bs + 4 * tx;
+  const double* pb = Bs + 2 * tx;
   MmRegs r0, r1;
   mm64_read(r0, pa, pb);
 #pragma clang loop unroll(disable)
@@ -443,7 +446,7 @@ __device__ __forceinline__ void obf_mm_step(const Sweep& a, const ObfShared& sh,
 #pragma unroll
       for (int p = 0; p < 4; ++p)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + 4 * tx + q] = tg[(KB - 1) * KB / 2 + i][p][q];
+        for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + mm_col(tx, q)] = tg[(KB - 1) * KB / 2 + i][p][q];
     }
     __syncthreads();
   }
@@ -462,7 +465,7 @@ __global__ __launch_bounds__(512) void ob_factor_kernel(Sweep a) {
   };
   if (threadIdx.x < 256) {
     const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
-    // tile (i, j), i <= j < 3, lives in tg[j * (j + 1) / 2 + i], thread (ty, tx) holding rows 4 ty + p, columns 4 tx + q
+    // tile (i, j), i <= j < 3, lives in tg[j * (j + 1) / 2 + i], thread (ty, tx) holding rows 4 ty + p, columns mm_col(tx, q)
     double tg[6][4][4];
 #pragma unroll
     for (int j = 0; j < 3; ++j)
@@ -472,7 +475,7 @@ __global__ __launch_bounds__(512) void ob_factor_kernel(Sweep a) {
         for (int p = 0; p < 4; ++p)
 #pragma unroll
           for (int q = 0; q < 4; ++q)
-            tg[j * (j + 1) / 2 + i][p][q] = at(a.o0 + i * NB + 4 * ty + p, a.o0 + j * NB + 4 * tx + q);
+            tg[j * (j + 1) / 2 + i][p][q] = at(a.o0 + i * NB + 4 * ty + p, a.o0 + j * NB + mm_col(tx, q));
     __syncthreads();
     obf_mm_step<3>(a, sh, tg);
     obf_mm_step<2>(a, sh, tg);
@@ -534,7 +537,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
     for (int p = 0; p < 4; ++p)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = a.o0 + b * NB + 4 * tx + q;
+        const int col = a.o0 + b * NB + mm_col(tx, q);
         f[b][p][q] = (b < nbi && col < a.n) ? a.F[(int64_t)(r0 + 4 * ty + p) * a.ldf + col] : 0.0;
       }
   int flip = 0;
@@ -545,7 +548,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) As[(4 * tx + q) * LDT + 4 * ty + p] = f[kl][p][q];
+      for (int q = 0; q < 4; ++q) As[(mm_col(tx, q)) * LDT + 4 * ty + p] = f[kl][p][q];
     double* Bs = Bs0 + flip * NB * LDT;
     flip ^= 1;
     put_b(Bs);
@@ -557,7 +560,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
     for (int p = 0; p < 4; ++p)
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        const int col = a.o0 + kl * NB + 4 * tx + q;
+        const int col = a.o0 + kl * NB + mm_col(tx, q);
         if (col < a.n) a.F[(int64_t)(r0 + 4 * ty + p) * a.ldf + col] = v[p][q];
       }
     if (kl == 0) break;
@@ -565,7 +568,7 @@ __global__ __launch_bounds__(256) void tall_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) As[(4 * tx + q) * LDT + 4 * ty + p] = v[p][q];
+      for (int q = 0; q < 4; ++q) As[(mm_col(tx, q)) * LDT + 4 * ty + p] = v[p][q];
 #pragma unroll
     for (int j = 2; j >= 0; --j) {
       if (j >= kl) continue;
@@ -609,13 +612,13 @@ __global__ __launch_bounds__(256) void trinv_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) a.Uob[(int64_t)(k * NB + 4 * ty + p) * 256 + l * NB + 4 * tx + q] = v[p][q];
+      for (int q = 0; q < 4; ++q) a.Uob[(int64_t)(k * NB + 4 * ty + p) * 256 + l * NB + mm_col(tx, q)] = v[p][q];
   };
   auto put_slot = [&](double* dst, const double (&v)[4][4], double sign) {    // right-operand layout: dst[m * LDT + c]
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + 4 * tx + q] = sign * v[p][q];
+      for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + mm_col(tx, q)] = sign * v[p][q];
   };
   double acc[4][4];
   {
@@ -623,7 +626,7 @@ __global__ __launch_bounds__(256) void trinv_kernel(Sweep a) {
 #pragma unroll
     for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int q = 0; q < 4; ++q) acc[p][q] = D[(4 * ty + p) * NB + 4 * tx + q];
+      for (int q = 0; q < 4; ++q) acc[p][q] = D[(4 * ty + p) * NB + mm_col(tx, q)];
   }
   put_global(l, acc);
   if (l == 0) return;
