@@ -108,7 +108,9 @@ def test_prepare_c1(c1):
     assert eu <= 1e-6 and ep <= 5e-5
 
 
-@pytest.mark.parametrize("n,k", [(8, 64), (100, 400), (200, 1000), (1160, 2400)])
+# (sizes around the 64-column inner and 256-column outer blocks of the sweep: one partial tile, exactly one outer block,
+#  an outer block of one / three inner blocks, several outer blocks with a ragged last one)
+@pytest.mark.parametrize("n,k", [(8, 64), (100, 400), (200, 1000), (256, 1000), (320, 1300), (704, 2900), (1160, 2400)])
 def test_prepare_ragged_sizes(n, k):
     Xb, Xtb = synth.make_activations(k, n, 5, "prep", 2, 20.0)
     H, A = O.accumulate(Xb, Xtb)
