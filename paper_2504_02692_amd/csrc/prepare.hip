@@ -389,35 +389,38 @@ __device__ __forceinline__ void solve_wave(const double* Vt, const double* dsh, 
 // tiles (upper triangle) are read once and never go back to memory in between.  Eight wavefronts in two groups
 // with separate programs (and so separate register allocations: the tiles fill most of the registers of the
 // first group, a factorisation those of a wavefront of the second); both run the same number of barriers.
-// For K = 3 .. 0 (inner blocks):
-//   wavefront 4 factors tile (K, K) (cholesky_wave);                                             | barrier
-//   wavefronts 4 .. 4+K-1 solve for the panels V_iK, one tile each, wavefront 7 inverts V_KK;    | barrier
-//   wavefronts 0-3 store the V_iK and update the tiles (i <= j < K) they hold in registers:
-//   F_ij -= V_iK V_jK^T (mm64);                                                                  | barrier
-//   wavefronts 0-3 move column K-1 of the tiles to LDS (tile (K-1, K-1) to T, the others to the slots). | barrier
-// Outputs: V_iK to Vob (for tall_kernel and trinv_kernel), Winv_K to Dinv.  Tiles past the end of the matrix are
-// identity / zero padding and are carried along (only the last outer block of a ragged n has any).
+// After the factorisation of tile (3, 3), for K = 3, 2, 1 (inner blocks):
+//   wavefronts 4 .. 4+K-1 solve for the panels V_iK, one tile each, wavefront 7 inverts V_KK;        | barrier
+//   wavefronts 0-3 store the V_iK, update tile (K-1, K-1) (F_ij -= V_iK V_jK^T, mm64_sub; they hold
+//   the tiles (i <= j < K) in registers) and put it into T;                                          | barrier
+//   wavefront 4 factors tile (K-1, K-1) WHILE wavefronts 0-3 update the other tiles;                 | barrier
+//   wavefronts 0-3 move the rest of tile column K-1 to the LDS slots.                                | barrier
+// and at the end wavefront 7 inverts V_00.  Outputs: V_iK to Vob (for tall_kernel and trinv_kernel), Winv_K to Dinv.
+// Tiles past the end of the matrix are identity / zero padding and are carried along (only the last outer block of
+// a ragged n has any).
 constexpr int OBF_LDS = (DIAG_LDS_DOUBLES + 3 * NB * LDT) * 8;
 struct ObfShared { double *T, *colb, *dsh, *slot0; };
 
+__device__ __forceinline__ void obf_invert(const Sweep& a, const ObfShared& sh, int kb, int nbi) {
+  if (kb >= nbi) return;                                      // (a padding tile: nothing to store)
+  const int lane = threadIdx.x & 63;
+  double wv[NB];
+  inverse_wave(sh.T, sh.dsh, wv);
+  double* D = a.Dinv + (int64_t)(a.jlo + kb) * NB * NB;
+#pragma unroll
+  for (int cc = 0; cc < NB; ++cc) D[lane * NB + cc] = wv[cc];
+}
+
 template <int KB>
 __device__ __forceinline__ void obf_seq_step(const Sweep& a, const ObfShared& sh, int nbi) {
-  const int w = (threadIdx.x >> 6) - 4, lane = threadIdx.x & 63;
-  if (w == 0) cholesky_wave(a, sh.T, sh.colb, sh.dsh, (a.jlo + KB) * NB);
-  __syncthreads();
-  if (w == 3 && KB < nbi) {
-    double wv[NB];
-    inverse_wave(sh.T, sh.dsh, wv);
-    double* D = a.Dinv + (int64_t)(a.jlo + KB) * NB * NB;
-#pragma unroll
-    for (int cc = 0; cc < NB; ++cc) D[lane * NB + cc] = wv[cc];
-  }
-  if constexpr (KB > 0) {
-    if (w < KB) solve_wave(sh.T, sh.dsh, sh.slot0 + w * NB * LDT);
-    __syncthreads();
-    __syncthreads();
-    __syncthreads();
-  }
+  const int w = (threadIdx.x >> 6) - 4;
+  if (w == 3) obf_invert(a, sh, KB, nbi);
+  if (w < KB) solve_wave(sh.T, sh.dsh, sh.slot0 + w * NB * LDT);
+  __syncthreads();                                            // the panels are in the slots; T and dsh are free
+  __syncthreads();                                            // tile (KB-1, KB-1) is in T
+  if (w == 0) cholesky_wave(a, sh.T, sh.colb, sh.dsh, (a.jlo + KB - 1) * NB);
+  __syncthreads();                                            // its factor is in T; the slots are free
+  __syncthreads();                                            // the next panels' tiles are in the slots
 }
 
 template <int KB>
@@ -425,31 +428,33 @@ __device__ __forceinline__ void obf_mm_step(const Sweep& a, const ObfShared& sh,
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const int c = threadIdx.x & 63, rb = threadIdx.x >> 6;
   auto slot = [&](int i) { return sh.slot0 + i * NB * LDT; };
+  constexpr int DIAG = (KB - 1) * KB / 2 + KB - 1;            // tile (KB-1, KB-1)
   __syncthreads();
-  if constexpr (KB > 0) {
-    __syncthreads();
 #pragma unroll
-    for (int i = 0; i < KB; ++i)
+  for (int i = 0; i < KB; ++i)
 #pragma unroll
-      for (int p = 0; p < 16; ++p)
-        a.Vob[(int64_t)(i * NB + rb + 4 * p) * NBO + KB * NB + c] = slot(i)[c * LDT + rb + 4 * p];
+    for (int p = 0; p < 16; ++p)
+      a.Vob[(int64_t)(i * NB + rb + 4 * p) * NBO + KB * NB + c] = slot(i)[c * LDT + rb + 4 * p];
+  // the tile the next factorisation waits for first
+  mm64_sub(slot(KB - 1), slot(KB - 1), tg[DIAG]);             // A[r][l] = V_iK[r][l], B[l][cc] = V_jK[cc][l]
 #pragma unroll
-    for (int j = 0; j < KB; ++j)
+  for (int p = 0; p < 4; ++p)
 #pragma unroll
-      for (int i = 0; i <= j; ++i) {
-        mm64_sub(slot(i), slot(j), tg[j * (j + 1) / 2 + i]);   // A[r][l] = V_iK[r][l], B[l][cc] = V_jK[cc][l]
-      }
-    __syncthreads();                                          // everyone is done with the slots (T since the solves)
+    for (int q = 0; q < 4; ++q) sh.T[(4 * ty + p) * LDT + mm_col(tx, q)] = tg[DIAG][p][q];
+  __syncthreads();
 #pragma unroll
-    for (int i = 0; i < KB; ++i) {
-      double* dst = i == KB - 1 ? sh.T : slot(i);
+  for (int j = 0; j < KB; ++j)
 #pragma unroll
-      for (int p = 0; p < 4; ++p)
+    for (int i = 0; i <= j; ++i)
+      if (j * (j + 1) / 2 + i != DIAG) mm64_sub(slot(i), slot(j), tg[j * (j + 1) / 2 + i]);
+  __syncthreads();                                            // everyone is done with the slots
 #pragma unroll
-        for (int q = 0; q < 4; ++q) dst[(4 * ty + p) * LDT + mm_col(tx, q)] = tg[(KB - 1) * KB / 2 + i][p][q];
-    }
-    __syncthreads();
-  }
+  for (int i = 0; i < KB - 1; ++i)
+#pragma unroll
+    for (int p = 0; p < 4; ++p)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) slot(i)[(4 * ty + p) * LDT + mm_col(tx, q)] = tg[(KB - 1) * KB / 2 + i][p][q];
+  __syncthreads();
 }
 
 __global__ __launch_bounds__(512) void ob_factor_kernel(Sweep a) {
@@ -476,30 +481,32 @@ __global__ __launch_bounds__(512) void ob_factor_kernel(Sweep a) {
 #pragma unroll
           for (int q = 0; q < 4; ++q)
             tg[j * (j + 1) / 2 + i][p][q] = at(a.o0 + i * NB + 4 * ty + p, a.o0 + j * NB + mm_col(tx, q));
-    __syncthreads();
+    __syncthreads();                                          // tile column 3 is in LDS
+    __syncthreads();                                          // tile (3, 3) is factored
     obf_mm_step<3>(a, sh, tg);
     obf_mm_step<2>(a, sh, tg);
     obf_mm_step<1>(a, sh, tg);
-    obf_mm_step<0>(a, sh, tg);
   } else {
-    const int c = threadIdx.x & 63, rb = (threadIdx.x >> 6) - 4;
+    const int c = threadIdx.x & 63, w = (threadIdx.x >> 6) - 4;
     // column 3 of the tiles: (3, 3) to T, the others to the slots, row-major
     double ld[4][16];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int p = 0; p < 16; ++p) ld[i][p] = at(a.o0 + i * NB + rb + 4 * p, a.o0 + 3 * NB + c);
+      for (int p = 0; p < 16; ++p) ld[i][p] = at(a.o0 + i * NB + w + 4 * p, a.o0 + 3 * NB + c);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       double* dst = i < 3 ? sh.slot0 + i * NB * LDT : sh.T;
 #pragma unroll
-      for (int p = 0; p < 16; ++p) dst[(rb + 4 * p) * LDT + c] = ld[i][p];
+      for (int p = 0; p < 16; ++p) dst[(w + 4 * p) * LDT + c] = ld[i][p];
     }
+    __syncthreads();
+    if (w == 0) cholesky_wave(a, sh.T, sh.colb, sh.dsh, (a.jlo + 3) * NB);
     __syncthreads();
     obf_seq_step<3>(a, sh, nbi);
     obf_seq_step<2>(a, sh, nbi);
     obf_seq_step<1>(a, sh, nbi);
-    obf_seq_step<0>(a, sh, nbi);
+    if (w == 3) obf_invert(a, sh, 0, nbi);
   }
 }
 
