@@ -93,11 +93,10 @@ __global__ void build_F_kernel(const float* H, int64_t ldh, int n, const double*
 // owns rows 4ty..4ty+3 and columns 2tx, 2tx+1, 32+2tx, 33+2tx (mm_col), so that its four entries of a row of
 // As and of Bs are two 16-byte LDS reads each and the 16 threads tx of a row read 16 consecutive 16-byte pieces
 // (no bank conflicts; four consecutive columns per thread would put tx and tx+8 on the same banks).
-// Measured: a product takes ~10K clocks on a CU (a wavefront's 16 v_fma_f64 of a step in ~150 clocks; the same
-// FMAs alone issue in ~75), with 8- or 16-byte reads, reads one or three steps ahead, one or two wavefronts per
-// SIMD alike: the four wavefronts' operand reads (32 KB per two steps) keep the CU's LDS port busy for about that long.
-// The reads of step l + 1 are issued before the products of step l (two register sets): left to itself the
-// compiler reads into the same registers every step and waits for them before the first product.
+// The operand reads run ahead of the products in register sets of their own: left to itself the compiler reads
+// into the same registers every step and waits for them before the first product (~150 clocks per step, 10K per
+// product); one step ahead 131, three steps ahead 123 clocks per step = 7.9K clocks per product, which is what the
+// four wavefronts' operand reads (16 KB per step at 128 B per clock) allow; the 16 v_fma_f64 of a step issue in ~75.
 __device__ __forceinline__ constexpr int mm_col(int tx, int q) { return (q >> 1) * 32 + 2 * tx + (q & 1); }
 struct MmRegs { f64x2 a0, a1, b0, b1; };
 __device__ __forceinline__ void mm64_read(MmRegs& r, const double* pa, const double* pb) {
@@ -115,23 +114,53 @@ __device__ __forceinline__ void mm64_mul(const MmRegs& r, double (&acc)[4][4]) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[p][q] = fma(a[p], b[q], acc[p][q]);
 }
-template <bool SUB>
+// DEEP: reads three steps ahead (four register sets) instead of one: 16 products (~75 clocks) are shorter than an
+// LDS round trip.  Reads past the last step fetch the last step again, so that they need no branch (a conditional
+// read costs a second copy of the register set and moves).
+template <bool SUB, bool DEEP>
 __device__ __forceinline__ void mm64_core(const double* As, const double* Bs, double (&acc)[4][4]) {
   const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
   const double* pa = As + 4 * ty;
   const double* pb = Bs + 2 * tx;
-  MmRegs r0, r1;
-  mm64_read(r0, pa, pb);
+  auto at = [](int l) { return (l < NB ? l : NB - 1) * LDT; };
+  if (!DEEP) {
+    MmRegs r0, r1;
+    mm64_read(r0, pa, pb);
 #pragma clang loop unroll(disable)
-  for (int l = 0; l < NB; l += 2) {
-    mm64_read(r1, pa + (l + 1) * LDT, pb + (l + 1) * LDT);
-    __builtin_amdgcn_sched_barrier(0);
-    mm64_mul<SUB>(r0, acc);
-    __builtin_amdgcn_sched_barrier(0);
-    if (l + 2 < NB) mm64_read(r0, pa + (l + 2) * LDT, pb + (l + 2) * LDT);
-    __builtin_amdgcn_sched_barrier(0);
-    mm64_mul<SUB>(r1, acc);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int l = 0; l < NB; l += 2) {
+      mm64_read(r1, pa + (l + 1) * LDT, pb + (l + 1) * LDT);
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_mul<SUB>(r0, acc);
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_read(r0, pa + at(l + 2), pb + at(l + 2));
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_mul<SUB>(r1, acc);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  } else {
+    MmRegs r0, r1, r2, r3;
+    mm64_read(r0, pa, pb);
+    mm64_read(r1, pa + LDT, pb + LDT);
+    mm64_read(r2, pa + 2 * LDT, pb + 2 * LDT);
+#pragma clang loop unroll(disable)
+    for (int l = 0; l < NB; l += 4) {
+      mm64_read(r3, pa + (l + 3) * LDT, pb + (l + 3) * LDT);
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_mul<SUB>(r0, acc);
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_read(r0, pa + at(l + 4), pb + at(l + 4));
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_mul<SUB>(r1, acc);
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_read(r1, pa + at(l + 5), pb + at(l + 5));
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_mul<SUB>(r2, acc);
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_read(r2, pa + at(l + 6), pb + at(l + 6));
+      __builtin_amdgcn_sched_barrier(0);
+      mm64_mul<SUB>(r3, acc);
+      __builtin_amdgcn_sched_barrier(0);
+    }
   }
 }
 
@@ -140,12 +169,13 @@ __device__ __forceinline__ void mm64(const double* As, const double* Bs, double 
   for (int p = 0; p < 4; ++p)
 #pragma unroll
     for (int q = 0; q < 4; ++q) acc[p][q] = 0.0;
-  mm64_core<false>(As, Bs, acc);
+  mm64_core<false, true>(As, Bs, acc);
 }
 
 // acc[i][c] -= sum_l A[i][l] * B[l][c], same layouts (the running tile is the accumulator: no second register tile)
+constexpr bool MM_SUB_DEEP = true;
 __device__ __forceinline__ void mm64_sub(const double* As, const double* Bs, double (&acc)[4][4]) {
-  mm64_core<true>(As, Bs, acc);
+  mm64_core<true, MM_SUB_DEEP>(As, Bs, acc);
 }
 
 // Stage a 64 x 64 tile of a row-major fp64 matrix.  transposed == false: dst[c*LDT + r] = src[r][c]
