@@ -318,25 +318,28 @@ constexpr int SB = 8;                         // column blocks per super-block (
 constexpr int KS = SB * QB;
 struct QLayout {
   int64_t mp, np;
-  size_t off[20], total;
+  size_t off[24], total;
 };
 QLayout q_layout(int64_t m, int64_t n) {
   QLayout L;
   L.mp = round_up(m, 256);
   L.np = round_up(n, 256);
   size_t o = 0;
-  for (int i = 0; i < 20; ++i) {
+  for (int i = 0; i < 24; ++i) {
     L.off[i] = o;
     // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of its updates (all columns from the
     // super-block's first on, plus a tile of padding rows); 8-11: left operands of the updates inside a
-    // super-block (quantize_sb.hip); 12-19: a second set of 0-7 (the far update of a super-block runs beside the
-    // next super-block, which writes its own -E, V and right operands)
+    // super-block (quantize_sb.hip); 12-23: a second set of 0-11 (the far update of a super-block runs beside the
+    // next super-block, which writes its own -E, V and right operands; or the two row halves of a tall matrix
+    // run as two chains, each at its own super-block)
     const int k = i < 12 ? i : i - 12;
     o += (size_t)(k < 4 ? L.mp * KS * 2 : k < 8 ? (L.np + 256) * KS * 2 : (int64_t)(kSbCols / 16) * kSbCols * 16 * 2);
   }
   L.total = o;
   return L;
 }
+
+constexpr int64_t kRowSplitMin = 12288;          // rows from which a matrix is quantised as two row halves
 
 template <int R, int NW>
 hipError_t launch_quant(const QuantArgs& a, hipStream_t s) {
@@ -403,7 +406,7 @@ __global__ __launch_bounds__(256) void zero_dead_columns_kernel(float* W, int64_
 // operands are double-buffered: far2(k) reads set k & 1 while super-block k + 1 writes the other.
 static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P, int64_t ldh,
                              const uint8_t* dead, int bits, int group, int sym, uint8_t* codes, float* scales,
-                             float* zeros, uint16_t* const* buf, hipStream_t s, int terms) {
+                             float* zeros, uint16_t* const* buf, hipStream_t s, int terms, bool may_use_helper = true) {
   constexpr int64_t LDE = kSbCols;               // row stride of the -E / V buffers and of the far right operands
   if (dead) {
     hipLaunchKernelGGL(zero_dead_columns_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, s, W, ldw, (int)m, (int)n, dead);
@@ -430,7 +433,7 @@ static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const 
   int cus = 256, dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) cus = 256;
   const int sbk_wgs = (int)((m + 63) / 64);
-  const bool two_chains = terms != 0 && nsb >= 3 && sbk_wgs <= cus / 4;
+  const bool two_chains = may_use_helper && terms != 0 && nsb >= 3 && sbk_wgs <= cus / 4;
   std::unique_lock<std::mutex> side_lock(side_stream_mutex(), std::defer_lock);
   SideStream* side = nullptr;
   if (two_chains) {
@@ -525,13 +528,44 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
   if (ws_bytes < L.total) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   unsigned char* base = (unsigned char*)ws;
-  uint16_t* buf[20];
-  for (int i = 0; i < 20; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
+  uint16_t* buf[24];
+  for (int i = 0; i < 24; ++i) buf[i] = (uint16_t*)(base + L.off[i]);
 
   // The super-block kernel takes groups that tile its 16/32/128-column pieces; the clip-range search and other
   // group sizes go through the block-by-block kernels below.
-  if (mse_steps == 0 && (group <= 0 || group == 16 || group == 32 || group == 64 || group == 128))
+  if (mse_steps == 0 && (group <= 0 || group == 16 || group == 32 || group == 64 || group == 128)) {
+    // Rows are independent (Step 1).  A tall matrix goes through as two row halves on two streams: the super-block
+    // kernel of one half, whose length is a chain of column steps whatever the number of rows, then runs beside the
+    // far update of the other half instead of leaving the chip to it alone (and 344 workgroups of 64 rows no
+    // longer make a second, mostly empty round on 256 CUs).
+    const int64_t nsb = (n + kSbCols - 1) / kSbCols;
+    if (terms != 0 && nsb >= 2 && m >= kRowSplitMin) {
+      const int64_t mA = round_up((m + 1) / 2, 256), mB = m - mA;   // (a multiple of the GEMM's row tile: the halves' padded
+                                                                    //  rows of the -E / V buffers then do not overlap)
+      const int64_t G = group > 0 ? n / group : 1;
+      std::lock_guard<std::mutex> side_lock(side_stream_mutex());
+      SideStream* side = side_stream(2);
+      if (!side) { set_last_hip_error(hipGetLastError()); return GPTAQ_ELAUNCH; }
+      hipEvent_t ev_fork = side->events[0], ev_join = side->events[1];
+      if (hipEventRecord(ev_fork, s) != hipSuccess || hipStreamWaitEvent(side->stream, ev_fork, 0) != hipSuccess) {
+        set_last_hip_error(hipGetLastError());
+        return GPTAQ_ELAUNCH;
+      }
+      uint16_t* bufB[12];
+      for (int i = 0; i < 4; ++i) bufB[i] = buf[i] + mA * kSbCols;          // its rows of the -E / V buffers
+      for (int i = 4; i < 12; ++i) bufB[i] = buf[12 + i];                  // operands of its own
+      const int rcB = quantize_layer_sb(W + mA * ldw, mB, n, ldw, U, P, ldh, dead, bits, group, sym, codes + mA * n,
+                                        scales + mA * G, zeros + mA * G, bufB, side->stream, terms, false);
+      const int rcA = quantize_layer_sb(W, mA, n, ldw, U, P, ldh, dead, bits, group, sym, codes, scales, zeros, buf, s,
+                                        terms, false);
+      // the helper stream is behind the caller's stream when the call returns, error or not
+      const hipError_t keep = (hipError_t)gptaq_last_hip_error();
+      if (hipEventRecord(ev_join, side->stream) == hipSuccess) hipStreamWaitEvent(s, ev_join, 0);
+      if (rcA != GPTAQ_OK || rcB != GPTAQ_OK) set_last_hip_error(keep);
+      return rcA != GPTAQ_OK ? rcA : rcB;
+    }
     return quantize_layer_sb(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, codes, scales, zeros, buf, s, terms);
+  }
 
   QuantArgs a;
   a.W = W; a.ldw = ldw; a.m = (int)m; a.n = (int)n;

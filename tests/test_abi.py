@@ -47,8 +47,8 @@ def test_workspace_queries(lib):
     assert lib.gptaq_accumulate_workspace_bytes(0, 512) == 0
     assert lib.gptaq_prepare_workspace_bytes(512) > 512 * 512 * 8
     # -E / V operands of one super-block (1024 columns), right operands for all columns + one tile of padding rows
-    # two sets of (-E / V of a super-block, right operands of its far update), left operands of the updates inside it
-    assert lib.gptaq_quantize_workspace_bytes(512, 512) == 2 * (4 * 512 * 1024 + 4 * (512 + 256) * 1024) * 2 + 4 * (1024 // 16) * 1024 * 16 * 2
+    # two sets of (-E / V of a super-block, right operands of its far update, left operands of the updates inside it)
+    assert lib.gptaq_quantize_workspace_bytes(512, 512) == 2 * (4 * 512 * 1024 + 4 * (512 + 256) * 1024 + 4 * (1024 // 16) * 1024 * 16) * 2
     assert lib.gptaq_status_string(0) == b"ok"
 
 
