@@ -253,17 +253,25 @@ def main() -> int:
         for sb_end in range(1024, l.n, 1024):
             far_flop += 2.0 * l.m * 1024 * (l.n - sb_end) * 2
     t_sb, t_far = prof["column_loop"][1] * 1e-3, prof["trailing_gemm"][1] * 1e-3
+    t_q = stage_ms["quantize"] * 1e-3
+    overlap = ("; bracketed on the stream it runs on: the kernels of a tall matrix's two row halves and of a short "
+               "matrix's two far chains run beside each other, so these times overlap and sum to more than the stage")
     other = {
+        "quantize_stage": {"bound": "hbm", "achieved": wbytes / t_q / 1e9, "peak": 8000.0, "unit": "GB/s",
+                           "frac": wbytes / t_q / 1e9 / 8000.0, "frac_of_measured_copy": wbytes / t_q / 1e9 / hbm_copy,
+                           "trailing_update_tflops": tflop / t_q / 1e12,
+                           "note": "the whole quantize stage (events around it in the stage-split pass): 17 algorithmic bytes per weight, "
+                                   "and the 2 m n^2 algorithmic flop of the trailing update over the same time"},
         "superblock_kernel": {"bound": "hbm", "achieved": wbytes / t_sb / 1e9, "peak": 8000.0, "unit": "GB/s",
                               "frac": wbytes / t_sb / 1e9 / 8000.0, "frac_of_measured_copy": wbytes / t_sb / 1e9 / hbm_copy,
                               "mfma_tflops_inside": (tflop - far_flop) / t_sb / 1e12,
                               "note": "column steps + updates inside 1024-column super-blocks; bound by the chain of "
-                                      "sequential column steps (n per layer), not by bandwidth"},
+                                      "sequential column steps (n per layer), not by bandwidth" + overlap},
         "far_update_gemm": {"bound": "mfma", "achieved": far_flop / t_far / 1e12 if t_far > 0 else 0.0,
                             "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                             "frac": far_flop / t_far / 1e12 / PEAK_BF16_TFLOPS if t_far > 0 else 0.0,
                             "note": "algorithmic flop of the updates that leave a super-block; executed x3 (bf16 hi/lo "
-                                    "split of both operands)"},
+                                    "split of both operands)" + overlap},
         "trailing_update_total": {"bound": "mfma", "achieved": tflop / (t_sb + t_far) / 1e12, "peak": PEAK_BF16_TFLOPS,
                                   "unit": "TFLOP/s", "frac": tflop / (t_sb + t_far) / 1e12 / PEAK_BF16_TFLOPS,
                                   "note": "2 m n^2 algorithmic flop over super-block kernel + far GEMM time"},
