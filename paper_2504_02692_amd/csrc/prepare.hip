@@ -9,12 +9,12 @@
 // right-hand side R of the solve V U = I afterwards.  Two block levels:
 //
 //   for every outer block OB of 256 columns, last to first      (I: rows above OB, J: columns right of OB)
-//     for every inner block K of 64 columns in OB, last to first: ONE launch (step_kernel) over the tiles of OB
-//       diag   : F_KK = V_KK V_KK^T                               (by one wavefront of every workgroup, redundantly;
-//                                                                  Winv_K = V_KK^-1 by another, beside the solves)
+//     ob     : ONE launch, one workgroup (ob_factor_kernel), for the 256 x 256 diagonal block of OB; for every inner
+//              block K of 64 columns in OB, last to first:
+//       diag   : F_KK = V_KK V_KK^T   (one wavefront; Winv_K = V_KK^-1 by another, beside the solves)
 //       panel  : V_iK = F_iK V_KK^-T  for the row tiles i of OB above K (triangular solves, one row per lane)
-//       inner  : F_ij -= V_iK V_jK^T   for the tiles (i <= j) of OB left of K (rank 64)
-//     tall   : the same panels and rank-64 updates for the rows above OB, all four inner blocks in one launch
+//       inner  : F_ij -= V_iK V_jK^T  for the tiles (i <= j) of OB left of K (rank 64), the next diagonal tile first
+//     tall   : the same panels (as products with Winv_K) and rank-64 updates for the rows above OB, one launch
 //     syrk   : F_II  -= V_I,OB V_I,OB^T                (rank 256)  } the n^3 * 2/3 bulk: digit-sliced operands,
 //     trinv  : U_OB,OB = V_OB,OB^-1  from the Winv_K and the V_kj inside OB          exact int8 MFMA products,
 //     rowblk : U_OB,J  = U_OB,OB R_OB,J                                              fp64 recombination
