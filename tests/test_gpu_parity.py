@@ -376,6 +376,26 @@ def test_stacked_layers_equal_separate_calls(c1):
         assert np.array_equal(one[key], np.concatenate([a[key], b[key]])), key
 
 
+def test_tall_matrix_in_two_row_halves_equals_separate_calls():
+    """A matrix of 10240 rows or more is quantised as two row halves on two streams (rows are independent, Step 1).
+    The result must be bit for bit what two separate calls on those halves give (each short enough to take the
+    one-stream route), over several super-blocks and with a ragged last super-block."""
+    n, m, k = 2100, 10500, 2600
+    Xb, Xtb = synth.make_activations(k, n, 11, "tall", 2, 20.0)
+    H, A = O.accumulate(Xb, Xtb)
+    U, P, _ = O.prepare(H, A, 0.01)
+    U32, P32 = dev(U.astype(np.float32)), dev(P.astype(np.float32))
+    W = synth.make_weights(m, n, 12, "tall")
+    one = PU.gpu_quantize(W, U32, P32, 4, 0, False, 128)
+    half = -(-((m + 1) // 2) // 256) * 256                     # where the library splits
+    a, b = PU.gpu_quantize(W[:half], U32, P32, 4, 0, False, 128), PU.gpu_quantize(W[half:], U32, P32, 4, 0, False, 128)
+    for key in ("codes", "scales", "zeros", "What"):
+        assert np.array_equal(one[key], np.concatenate([a[key], b[key]])), key
+    again = PU.gpu_quantize(W, U32, P32, 4, 0, False, 128)
+    for key in ("codes", "scales", "zeros", "What"):
+        assert np.array_equal(one[key], again[key]), key
+
+
 def test_bench_line_on_the_small_workload():
     """bench.py end to end on the 512 x 512 layer: one JSON line with the fields the contract names."""
     import json, os, subprocess, sys
