@@ -960,7 +960,11 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
                      ni, deadbuf, Ah, Al, np, info);
   GPTAQ_LAUNCH_CHECK();
 
-  const int tile = gemm_tile_for(n, n);
+  // The K ranges of these two products are triangular, so tiles differ in length by the whole of K; while 256-tiles
+  // make a single round, the longest one sets the time and 128-tiles balance better (n = 4096: 4.66 -> 4.53 ms per
+  // call; n = 11008, 7 rounds of 256-tiles: 25.2 -> 27.5, so not there)
+  const int t256 = gemm_tile_for(n, n);
+  const int tile = (t256 == 256 && (np / 256) * (np / 256) <= 256) ? 128 : t256;
   GemmBatch b{};
   b.nprob = 1; b.tile = tile;
   GemmProblem& g = b.p[0];
