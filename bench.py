@@ -7,7 +7,7 @@ U, P <- prepare; then for every layer that reads that input  quantize_layer.
 Inputs are synthetic (paper_2504_02692_amd/synth.py) and resident in HBM before the timed
 region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 32768] [--staged]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload llama7b] [--chunk 32768] [--staged] [--full-dxxt]
     python bench.py --extras      (timing table of act_order, packing, activation quantiser, clip-range search)
 """
 from __future__ import annotations
@@ -135,6 +135,9 @@ def main() -> int:
     ap.add_argument("--chunk", type=int, default=32768, help="tokens per gptaq_accumulate call")
     ap.add_argument("--staged", action="store_true",
                     help="hand the chunks to gptaq_accumulate_staged (products per 32768 pending tokens)")
+    ap.add_argument("--full-dxxt", action="store_true",
+                    help="accumulate every entry of dXXT (what act_order needs) instead of the entries with col >= row, "
+                         "which are all that Eq. 17 reads when the columns are taken in their natural order")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--extras", action="store_true",
                     help="print the timing table of the entry points beside the main path and exit")
@@ -181,19 +184,26 @@ def main() -> int:
     dead = {iid: torch.zeros(n, dtype=torch.uint8, device=dev) for iid, n in inputs.items()}
     stage_ms = {"accumulate": 0.0, "prepare": 0.0, "quantize": 0.0}
 
+    def accumulate(iid, upper):
+        X, Xt = acts[iid]
+        H, A = HA[iid]
+        H.zero_(); A.zero_()
+        pending = 0
+        for t0 in range(0, wl.tokens, args.chunk):
+            t1 = min(wl.tokens, t0 + args.chunk)
+            if args.staged:
+                pending = B.gptaq_accumulate_staged(X[t0:t1], Xt[t0:t1], H, A, ws_acc, pending, flush=t1 == wl.tokens,
+                                                    upper=upper)
+            else:
+                (B.gptaq_accumulate_upper if upper else B.gptaq_accumulate)(X[t0:t1], Xt[t0:t1], H, A, ws_acc)
+
+    upper = not args.full_dxxt
+
     def step(r: int, ev=None):
         for iid, n in inputs.items():
-            X, Xt = acts[iid]
             H, A = HA[iid]
             if ev: ev[0].record()
-            H.zero_(); A.zero_()
-            pending = 0
-            for t0 in range(0, wl.tokens, args.chunk):
-                t1 = min(wl.tokens, t0 + args.chunk)
-                if args.staged:
-                    pending = B.gptaq_accumulate_staged(X[t0:t1], Xt[t0:t1], H, A, ws_acc, pending, flush=t1 == wl.tokens)
-                else:
-                    B.gptaq_accumulate(X[t0:t1], Xt[t0:t1], H, A, ws_acc)
+            accumulate(iid, upper)
             if ev: ev[1].record()
             B.gptaq_prepare(H, A, wl.damp, ws_prep, dead=dead[iid], info=info[iid])
             if ev: ev[2].record()
@@ -228,6 +238,16 @@ def main() -> int:
     prof = {name: B.gptaq_profile_read(i) for i, name in enumerate(B.PROFILE_TAGS)}
     B.gptaq_profile_enable(0)
 
+    # the accumulation alone in both forms, untimed extra passes (the other form's number is context for the headline)
+    acc_ms = {}
+    for form in ("upper", "full"):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for iid in inputs:
+            accumulate(iid, form == "upper")
+        e1.record(); e1.synchronize()
+        acc_ms[form] = e0.elapsed_time(e1)
+
     # what the matrix cores of this machine sustain on nothing but MFMAs (all-ones and random operands), measured here
     peak_ones, clk_ones = B.gptaq_measure_mfma_peak(False, 50)
     peak_rand, clk_rand = B.gptaq_measure_mfma_peak(True, 50)
@@ -235,12 +255,14 @@ def main() -> int:
 
     ms_per_step = elapsed * 1e3 / args.steps
     n_layers = len(wl.layers)
-    # dominant kernel: the accumulate MFMA GEMM.  Algorithmic flop per launch = n(n+1)c [H, upper half]
-    # + 2 n^2 c [dXXT] for a pass over c tokens of an n-wide input.
+    # dominant kernel: the accumulate MFMA GEMM.  Algorithmic flop per launch over c tokens of an n-wide input =
+    # n(n+1)c [H, upper half] + 2 n^2 c [all of dXXT], or + n(n+1)c when only the entries of dXXT with col >= row are
+    # accumulated.  Executed: every dXXT product twice (exact hi/lo split of dX).
     flops = 0.0
     for iid, n in inputs.items():
-        flops += (n * (n + 1) + 2 * n * n) * float(wl.tokens)
+        flops += (n * (n + 1) + (n * (n + 1) if upper else 2 * n * n)) * float(wl.tokens)
     flops *= args.steps
+    executed_ratio = 1.5 if upper else 5.0 / 3.0
     achieved = flops / (gemm_ms * 1e-3) / 1e12 if gemm_ms > 0 else 0.0
     # secondary kernels (from the untimed, fully bracketed pass).  The super-block kernel does the column steps and every
     # update inside a 1024-column super-block: against HBM with 17 algorithmic bytes per weight (read W 4, write W^ 4,
@@ -282,7 +304,8 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", f"{wl.name}_block_hbm_traffic.json")
     if os.path.exists(tpath):
         tj = json.load(open(tpath))
-        if tj.get("workload") == wl.name and tj.get("chunk", 32768) == args.chunk and not args.staged:
+        if tj.get("workload") == wl.name and tj.get("chunk", 32768) == args.chunk and not args.staged \
+                and tj.get("dxxt", "full") == ("upper" if upper else "full"):
             traffic, traffic_src = tj.get("bytes_per_launch_avg"), "profiles/" + os.path.basename(tpath)
     out = {
         "metric": "ms_per_layer_solve", "value": ms_per_step / n_layers, "unit": "ms/layer",
@@ -291,23 +314,30 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{wl.name}: " + ", ".join(f"{l.name} {l.m}x{l.n}" for l in wl.layers) +
                                f"; {wl.tokens} tokens; W{wl.bits} g{wl.group} {'sym' if wl.sym else 'asym'} "
-                               f"B{wl.blocksize}; accumulate chunk {args.chunk}{' (staged)' if args.staged else ''}; layers with a common input (q/k/v, gate/up) "
-                               f"quantised as one stacked matrix",
+                               f"B{wl.blocksize}; accumulate chunk {args.chunk}{' (staged)' if args.staged else ''}; "
+                               f"dXXT: {'entries with col >= row (all that Eq. 17 reads in natural column order)' if upper else 'all entries'}; "
+                               f"layers with a common input (q/k/v, gate/up) quantised as one stacked matrix",
                    "layers_per_step": n_layers},
         "roofline": {"bound": "mfma", "kernel": "gemm_nt_kernel<256> (accumulate: H and dXXT)",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "traffic_source": traffic_src,
                      "launches": launches, "avg_launch_ms": gemm_ms / max(1, launches),
-                     "executed": achieved * 5.0 / 3.0,
+                     "executed": achieved * executed_ratio,
+                     "algorithmic_flop_note": ("n(n+1)c for H plus n(n+1)c for the entries of dXXT with col >= row; the same "
+                                               "launches priced at the 3 n^2 c of a full dXXT would read "
+                                               f"{achieved * 1.5:.0f} TFLOP/s") if upper else "n(n+1)c for H plus 2 n^2 c for dXXT",
                      "measured_mfma_loop": {"ones_tflops": peak_ones, "ones_clock_ghz": clk_ones,
                                             "random_tflops": peak_rand, "random_clock_ghz": clk_rand,
-                                            "executed_frac_of_random": achieved * 5.0 / 3.0 / peak_rand,
+                                            "executed_frac_of_random": achieved * executed_ratio / peak_rand,
                                             "note": "pure bf16 MFMA loop on all CUs for 50 ms (power-limited clock); "
-                                                    "executed = 5 n^2 c flop (exact hi/lo split of dX) against "
-                                                    "3 n^2 c algorithmic"},
+                                                    "executed = every dXXT product twice (exact hi/lo split of dX): "
+                                                    + ("3 n^2 c against 2 n^2 c algorithmic" if upper else
+                                                       "5 n^2 c against 3 n^2 c algorithmic")},
                      "measured_hbm_copy_gbps": hbm_copy},
         "other_kernels": other,
         "stages_ms_per_step": stage_ms,
+        "accumulate_ms_per_step_by_form": {"dxxt_upper": acc_ms["upper"], "dxxt_full": acc_ms["full"],
+                                           "timed_path_uses": "dxxt_upper" if upper else "dxxt_full"},
         "kernels_ms_per_step": {k: v[1] for k, v in prof.items()},
         "kernel_launches_per_step": {k: v[0] for k, v in prof.items()},
     }

@@ -95,6 +95,25 @@ int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t t
                             int64_t ldx, float* H, float* dXXT, int64_t ldh,
                             void* ws, size_t ws_bytes, int64_t* pending, int flush, void* stream);
 
+/* gptaq_accumulate and gptaq_accumulate_staged restricted to the part of dXXT that the solve reads when the
+ * input channels are processed in their natural order.  Theorem 4.2 / Eq. 17 build P from dXXT L masked to its
+ * STRICTLY UPPER triangle, with L lower triangular: entry (i, j) of the masked product is a sum over k >= j > i
+ * of dXXT[i][k] L[k][j], so no entry of dXXT on or below its diagonal ever reaches P, U or a quantised weight.
+ * These calls leave the products for that half out (a third of the matrix-core work of a launch):
+ *   dXXT : on return the entries with col >= row hold the same sums, bit for bit, as after the full call; the
+ *          entries below the diagonal are in an unspecified state (some tiles updated, others untouched) but stay
+ *          finite if they were finite on entry (zero-initialise the matrix as for the full call).
+ *          gptaq_prepare on such a matrix returns the same U and P, bit for bit, as on the full one.
+ *   NOT for act_order: gptaq_permute_hessian moves entries across the diagonal and needs the full matrix.
+ * H and every other argument as for the full calls; a series may not mix full and upper calls if the lower
+ * half is to mean anything. */
+int gptaq_accumulate_upper(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                           int64_t ldx, float* H, float* dXXT, int64_t ldh,
+                           void* ws, size_t ws_bytes, void* stream);
+int gptaq_accumulate_staged_upper(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                                  int64_t ldx, float* H, float* dXXT, int64_t ldh,
+                                  void* ws, size_t ws_bytes, int64_t* pending, int flush, void* stream);
+
 /* Copies the upper triangle of the n x n fp32 matrix H onto its lower triangle. */
 int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
 

@@ -23,11 +23,16 @@ _SIGS = {
     "gptaq_accumulate_workspace_bytes": (_c.c_size_t, [_c.c_int64, _c.c_int64]),
     "gptaq_accumulate": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
                                     _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
+    "gptaq_accumulate_upper": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
+                                          _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.c_void_p]),
     "gptaq_accumulate_noalloc": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
                                             _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p]),
     "gptaq_accumulate_staged": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p,
                                            _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t, _c.POINTER(_c.c_int64),
                                            _c.c_int, _c.c_void_p]),
+    "gptaq_accumulate_staged_upper": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64,
+                                                 _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t,
+                                                 _c.POINTER(_c.c_int64), _c.c_int, _c.c_void_p]),
     "gptaq_symmetrize": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p]),
     "gptaq_prepare_workspace_bytes": (_c.c_size_t, [_c.c_int64]),
     "gptaq_prepare": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_float,
@@ -124,17 +129,28 @@ def gptaq_quantize_workspace_bytes(m: int, n: int) -> int:
     return load().gptaq_quantize_workspace_bytes(m, n)
 
 
-def gptaq_accumulate(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXXT: torch.Tensor,
-                     ws: torch.Tensor) -> None:
-    """H += X^T X (upper triangle), dXXT += (Xtilde - X)^T X for token-major bf16 X, Xtilde."""
+def _accumulate(name: str, X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXXT: torch.Tensor,
+                ws: torch.Tensor) -> None:
     _need(X, torch.bfloat16, "X"); _need(Xtilde, torch.bfloat16, "Xtilde")
     _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
     tokens, n = X.shape
     if Xtilde.shape != X.shape or Xtilde.stride(0) != X.stride(0) or H.shape != (n, n) or dXXT.shape != (n, n) \
             or H.stride(0) != dXXT.stride(0):
-        raise GptaqError("gptaq_accumulate: shape mismatch")
-    _check(load().gptaq_accumulate(_ptr(X), _ptr(Xtilde), tokens, n, X.stride(0), _ptr(H), _ptr(dXXT),
-                                   H.stride(0), _ptr(ws), ws.numel(), _stream()), "gptaq_accumulate")
+        raise GptaqError(f"{name}: shape mismatch")
+    _check(getattr(load(), name)(_ptr(X), _ptr(Xtilde), tokens, n, X.stride(0), _ptr(H), _ptr(dXXT),
+                                 H.stride(0), _ptr(ws), ws.numel(), _stream()), name)
+
+
+def gptaq_accumulate(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXXT: torch.Tensor,
+                     ws: torch.Tensor) -> None:
+    """H += X^T X (upper triangle), dXXT += (Xtilde - X)^T X for token-major bf16 X, Xtilde."""
+    _accumulate("gptaq_accumulate", X, Xtilde, H, dXXT, ws)
+
+
+def gptaq_accumulate_upper(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXXT: torch.Tensor,
+                           ws: torch.Tensor) -> None:
+    """gptaq_accumulate that maintains only the entries of dXXT with col >= row (natural column order)."""
+    _accumulate("gptaq_accumulate_upper", X, Xtilde, H, dXXT, ws)
 
 
 def gptaq_accumulate_noalloc(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Tensor, dXXT: torch.Tensor) -> None:
@@ -150,9 +166,11 @@ def gptaq_accumulate_noalloc(X: torch.Tensor, Xtilde: torch.Tensor, H: torch.Ten
 
 
 def gptaq_accumulate_staged(X: Optional[torch.Tensor], Xtilde: Optional[torch.Tensor], H: torch.Tensor, dXXT: torch.Tensor,
-                            ws: torch.Tensor, pending: int, flush: bool = False) -> int:
+                            ws: torch.Tensor, pending: int, flush: bool = False, upper: bool = False) -> int:
     """Appends a chunk to the staged operands in `ws` (products run per 32768 pending tokens or on flush);
-    returns the new number of pending tokens.  X, Xtilde may be None with flush=True."""
+    returns the new number of pending tokens.  X, Xtilde may be None with flush=True.
+    upper=True calls gptaq_accumulate_staged_upper."""
+    fn = "gptaq_accumulate_staged_upper" if upper else "gptaq_accumulate_staged"
     _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
     n = H.shape[0]
     tokens, ldx = 0, n
@@ -164,9 +182,9 @@ def gptaq_accumulate_staged(X: Optional[torch.Tensor], Xtilde: Optional[torch.Te
     if dXXT.shape != (n, n) or H.stride(0) != dXXT.stride(0):
         raise GptaqError("gptaq_accumulate_staged: shape mismatch")
     p = _c.c_int64(int(pending))
-    _check(load().gptaq_accumulate_staged(_ptr(X), _ptr(Xtilde), tokens, n, ldx, _ptr(H), _ptr(dXXT), H.stride(0),
-                                          _ptr(ws), ws.numel() * ws.element_size(), _c.byref(p), int(bool(flush)),
-                                          _stream()), "gptaq_accumulate_staged")
+    _check(getattr(load(), fn)(_ptr(X), _ptr(Xtilde), tokens, n, ldx, _ptr(H), _ptr(dXXT), H.stride(0),
+                               _ptr(ws), ws.numel() * ws.element_size(), _c.byref(p), int(bool(flush)),
+                               _stream()), fn)
     return p.value
 
 

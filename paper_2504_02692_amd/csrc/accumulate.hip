@@ -89,8 +89,11 @@ extern "C" size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n) {
 }
 
 // H += X X^T (upper tiles) and dXXT += (hi + lo) X^T over cp tokens of split operands, as one launch.
+// dxxt_upper: only the tiles of dXXT that touch its upper triangle.  Eq. 17 masks dXXT L to its strictly upper part and
+// L is lower triangular, so entry (i, k) of dXXT reaches P only through sums over k >= j > i: in the natural column
+// order nothing on or below the diagonal is ever read, and a third of the products of the launch can be left out.
 static hipError_t launch_products(const uint16_t* oX, const uint16_t* oHi, const uint16_t* oLo, int64_t np, int64_t cp,
-                                  int64_t n, float* H, float* dXXT, int64_t ldh, hipStream_t s) {
+                                  int64_t n, float* H, float* dXXT, int64_t ldh, bool dxxt_upper, hipStream_t s) {
   const int tile = gemm_tile_for(n, n);
   GemmBatch b{};
   b.nprob = 2;
@@ -98,7 +101,7 @@ static hipError_t launch_products(const uint16_t* oX, const uint16_t* oHi, const
   GemmProblem& a = b.p[0];
   a.C = dXXT; a.ldc = ldh; a.M = (int)n; a.N = (int)n; a.K = (int)cp;
   a.tiles_m = a.tiles_n = (int)(np / tile);
-  a.kind = 1; a.nterm = 1; a.tile_mode = 0; a.k_mode = 0; a.store_mode = 0;
+  a.kind = 1; a.nterm = 1; a.tile_mode = dxxt_upper ? 2 : 0; a.k_mode = 0; a.store_mode = 0;
   a.term[0] = {{oHi, oLo}, {oX, oX}, 32, 32, np * 32, np * 32};
   GemmProblem& h = b.p[1];
   h = a;
@@ -120,7 +123,7 @@ static int accumulate_args(const uint16_t* X, const uint16_t* Xtilde, int64_t to
 }
 
 static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx, float* H,
-                           float* dXXT, int64_t ldh, void* ws, size_t ws_bytes, void* stream) {
+                           float* dXXT, int64_t ldh, bool dxxt_upper, void* ws, size_t ws_bytes, void* stream) {
   if (!ws) return GPTAQ_ENULL;
   if (const int rc = accumulate_args(X, Xtilde, tokens, n, ldx, H, dXXT, ldh)) return rc;
   if ((uintptr_t)ws & 255) return GPTAQ_EWORKSPACE;
@@ -143,7 +146,7 @@ static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t to
                          oX, oHi, oLo, np, 0);
     }
     GPTAQ_LAUNCH_CHECK();
-    hipError_t e = launch_products(oX, oHi, oLo, np, cp, n, H, dXXT, ldh, s);
+    hipError_t e = launch_products(oX, oHi, oLo, np, cp, n, H, dXXT, ldh, dxxt_upper, s);
     if (e != hipSuccess) { set_last_hip_error(e); return GPTAQ_ELAUNCH; }
   }
   return GPTAQ_OK;
@@ -152,7 +155,13 @@ static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t to
 extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens,
                                 int64_t n, int64_t ldx, float* H, float* dXXT, int64_t ldh,
                                 void* ws, size_t ws_bytes, void* stream) {
-  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, ws, ws_bytes, stream);
+  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, false, ws, ws_bytes, stream);
+}
+
+extern "C" int gptaq_accumulate_upper(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens,
+                                      int64_t n, int64_t ldx, float* H, float* dXXT, int64_t ldh,
+                                      void* ws, size_t ws_bytes, void* stream) {
+  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, true, ws, ws_bytes, stream);
 }
 
 // Device address of this GPU's copy of `scratch`, looked up once per device (with that device current).
@@ -181,12 +190,12 @@ extern "C" int gptaq_accumulate_noalloc(const uint16_t* X, const uint16_t* Xtild
   if (!ws) return GPTAQ_ELAUNCH;
   // every pass overwrites the part of the scratch it reads (zero padding included), so nothing of the last
   // call's contents is ever read and nothing has to be cleared
-  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, ws, kScratchBytes, stream);
+  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, false, ws, kScratchBytes, stream);
 }
 
-extern "C" int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx,
-                                       float* H, float* dXXT, int64_t ldh, void* ws, size_t ws_bytes, int64_t* pending,
-                                       int flush, void* stream) {
+static int accumulate_staged_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx,
+                                  float* H, float* dXXT, int64_t ldh, bool dxxt_upper, void* ws, size_t ws_bytes,
+                                  int64_t* pending, int flush, void* stream) {
   constexpr int64_t CAP = 32768;                 // tokens per product launch
   if (!H || !dXXT || !ws || !pending || (tokens > 0 && (!X || !Xtilde))) return GPTAQ_ENULL;
   if (tokens < 0 || n <= 0 || n % 8 || ldx < n || ldx % 8 || ldh < n || n > (1 << 20) || tokens > (int64_t)1 << 30 ||
@@ -197,7 +206,7 @@ extern "C" int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde
   if (((uintptr_t)ws & 255) || ws_bytes < (size_t)(6 * np * CAP)) return GPTAQ_EWORKSPACE;
   hipStream_t s = (hipStream_t)stream;
   uint16_t *oX = (uint16_t*)ws, *oHi = oX + np * CAP, *oLo = oHi + np * CAP;
-  auto products = [&](int64_t cp) { return launch_products(oX, oHi, oLo, np, cp, n, H, dXXT, ldh, s); };
+  auto products = [&](int64_t cp) { return launch_products(oX, oHi, oLo, np, cp, n, H, dXXT, ldh, dxxt_upper, s); };
   int64_t done = 0, pend = *pending;
   while (done < tokens) {
     const int64_t take = tokens - done < CAP - pend ? tokens - done : CAP - pend, cp = round_up(take, 64);
@@ -222,6 +231,18 @@ extern "C" int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde
   }
   *pending = pend;
   return GPTAQ_OK;
+}
+
+extern "C" int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx,
+                                       float* H, float* dXXT, int64_t ldh, void* ws, size_t ws_bytes, int64_t* pending,
+                                       int flush, void* stream) {
+  return accumulate_staged_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, false, ws, ws_bytes, pending, flush, stream);
+}
+
+extern "C" int gptaq_accumulate_staged_upper(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                                             int64_t ldx, float* H, float* dXXT, int64_t ldh, void* ws, size_t ws_bytes,
+                                             int64_t* pending, int flush, void* stream) {
+  return accumulate_staged_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, true, ws, ws_bytes, pending, flush, stream);
 }
 
 extern "C" int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream) {

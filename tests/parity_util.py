@@ -32,7 +32,7 @@ def rel_fro(a, b) -> float:
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
-def gpu_accumulate(Xb, Xtb, chunks=None, ws_bytes=None):
+def gpu_accumulate(Xb, Xtb, chunks=None, ws_bytes=None, upper=False):
     tokens, n = Xb.shape
     X, Xt = to_dev_bf16(Xb), to_dev_bf16(Xtb)
     H = torch.zeros((n, n), dtype=torch.float32, device="cuda")
@@ -41,7 +41,7 @@ def gpu_accumulate(Xb, Xtb, chunks=None, ws_bytes=None):
     for t0, t1 in zip(bounds[:-1], bounds[1:]):
         nb = B.gptaq_accumulate_workspace_bytes(t1 - t0, n) if ws_bytes is None else ws_bytes
         ws = B.workspace(nb)
-        B.gptaq_accumulate(X[t0:t1], Xt[t0:t1], H, A, ws)
+        (B.gptaq_accumulate_upper if upper else B.gptaq_accumulate)(X[t0:t1], Xt[t0:t1], H, A, ws)
     torch.cuda.synchronize()
     return H, A
 

@@ -55,24 +55,24 @@ def test_workspace_queries(lib):
 def test_argument_errors_are_reported_before_any_launch(lib):
     one = ctypes.c_void_p(256)      # a non-null, aligned, never dereferenced address
     null = ctypes.c_void_p(0)
-    f = lib.gptaq_accumulate
-    assert f(null, one, 64, 64, 64, one, one, 64, one, 1 << 20, null) == -1
-    assert f(one, one, 64, 60, 64, one, one, 64, one, 1 << 20, null) == -2          # n % 8
-    assert f(one, one, 64, 64, 32, one, one, 64, one, 1 << 20, null) == -2          # ldx < n
-    assert f(one, one, 64, 64, 64, one, one, 64, one, 16, null) == -4               # workspace
-    assert f(one, one, 64, 64, 64, one, one, 64, ctypes.c_void_p(264), 1 << 20, null) == -4
-    assert f(one, one, 0, 64, 64, one, one, 64, one, 1 << 20, null) == 0            # empty chunk: no-op
-    g = lib.gptaq_accumulate_staged
-    pend = ctypes.c_int64(0)
+    for f in (lib.gptaq_accumulate, lib.gptaq_accumulate_upper):
+        assert f(null, one, 64, 64, 64, one, one, 64, one, 1 << 20, null) == -1
+        assert f(one, one, 64, 60, 64, one, one, 64, one, 1 << 20, null) == -2          # n % 8
+        assert f(one, one, 64, 64, 32, one, one, 64, one, 1 << 20, null) == -2          # ldx < n
+        assert f(one, one, 64, 64, 64, one, one, 64, one, 16, null) == -4               # workspace
+        assert f(one, one, 64, 64, 64, one, one, 64, ctypes.c_void_p(264), 1 << 20, null) == -4
+        assert f(one, one, 0, 64, 64, one, one, 64, one, 1 << 20, null) == 0            # empty chunk: no-op
     big = 6 * 256 * 32768
-    assert g(one, one, 64, 64, 64, one, one, 64, one, big, None, 0, null) == -1     # pending required
-    assert g(one, one, 100, 64, 64, one, one, 64, one, big, ctypes.byref(pend), 0, null) == -2   # ragged, no flush
-    assert g(one, one, 64, 64, 64, one, one, 64, one, 1 << 20, ctypes.byref(pend), 0, null) == -4
-    pend.value = 32
-    assert g(one, one, 64, 64, 64, one, one, 64, one, big, ctypes.byref(pend), 0, null) == -2    # pending % 64
-    pend.value = 0
-    assert g(null, null, 0, 64, 64, one, one, 64, one, big, ctypes.byref(pend), 1, null) == 0    # empty flush: no-op
-    assert pend.value == 0
+    for g in (lib.gptaq_accumulate_staged, lib.gptaq_accumulate_staged_upper):
+        pend = ctypes.c_int64(0)
+        assert g(one, one, 64, 64, 64, one, one, 64, one, big, None, 0, null) == -1     # pending required
+        assert g(one, one, 100, 64, 64, one, one, 64, one, big, ctypes.byref(pend), 0, null) == -2   # ragged, no flush
+        assert g(one, one, 64, 64, 64, one, one, 64, one, 1 << 20, ctypes.byref(pend), 0, null) == -4
+        pend.value = 32
+        assert g(one, one, 64, 64, 64, one, one, 64, one, big, ctypes.byref(pend), 0, null) == -2    # pending % 64
+        pend.value = 0
+        assert g(null, null, 0, 64, 64, one, one, 64, one, big, ctypes.byref(pend), 1, null) == 0    # empty flush: no-op
+        assert pend.value == 0
     p = lib.gptaq_prepare
     assert p(one, one, 64, 64, 0.01, null, null, one, 1 << 30, null) == -1          # info required
     assert p(one, one, 64, 32, 0.01, null, one, one, 1 << 30, null) == -2

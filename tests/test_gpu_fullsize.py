@@ -1,5 +1,5 @@
 """Parity at the full benchmark sizes (Llama-2-7B block shapes, 262144 tokens), in the launch
-configuration bench.py times (32768-token accumulate chunks, W4 g128, B = 128).
+configuration bench.py times (32768-token chunks through gptaq_accumulate_upper, W4 g128, B = 128).
 
 The full fp64 oracle does not fit these sizes everywhere, so each stage is checked on what the
 oracle can compute exactly:
@@ -28,17 +28,20 @@ def bits_of(t: torch.Tensor) -> np.ndarray:
     return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def accumulate_full(wl, iid, n):
+def accumulate_full(wl, iid, n, upper=True):
+    """upper: as bench.py does for the natural column order, only the entries of dXXT with col >= row (all that
+    Eq. 17 reads); the entries below the diagonal are then meaningless and no check here looks at them."""
     X, Xt = synth.make_activations_device(wl.tokens, n, wl.seed, iid, "cuda", wl.n_outliers, wl.outlier_scale, wl.noise)
     H = torch.zeros((n, n), device="cuda"); A = torch.zeros_like(H)
     ws = B.workspace(B.gptaq_accumulate_workspace_bytes(CHUNK, n))
+    acc = B.gptaq_accumulate_upper if upper else B.gptaq_accumulate
     for t0 in range(0, wl.tokens, CHUNK):
-        B.gptaq_accumulate(X[t0:t0 + CHUNK], Xt[t0:t0 + CHUNK], H, A, ws)
+        acc(X[t0:t0 + CHUNK], Xt[t0:t0 + CHUNK], H, A, ws)
     torch.cuda.synchronize()
     return X, Xt, H, A
 
 
-def check_sampled_blocks(wl, iid, n, X, Xt, H, A):
+def check_sampled_blocks(wl, iid, n, X, Xt, H, A, upper=True):
     rng = np.random.default_rng(11)
     out = synth.outlier_channels(n, wl.n_outliers, wl.seed, iid)
     S = np.unique(np.concatenate([out, [0, 1, 255, 256, n - 1], rng.choice(n, 96, replace=False)]))
@@ -53,7 +56,8 @@ def check_sampled_blocks(wl, iid, n, X, Xt, H, A):
     Hg = np.triu(Hg) + np.triu(Hg, 1).T
     Ag = A.cpu().numpy().astype(np.float64)
     eh = PU.rel_fro(Hg[np.ix_(S, S)], Hss)
-    ea = PU.rel_fro(Ag[np.ix_(S, T)], Ast)
+    keep = (T[None, :] >= S[:, None]) if upper else np.ones((len(S), len(T)), bool)
+    ea = PU.rel_fro(Ag[np.ix_(S, T)] * keep, Ast * keep)
     print(f"[{iid} n={n}] sampled H block {len(S)}x{len(S)}: {eh:.3e}; sampled dXXT block {len(S)}x{len(T)}: {ea:.3e}")
     assert eh <= 1e-5 and ea <= 1e-5
     return Hg, Ag

@@ -80,6 +80,48 @@ def test_accumulate_staged_small_chunks():
     assert torch.equal(Hd, H2)
 
 
+@pytest.mark.parametrize("tokens,n,chunks", [(4096, 512, None), (333, 1096, None), (640, 2304, [0, 200, 640]),
+                                             (1500, 520, [0, 64, 1500])])
+def test_accumulate_upper_is_the_full_sum_on_and_above_the_diagonal(tokens, n, chunks):
+    """gptaq_accumulate_upper: H and the entries of dXXT with col >= row equal the full call's bit for bit (and so
+    meet the oracle to the same bar); every entry below the diagonal is either untouched (zero) or the full call's
+    value; and the factors prepared from it are the full ones, bit for bit (Eq. 17 reads nothing below the diagonal)."""
+    Xb, Xtb = synth.make_activations(tokens, n, 9, "upper", 3, 20.0)
+    H, A = O.accumulate(Xb, Xtb)
+    Hf, Af = PU.gpu_accumulate(Xb, Xtb, chunks=chunks)
+    Hu, Au = PU.gpu_accumulate(Xb, Xtb, chunks=chunks, upper=True)
+    assert torch.equal(Hu, Hf)
+    af, au = Af.cpu().numpy(), Au.cpu().numpy()
+    assert np.array_equal(np.triu(au), np.triu(af))
+    assert PU.rel_fro(np.triu(au), np.triu(A)) <= 1e-5
+    low = np.tril(np.ones((n, n), bool), -1)
+    assert np.all((au[low] == 0) | (au[low] == af[low]))
+    assert np.count_nonzero(au[low]) < np.count_nonzero(af[low]) or n <= 128        # and it did leave work out
+    damp = 0.01
+    df, inf_f = PU.gpu_prepare(Hf, Af, damp)
+    du, inf_u = PU.gpu_prepare(Hu, Au, damp)
+    assert inf_f.cpu().tolist() == [0, 0] and inf_u.cpu().tolist() == [0, 0]
+    assert torch.equal(Hu, Hf) and torch.equal(Au, Af) and torch.equal(du, df)      # U, P, dead flags
+
+
+def test_accumulate_staged_upper_equals_direct_upper_calls():
+    from paper_2504_02692_amd import binding as B
+    n, chunk, tokens = 392, 2048, 17 * 2048 + 77
+    Xb, Xtb = synth.make_activations(tokens, n, 6, "staged-upper", 3, 20.0)
+    X, Xt = PU.to_dev_bf16(Xb), PU.to_dev_bf16(Xtb)
+    Hd = torch.zeros((n, n), device="cuda"); Ad = torch.zeros_like(Hd)
+    ws = B.workspace(B.gptaq_accumulate_workspace_bytes(32768, n))
+    pending = 0
+    for t0 in range(0, tokens, chunk):
+        pending = B.gptaq_accumulate_staged(X[t0:t0 + chunk], Xt[t0:t0 + chunk], Hd, Ad, ws, pending,
+                                            flush=t0 + chunk >= tokens, upper=True)
+    assert pending == 0
+    H2, A2 = PU.gpu_accumulate(Xb, Xtb, chunks=[0, 32768, tokens], upper=True)
+    assert torch.equal(Hd, H2) and torch.equal(Ad, A2)
+    _, A = O.accumulate(Xb, Xtb)
+    assert PU.rel_fro(np.triu(Ad.cpu().numpy()), np.triu(A)) <= 1e-5
+
+
 def test_symmetrize(c1):
     from paper_2504_02692_amd import binding as B
     Hd, _ = PU.gpu_accumulate(c1["Xb"], c1["Xtb"])

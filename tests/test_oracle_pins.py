@@ -122,6 +122,28 @@ def test_theorem_4_2_fused_P_equals_per_row_form():
         assert np.allclose(P[q, q + 1:], row2, rtol=1e-8, atol=1e-13)
 
 
+def test_P_reads_only_the_strictly_upper_triangle_of_dXXT():
+    """Eq. 16: row q of P is built from the columns after q of row q of dXXT (and Eq. 17 is the same rows stacked), so
+    the diagonal and the lower triangle of dXXT never reach P, and through it never reach a quantised weight.  The
+    library's upper-triangle accumulation rests on this; planted here as garbage below the diagonal."""
+    s = solved()
+    A, L, W = s["A"], s["L"], s["W"]
+    n = A.shape[0]
+    rng = np.random.default_rng(0)
+    low = np.tril(np.ones((n, n), bool))
+    for junk in (np.zeros((n, n)), 1e3 * np.abs(A).max() * rng.standard_normal((n, n))):
+        A2 = np.where(low, junk, A)
+        P2 = O.correction_matrix(A2, L)
+        assert np.allclose(P2, s["P"], rtol=1e-12, atol=1e-300)
+        U2, P3, _ = O.prepare(s["H"], np.where(low, junk, A), 0.01)
+        r0 = O.quantize_layer(W, s["U"], s["P"], 4, group=8)
+        r1 = O.quantize_layer(W, U2, P3, 4, group=8)
+        assert np.array_equal(r0["codes"], r1["codes"]) and np.allclose(r0["What"], r1["What"], rtol=1e-12)
+    # while an entry above the diagonal does
+    A3 = A.copy(); A3[2, 5] *= 1.5
+    assert not np.allclose(O.correction_matrix(A3, L)[2], s["P"][2], rtol=1e-6)
+
+
 def test_rows_of_P_are_ridge_regressions():
     """Row q of P regresses dX_q on the inputs after q (objective of Eq. 14 with the
     weight factored out); solved here by a library least-squares on the tokens, with
