@@ -53,6 +53,11 @@ int main() {
   EXPECT(gptaq_accumulate_staged(h, h, 64, 64, 64, f, f, 64, ws, 1 << 20, nullptr, 0, nullptr), GPTAQ_ENULL);
   pending = 40000;
   EXPECT(gptaq_accumulate_staged(h, h, 64, 64, 64, f, f, 64, ws, 1 << 20, &pending, 0, nullptr), GPTAQ_EDIM);
+  EXPECT(gptaq_accumulate_upper(nullptr, h, 64, 64, 64, f, f, 64, ws, 1 << 20, nullptr), GPTAQ_ENULL);
+  EXPECT(gptaq_accumulate_upper(h, h, 64, 60, 64, f, f, 64, ws, 1 << 20, nullptr), GPTAQ_EDIM);
+  EXPECT(gptaq_accumulate_upper(h, h, 64, 64, 64, f, f, 64, ws, 16, nullptr), GPTAQ_EWORKSPACE);
+  EXPECT(gptaq_accumulate_staged_upper(h, h, 64, 64, 64, f, f, 64, ws, 1 << 20, nullptr, 0, nullptr), GPTAQ_ENULL);
+  EXPECT(gptaq_accumulate_staged_upper(h, h, 64, 64, 64, f, f, 64, ws, 1 << 20, &pending, 0, nullptr), GPTAQ_EDIM);
   EXPECT(gptaq_symmetrize(nullptr, 64, 64, nullptr), GPTAQ_ENULL);
   EXPECT(gptaq_symmetrize(f, 64, 8, nullptr), GPTAQ_EDIM);
 
