@@ -43,6 +43,8 @@ struct GemmProblem {
                          // 2: square problem, only tiles with tile column >= tile row are scheduled
   int32_t k_mode;        // 0: all k; 1: k >= first column of the tile; 2: tile row0 <= k < tile col end
   int32_t store_mode;    // 0: C += acc; 1: C = acc; 2: C = acc where col > row, else 0
+  int32_t deal;          // how the tile list is shared out to the 8 XCDs: 0: one contiguous run each (tiles of equal
+                         // length); 1: dealt four tiles at a time (tile lengths that vary along the list: k_mode 1, 2)
   GemmTerm term[2];
 };
 

@@ -230,11 +230,17 @@ __device__ __forceinline__ void gemm_tile(const GemmBatch& b, unsigned char* sme
   int pi = 0;
   int ntile = b.ntiles[0];
   if (id >= ntile) { pi = 1; id -= ntile; ntile = b.ntiles[1]; }
-  {
+  const GemmProblem& P = b.p[pi];
+  if (!P.deal) {
     const int per = ntile >> 3, rem = ntile & 7, xcd = id & 7, loc = id >> 3;
     id = xcd < rem ? xcd * (per + 1) + loc : rem * (per + 1) + (xcd - rem) * per + loc;
+  } else if (id < (ntile & ~31)) {
+    // With triangular k ranges a contiguous run per XCD would give one XCD the long tiles and another the short ones.
+    // Here every XCD takes four consecutive tiles (the four tile rows of one column of a group) out of each 32, so
+    // each gets the same mix of lengths, and the 32 workgroups it runs side by side still share four left tiles.
+    const int xcd = id & 7, loc = id >> 3;
+    id = (((loc >> 2) << 3) + xcd) * 4 + (loc & 3);
   }
-  const GemmProblem& P = b.p[pi];
   int tm, tn;
   // Tiles are numbered in groups of GROUP tile rows, column by column inside a group, so the workgroups
   // an XCD runs side by side form a GROUP x 8 patch that shares GROUP left and 8 right operand tiles.

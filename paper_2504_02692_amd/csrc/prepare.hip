@@ -960,9 +960,9 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
                      ni, deadbuf, Ah, Al, np, info);
   GPTAQ_LAUNCH_CHECK();
 
-  // The K ranges of these two products are triangular, so tiles differ in length by the whole of K; while 256-tiles
-  // make a single round, the longest one sets the time and 128-tiles balance better (n = 4096: 4.66 -> 4.53 ms per
-  // call; n = 11008, 7 rounds of 256-tiles: 25.2 -> 27.5, so not there)
+  // The K ranges of these two products are triangular, so tiles differ in length by the whole of K: the tile list is
+  // dealt to the XCDs four tiles at a time (`deal`), not in contiguous runs (n = 11008: 2.8 -> 1.2 ms per product), and
+  // while 256-tiles make a single round, the longest one sets the time and 128-tiles balance better (n = 4096)
   const int t256 = gemm_tile_for(n, n);
   const int tile = (t256 == 256 && (np / 256) * (np / 256) <= 256) ? 128 : t256;
   GemmBatch b{};
@@ -971,7 +971,7 @@ extern "C" int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, floa
   // O = triu(dXXT U^T, 1): O[i][a] = sum_{b >= a} dXXT[i][b] U[a][b]
   g.C = Obuf; g.ldc = np; g.M = ni; g.N = ni; g.K = (int)np;
   g.tiles_m = g.tiles_n = (int)(np / tile);
-  g.kind = 2; g.nterm = 1; g.tile_mode = 1; g.k_mode = 1; g.store_mode = 2;
+  g.kind = 2; g.nterm = 1; g.tile_mode = 1; g.k_mode = 1; g.store_mode = 2; g.deal = 1;
   g.term[0] = {{Ah, Al}, {Uh, Ul}, np, np, 32, 32};
   hipError_t e;
   {
