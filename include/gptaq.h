@@ -101,9 +101,9 @@ int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t t
  * of dXXT[i][k] L[k][j], so no entry of dXXT on or below its diagonal ever reaches P, U or a quantised weight.
  * These calls leave the products for that half out (a third of the matrix-core work of a launch):
  *   dXXT : on return the entries with col >= row hold the same sums, bit for bit, as after the full call; the
- *          entries below the diagonal are in an unspecified state (some tiles updated, others untouched) but stay
- *          finite if they were finite on entry (zero-initialise the matrix as for the full call).
- *          gptaq_prepare on such a matrix returns the same U and P, bit for bit, as on the full one.
+ *          entries below the diagonal are in an unspecified state (some tiles updated, others untouched).
+ *          gptaq_prepare reads only the entries with col > row, so it returns the same U and P, bit for bit,
+ *          as on the full matrix.
  *   NOT for act_order: gptaq_permute_hessian moves entries across the diagonal and needs the full matrix.
  * H and every other argument as for the full calls; a series may not mix full and upper calls if the lower
  * half is to mean anything. */
@@ -127,10 +127,12 @@ int gptaq_symmetrize(float* H, int64_t n, int64_t ldh, void* stream);
  *   P = ((dXXT L) (.) M_U) L^T = triu(dXXT U^T, 1) U   (Eq. 17).
  *
  *   H    : in: upper triangle of H.  out: U (upper triangular, zeros below), fp32.
- *   dXXT : in: dXXT.                 out: P (strictly upper triangular, zeros elsewhere).
+ *   dXXT : in: dXXT; only the entries with col > row are read (Eq. 17 uses no others, see
+ *          gptaq_accumulate_upper).  out: P (strictly upper triangular, zeros elsewhere).
  *   dead : n bytes, out: 1 for dead inputs else 0.  May be NULL.
  *   info : 2 x int32, out: info[0] = 0, or 1 + index of the first non-positive pivot, or -(1 + row) of a
- *          NaN/Inf entry found in H (upper triangle) or dXXT (in both cases U and P are garbage);
+ *          NaN/Inf entry found in H (upper triangle) or dXXT (strictly upper triangle) (in both cases U and P
+ *          are garbage);
  *          info[1] = number of dead inputs.
  *   n    : at most 65280.
  * Streams: part of the factor sweep runs on a helper stream that the library creates once per device

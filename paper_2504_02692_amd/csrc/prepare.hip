@@ -775,14 +775,17 @@ __global__ __launch_bounds__(256) void extract_U_kernel(const double* F, int64_t
   }
 }
 
-// bf16 hi/lo split of an fp32 matrix (rows flagged in `zero_rows` read as 0), padded to np x np.
+// bf16 hi/lo split of the strictly upper triangle of an fp32 matrix (rows flagged in `zero_rows` read as 0), padded
+// to np x np; entries on and below the diagonal are not read and come out as 0.  Both uses want exactly that: Eq. 17
+// masks dXXT L to its strictly upper part and L is lower triangular, so entry (i, k) of dXXT only ever meets a
+// non-zero of L when k > i, and the masked product itself is strictly upper.
 // `info` (may be NULL): a NaN or Inf among the entries read is reported as info[0] = -(1 + row of the entry).
 __global__ __launch_bounds__(256) void split_rows_kernel(const float* A, int64_t lda, int n, const uint8_t* zero_rows,
                                                          uint16_t* Ah, uint16_t* Al, int64_t np, int32_t* info) {
   const int64_t c = (int64_t)blockIdx.x * 256 + threadIdx.x, r = blockIdx.y;
   if (c >= np) return;
   float v = 0.f;
-  if (r < n && c < n && !(zero_rows && zero_rows[r])) v = A[r * lda + c];
+  if (r < n && c < n && c > r && !(zero_rows && zero_rows[r])) v = A[r * lda + c];
   if (info && !__builtin_isfinite(v)) atomicMin(info, -(1 + (int)r));
   const uint16_t h = bf16_rne(v);
   Ah[r * np + c] = h;

@@ -98,10 +98,14 @@ def test_accumulate_upper_is_the_full_sum_on_and_above_the_diagonal(tokens, n, c
     assert np.all((au[low] == 0) | (au[low] == af[low]))
     assert np.count_nonzero(au[low]) < np.count_nonzero(af[low]) or n <= 128        # and it did leave work out
     damp = 0.01
+    Hg, Ag = Hu.clone(), Au.clone()
+    Ag[torch.tril(torch.ones((n, n), dtype=torch.bool, device="cuda"))] = float("nan")   # prepare must not even look there
     df, inf_f = PU.gpu_prepare(Hf, Af, damp)
     du, inf_u = PU.gpu_prepare(Hu, Au, damp)
-    assert inf_f.cpu().tolist() == [0, 0] and inf_u.cpu().tolist() == [0, 0]
+    dg, inf_g = PU.gpu_prepare(Hg, Ag, damp)
+    assert inf_f.cpu().tolist() == [0, 0] and inf_u.cpu().tolist() == [0, 0] and inf_g.cpu().tolist() == [0, 0]
     assert torch.equal(Hu, Hf) and torch.equal(Au, Af) and torch.equal(du, df)      # U, P, dead flags
+    assert torch.equal(Hg, Hf) and torch.equal(Ag, Af)
 
 
 def test_accumulate_staged_upper_equals_direct_upper_calls():
@@ -209,9 +213,14 @@ def test_prepare_reports_dead_inputs_and_bad_pivots():
     Hn = H.copy(); Hn[5, 60] = np.nan
     _, _, _, info = run_prepare(Hn, A, 0.01)
     assert info.cpu().tolist()[0] == -(1 + 5)
-    An = A.copy(); An[33, 2] = np.inf
+    An = A.copy(); An[33, 60] = np.inf
     _, _, _, info = run_prepare(H, An, 0.01)
     assert info.cpu().tolist()[0] == -(1 + 33)
+    # entries of dXXT on or below the diagonal are not read at all (Eq. 17 has no use for them)
+    An = A.copy(); An[33, 2] = np.inf; An[7, 7] = np.nan
+    U2, P2, _, info = run_prepare(H, An, 0.01)
+    assert info.cpu().tolist() == [0, 1]
+    assert torch.equal(U2, Ud) and torch.equal(P2, Pd)
 
 
 # -------------------------------------------------------------------- quantize
