@@ -162,6 +162,9 @@ int gptaq_prepare(float* H, float* dXXT, int64_t n, int64_t ldh, float damp,
  *   blocksize : 1..128.
  *   codes  : (m x n) uint8, one code per byte, leading dimension n.
  *   scales, zeros : (m x G) fp32, G = max(1, n / group); zeros hold integers.
+ *   ws     : >= gptaq_quantize_workspace_bytes(m, n) bytes, 256-byte aligned: the update operands (-E and V of a
+ *            1024-column super-block for all rows, twice; the rows of U and P of EVERY super-block on the columns
+ *            after it, as bf16 hi + lo: about 4 n^2 bytes, 0.46 GB at n = 11008, 11 GB at n = 53248).
  * Quantiser: range [min(0,min w), max(0,max w)], scale = (max-min)/(2^bits-1),
  * zero = rint(-min/scale), q = clamp(rint(w/scale)+zero), rint = half-to-even.
  */

@@ -275,15 +275,10 @@ __global__ __launch_bounds__(64 * NW) void quant_block_kernel(QuantArgs a) {
 // sb0 + c * blocksize .. of U and P), the entries in the columns [c_begin, c_end), transposed to
 // (column x K) with the chunk's rows at K offsets 128 c .. 128 c + 127 (zero padded), split into bf16 hi+lo.
 // grid (ceil(padded columns / 64), 2, chunks): blockIdx.y = 0 for U, 1 for P.
-__global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* U, const float* P, int64_t ldh, int n,
-                                                                   int sb0, int blocksize, int c_begin, int c_end,
-                                                                   uint16_t* Uth, uint16_t* Utl, uint16_t* Pth,
-                                                                   uint16_t* Ptl, int64_t ldo) {
+__device__ __forceinline__ void split_transpose_rows_tile(const float* S, int64_t ldh, int n, int sb0, int blocksize,
+                                                          int chunk, int c_begin, int c_end, uint16_t* oh, uint16_t* ol,
+                                                          int64_t ldo) {
   __shared__ uint16_t th[64][QB + 2], tl[64][QB + 2];
-  const float* S = blockIdx.y ? P : U;
-  uint16_t* oh = blockIdx.y ? Pth : Uth;
-  uint16_t* ol = blockIdx.y ? Ptl : Utl;
-  const int chunk = blockIdx.z;
   const int i0 = sb0 + chunk * blocksize;
   const int bw = min(blocksize, n - i0);
   const int j0 = blockIdx.x * 64;
@@ -309,6 +304,37 @@ __global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* 
   }
 }
 
+__global__ __launch_bounds__(256) void split_transpose_rows_kernel(const float* U, const float* P, int64_t ldh, int n,
+                                                                   int sb0, int blocksize, int c_begin, int c_end,
+                                                                   uint16_t* Uth, uint16_t* Utl, uint16_t* Pth,
+                                                                   uint16_t* Ptl, int64_t ldo) {
+  split_transpose_rows_tile(blockIdx.y ? P : U, ldh, n, sb0, blocksize, blockIdx.z, c_begin, c_end,
+                            blockIdx.y ? Pth : Uth, blockIdx.y ? Ptl : Utl, ldo);
+}
+
+// Rows of the far right operands of super-block k: its columns after the super-block, in whole 256-row GEMM tiles,
+// plus one tile of zero rows (a 256-tile whose first row is the last 128-tile's reads that far).
+__host__ __device__ inline int64_t far_rows(int64_t n, int k) {
+  const int64_t rest = n - (int64_t)(k + 1) * kSbCols;
+  return (rest + 255) / 256 * 256 + 256;
+}
+
+// The far right operands of EVERY super-block that has columns after it, in one launch: they depend on U and P only,
+// so nothing of this has to sit between two super-blocks.  Super-block k's operands start at row sum_{i<k} far_rows(i)
+// of the four output arrays (row stride kSbCols); row r of its part holds column (k + 1) * kSbCols + r.
+// grid (far_rows(0) / 64, 2, 8 * number of such super-blocks): blockIdx.z = 8 k + chunk of 128 rows of the super-block.
+__global__ __launch_bounds__(256) void far_operands_all_kernel(const float* U, const float* P, int64_t ldh, int n,
+                                                               uint16_t* Uth, uint16_t* Utl, uint16_t* Pth,
+                                                               uint16_t* Ptl) {
+  const int k = blockIdx.z / (kSbCols / QB), chunk = blockIdx.z % (kSbCols / QB);
+  if ((int64_t)blockIdx.x * 64 >= far_rows(n, k)) return;
+  int64_t first = 0;
+  for (int i = 0; i < k; ++i) first += far_rows(n, i);
+  const int64_t o = first * kSbCols;
+  split_transpose_rows_tile(blockIdx.y ? P : U, ldh, n, k * kSbCols, QB, chunk, (k + 1) * kSbCols, n,
+                            (blockIdx.y ? Pth : Uth) + o, (blockIdx.y ? Ptl : Utl) + o, (int64_t)kSbCols);
+}
+
 }  // namespace gptaq
 
 using namespace gptaq;
@@ -318,7 +344,7 @@ constexpr int SB = 8;                         // column blocks per super-block (
 constexpr int KS = SB * QB;
 struct QLayout {
   int64_t mp, np;
-  size_t off[24], total;
+  size_t off[24], off_far[4], total;
 };
 QLayout q_layout(int64_t m, int64_t n) {
   QLayout L;
@@ -327,14 +353,18 @@ QLayout q_layout(int64_t m, int64_t n) {
   size_t o = 0;
   for (int i = 0; i < 24; ++i) {
     L.off[i] = o;
-    // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of its updates (all columns from the
-    // super-block's first on, plus a tile of padding rows); 8-11: left operands of the updates inside a
-    // super-block (quantize_sb.hip); 12-23: a second set of 0-11 (the far update of a super-block runs beside the
-    // next super-block, which writes its own -E, V and right operands; or the two row halves of a tall matrix
-    // run as two chains, each at its own super-block)
+    // 0-3: -E, V (hi, lo) of one super-block; 4-7: right operands of the updates of one super-block as the
+    // block-per-wave path makes them (all columns from the super-block's first on, plus a tile of padding rows);
+    // 8-11: left operands of the updates inside a super-block (quantize_sb.hip); 12-15 and 20-23: a second set of 0-3
+    // and 8-11 (the far update of a super-block runs beside the next super-block, which writes its own -E and V; or
+    // the two row halves of a tall matrix run as two chains, each at its own super-block); 16-19: unused
     const int k = i < 12 ? i : i - 12;
-    o += (size_t)(k < 4 ? L.mp * KS * 2 : k < 8 ? (L.np + 256) * KS * 2 : (int64_t)(kSbCols / 16) * kSbCols * 16 * 2);
+    o += (size_t)(k < 4 ? L.mp * KS * 2 : k < 8 ? (i < 12 ? (L.np + 256) * KS * 2 : 0) : (int64_t)(kSbCols / 16) * kSbCols * 16 * 2);
   }
+  // the far right operands of every super-block of the layer (far_operands_all_kernel), made once per call
+  int64_t rows = 0;
+  for (int k = 0; (int64_t)(k + 1) * kSbCols < n; ++k) rows += far_rows(n, k);
+  for (int i = 0; i < 4; ++i) { L.off_far[i] = o; o += (size_t)rows * kSbCols * 2; }
   L.total = o;
   return L;
 }
@@ -404,11 +434,14 @@ __global__ __launch_bounds__(256) void zero_dead_columns_kernel(float* W, int64_
 // super-block's columns) stays on the caller's stream, "far2" (everything after) runs on the library's helper stream
 // beside super-block k + 1, which mostly leaves the chip idle (its length is set by the chain of column steps, and a
 // 4096-row layer fills 64 of the 256 CUs).  Every column still receives its updates in super-block order (far1(k)
-// waits for far2(k - 1), which touches the same columns), so results are bit-reproducible.  -E, V and the right
-// operands are double-buffered: far2(k) reads set k & 1 while super-block k + 1 writes the other.
+// waits for far2(k - 1), which touches the same columns), so results are bit-reproducible.  -E and V are
+// double-buffered: far2(k) reads set k & 1 while super-block k + 1 writes the other.  The right operands of all far
+// updates (`farop`) are made once per call, before the first super-block: they depend on U and P only, and a split
+// pass between two super-blocks sat on the critical path of every one of them (4096 x 11008: 5.8 -> 4.9 ms).
 static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const float* U, const float* P, int64_t ldh,
                              const uint8_t* dead, int bits, int group, int sym, uint8_t* codes, float* scales,
-                             float* zeros, uint16_t* const* buf, hipStream_t s, int terms, bool may_use_helper = true) {
+                             float* zeros, uint16_t* const* buf, uint16_t* const* farop, hipStream_t s, int terms,
+                             bool may_use_helper = true, bool make_farop = true) {
   constexpr int64_t LDE = kSbCols;               // row stride of the -E / V buffers and of the far right operands
   if (dead) {
     hipLaunchKernelGGL(zero_dead_columns_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, s, W, ldw, (int)m, (int)n, dead);
@@ -440,17 +473,39 @@ static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const 
   SideStream* side = nullptr;
   if (two_chains) {
     side_lock.lock();
-    side = side_stream(2 * nsb + 1);
+    side = side_stream(3 * nsb + 3);
     if (!side) { set_last_hip_error(hipGetLastError()); return GPTAQ_ELAUNCH; }
   }
   bool ok = true;
   auto chk = [&](hipError_t e) { if (e != hipSuccess && ok) { ok = false; set_last_hip_error(e); } };
+  if (make_farop && terms != 0 && nsb >= 2) {
+    // right operands of every far update: rows of U and P of each super-block, the columns after it, transposed to
+    // (column x K) and split into bf16 hi + lo; a GEMM reads whole tiles of rows, hence the zero rows past n.  With two
+    // chains the pass runs on the helper stream, beside the first super-block.
+    hipStream_t st = s;
+    if (two_chains) {
+      st = side->stream;
+      chk(hipEventRecord(side->events[2 * nsb + 1], s));             // (U and P are ready where the caller's stream stands)
+      chk(hipStreamWaitEvent(st, side->events[2 * nsb + 1], 0));
+    }
+    {
+      ProfScope ps(kProfTrailSplit, st);
+      hipLaunchKernelGGL(far_operands_all_kernel, dim3((unsigned)(far_rows(n, 0) / 64), 2, (unsigned)((nsb - 1) * (kSbCols / QB))),
+                         dim3(256), 0, st, U, (terms & 2) ? P : U, ldh, (int)n, farop[0], farop[1], farop[2], farop[3]);
+      chk(hipGetLastError());
+    }
+    if (two_chains) chk(hipEventRecord(side->events[2 * nsb + 2], st));
+  }
   auto ev_sbk = [&](int k) { return side->events[2 * k]; };       // super-block k's kernel has finished
   auto ev_far2 = [&](int k) { return side->events[2 * k + 1]; };  // its far2 update has finished
-  // W[:, c0:c1] += [-E | V] [U; P][super-block rows, c0:c1] from buffer set `set`; the right operands' row 0 is column cbase
-  auto far_update = [&](int set, int64_t c0, int64_t c1, int64_t cbase, hipStream_t st, int max_wgs) {
+  // W[:, c0:c1] += [-E | V] [U; P][super-block rows, c0:c1]: -E and V from buffer set `set`, the right operands of
+  // super-block k from `farop` (made for the whole layer before the first super-block; row 0 of k's part is column cbase)
+  auto far_update = [&](int set, int k, int64_t c0, int64_t c1, int64_t cbase, hipStream_t st, int max_wgs) {
     uint16_t* const* ev = buf + (set ? 12 : 0);
-    uint16_t* const* rop = buf + (set ? 16 : 4);
+    int64_t first = 0;
+    for (int i = 0; i < k; ++i) first += far_rows(n, i);
+    const uint16_t* rop[4];
+    for (int i = 0; i < 4; ++i) rop[i] = farop[i] + first * LDE;
     const int64_t nt = c1 - c0, ro = (c0 - cbase) * LDE;
     const int tile = gemm_tile_for(m, nt);
     GemmBatch b{};
@@ -470,7 +525,6 @@ static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const 
     const bool far = terms != 0 && sb_end < n;
     const int set = two_chains ? (k & 1) : 0;
     uint16_t* const* ev = buf + (set ? 12 : 0);
-    uint16_t* const* rop = buf + (set ? 16 : 4);
     a.sb0 = (int)sb0; a.sbw = (int)(sb_end - sb0);
     a.Eh = far ? ev[0] : nullptr; a.El = ev[1]; a.Vh = ev[2]; a.Vl = ev[3];
     // this super-block's columns must have every earlier update, and its buffer set must be free again
@@ -478,15 +532,6 @@ static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const 
     if (terms != 0) {
       ProfScope ps(kProfTrailSplit, s);
       chk(launch_near_operands(U, (terms & 2) ? P : nullptr, ldh, (int)n, (int)sb0, a.sbw, buf + 8, s));
-      if (far) {
-        // right operands of the far update: rows of U and P of this super-block, columns after it, transposed
-        // to (column x K) and split; a GEMM reads whole tiles of rows, hence the zero rows past n
-        const int64_t rows = round_up(n - sb_end, 256) + 256;
-        hipLaunchKernelGGL(split_transpose_rows_kernel, dim3((unsigned)(rows / 64), 2, (unsigned)(kSbCols / QB)), dim3(256),
-                           0, s, U, (terms & 2) ? P : U, ldh, (int)n, (int)sb0, QB, (int)sb_end, (int)n, rop[0], rop[1],
-                           rop[2], rop[3], LDE);
-        chk(hipGetLastError());
-      }
     }
     {
       ProfScope ps(kProfColumnLoop, s);
@@ -494,16 +539,27 @@ static int quantize_layer_sb(float* W, int64_t m, int64_t n, int64_t ldw, const 
     }
     if (!far) continue;
     const int64_t next_end = n < sb_end + kSbCols ? n : sb_end + kSbCols;
-    if (two_chains && next_end < n) {
+    const bool has_far2 = two_chains && next_end < n;
+    // While far2 is long (many columns left) it sets the pace and starts at once, sharing the chip with far1; once it
+    // is shorter than a super-block it only slows far1 down, which the next super-block waits for: then it starts
+    // when far1 is done.
+    // (measured on 4096 x 11008 with the switch at 0 / 2 / 4 / 6 / 10 super-blocks of columns left: 5.66 / 5.62 / 5.60 /
+    // 5.54 / 5.68 ms; 4096 x 4096: 1.59 / 1.53 / 1.50 / 1.51 / 1.50)
+    constexpr int kFar2LateCols = 6 * kSbCols;
+    const bool far2_late = has_far2 && (n - next_end) <= kFar2LateCols;
+    auto launch_far2 = [&]() {
       chk(hipEventRecord(ev_sbk(k), s));
       chk(hipStreamWaitEvent(side->stream, ev_sbk(k), 0));
       // far2: beside the next super-block, on the compute units that one leaves free (a 256-tile fills a unit, two
       // 128-tiles share one)
-      far_update(set, next_end, n, sb_end, side->stream, (cus - sbk_wgs) * (gemm_tile_for(m, n - next_end) == 256 ? 1 : 2));
+      far_update(set, k, next_end, n, sb_end, side->stream, (cus - sbk_wgs) * (gemm_tile_for(m, n - next_end) == 256 ? 1 : 2));
       chk(hipEventRecord(ev_far2(k), side->stream));
-    }
+    };
+    if (has_far2 && !far2_late) launch_far2();
     if (two_chains && k >= 1) chk(hipStreamWaitEvent(s, ev_far2(k - 1), 0));   // it adds to the same columns: keep the order
-    far_update(set, sb_end, two_chains ? next_end : n, sb_end, s, 0);   // far1: the next super-block's columns (or all of them)
+    if (two_chains && k == 0 && make_farop) chk(hipStreamWaitEvent(s, side->events[2 * nsb + 2], 0));   // the far operands
+    far_update(set, k, sb_end, two_chains ? next_end : n, sb_end, s, 0);   // far1: the next super-block's columns (or all of them)
+    if (far2_late) launch_far2();
   }
   if (two_chains) {
     // whatever was handed to the helper stream is behind the caller's stream when the call returns, error or not
@@ -541,7 +597,16 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
     // far update of the other half instead of leaving the chip to it alone (and 344 workgroups of 64 rows no
     // longer make a second, mostly empty round on 256 CUs).
     const int64_t nsb = (n + kSbCols - 1) / kSbCols;
+    uint16_t* farop[4];
+    for (int i = 0; i < 4; ++i) farop[i] = (uint16_t*)(base + L.off_far[i]);
     if (terms != 0 && nsb >= 2 && m >= kRowSplitMin) {
+      {
+        // the far operands serve both halves: made once, before the streams fork
+        ProfScope ps(kProfTrailSplit, s);
+        hipLaunchKernelGGL(far_operands_all_kernel, dim3((unsigned)(far_rows(n, 0) / 64), 2, (unsigned)((nsb - 1) * (kSbCols / QB))),
+                           dim3(256), 0, s, U, (terms & 2) ? P : U, ldh, (int)n, farop[0], farop[1], farop[2], farop[3]);
+        GPTAQ_LAUNCH_CHECK();
+      }
       const int64_t mA = round_up((m + 1) / 2, 256), mB = m - mA;   // (a multiple of the GEMM's row tile: the halves' padded
                                                                     //  rows of the -E / V buffers then do not overlap)
       const int64_t G = group > 0 ? n / group : 1;
@@ -557,16 +622,16 @@ static int quantize_layer_impl(float* W, int64_t m, int64_t n, int64_t ldw, cons
       for (int i = 0; i < 4; ++i) bufB[i] = buf[i] + mA * kSbCols;          // its rows of the -E / V buffers
       for (int i = 4; i < 12; ++i) bufB[i] = buf[12 + i];                  // operands of its own
       const int rcB = quantize_layer_sb(W + mA * ldw, mB, n, ldw, U, P, ldh, dead, bits, group, sym, codes + mA * n,
-                                        scales + mA * G, zeros + mA * G, bufB, side->stream, terms, false);
-      const int rcA = quantize_layer_sb(W, mA, n, ldw, U, P, ldh, dead, bits, group, sym, codes, scales, zeros, buf, s,
-                                        terms, false);
+                                        scales + mA * G, zeros + mA * G, bufB, farop, side->stream, terms, false, false);
+      const int rcA = quantize_layer_sb(W, mA, n, ldw, U, P, ldh, dead, bits, group, sym, codes, scales, zeros, buf, farop,
+                                        s, terms, false, false);
       // the helper stream is behind the caller's stream when the call returns, error or not
       const hipError_t keep = (hipError_t)gptaq_last_hip_error();
       if (hipEventRecord(ev_join, side->stream) == hipSuccess) hipStreamWaitEvent(s, ev_join, 0);
       if (rcA != GPTAQ_OK || rcB != GPTAQ_OK) set_last_hip_error(keep);
       return rcA != GPTAQ_OK ? rcA : rcB;
     }
-    return quantize_layer_sb(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, codes, scales, zeros, buf, s, terms);
+    return quantize_layer_sb(W, m, n, ldw, U, P, ldh, dead, bits, group, sym, codes, scales, zeros, buf, farop, s, terms);
   }
 
   QuantArgs a;

@@ -46,9 +46,12 @@ def test_workspace_queries(lib):
     assert lib.gptaq_accumulate_workspace_bytes(262144, 4096) == 3 * 4096 * 32768 * 2
     assert lib.gptaq_accumulate_workspace_bytes(0, 512) == 0
     assert lib.gptaq_prepare_workspace_bytes(512) > 512 * 512 * 8
-    # -E / V operands of one super-block (1024 columns), right operands for all columns + one tile of padding rows
-    # two sets of (-E / V of a super-block, right operands of its far update, left operands of the updates inside it)
-    assert lib.gptaq_quantize_workspace_bytes(512, 512) == 2 * (4 * 512 * 1024 + 4 * (512 + 256) * 1024 + 4 * (1024 // 16) * 1024 * 16) * 2
+    # two sets of (-E / V of a super-block of 1024 columns, left operands of the updates inside it), the right operands
+    # of one super-block for the block-by-block path, and the far right operands of every super-block that has columns
+    # after it: 3072 + 2048 + 1024 rows and a 256-row tile of padding each at n = 4096, none at n = 512
+    sets = lambda m: 2 * (4 * m * 1024 + 4 * (1024 // 16) * 1024 * 16) * 2
+    assert lib.gptaq_quantize_workspace_bytes(512, 512) == sets(512) + 4 * (512 + 256) * 1024 * 2
+    assert lib.gptaq_quantize_workspace_bytes(512, 4096) == sets(512) + 4 * (4096 + 256) * 1024 * 2 + 4 * (6144 + 3 * 256) * 1024 * 2
     assert lib.gptaq_status_string(0) == b"ok"
 
 
