@@ -84,7 +84,7 @@ def extras():
     dev = "cuda"
     print(f"{'operation':58s} {'size':>22s} {'ms':>9s} {'GB/s':>8s}")
     for n in (4096, 11008):
-        tokens = 8192
+        tokens = 32768
         X, Xt = synth.make_activations_device(tokens, n, 0, f"extras{n}", dev)
         H = torch.zeros((n, n), device=dev); A = torch.zeros_like(H)
         B.gptaq_accumulate(X, Xt, H, A, B.workspace(B.gptaq_accumulate_workspace_bytes(tokens, n)))
@@ -95,6 +95,19 @@ def extras():
         ws = B.workspace(B.gptaq_permute_hessian_workspace_bytes(n))
         t = time_ms(lambda: B.gptaq_permute_hessian(H, A, perm, ws))
         print(f"{'act_order: permute H and dXXT (rows and columns)':58s} {f'n = {n}':>22s} {t:9.3f} {4 * n * n * 4 / t / 1e6:8.0f}")
+        # the two-pass route (order first, then the sums of the reordered inputs, upper triangle of dXXT only)
+        diag = torch.zeros(n, device=dev)
+        t = time_ms(lambda: B.gptaq_accumulate_diag(X, diag))
+        print(f"{'act_order, two passes: diagonal of H from X':58s} {f'{tokens} x {n}':>22s} {t:9.3f} {tokens * n * 2 / t / 1e6:8.0f}")
+        inv = B.gptaq_invert_permutation(perm)
+        wsa = B.workspace(B.gptaq_accumulate_workspace_bytes(tokens, n))
+        H2 = torch.zeros((n, n), device=dev); A2 = torch.zeros_like(H2)
+        for name, fn in (("accumulate, every entry of dXXT", lambda: B.gptaq_accumulate(X, Xt, H2, A2, wsa)),
+                         ("accumulate, upper triangle of dXXT", lambda: B.gptaq_accumulate_upper(X, Xt, H2, A2, wsa)),
+                         ("accumulate, upper triangle, reordered inputs", lambda: B.gptaq_accumulate_upper_permuted(X, Xt, inv, H2, A2, wsa))):
+            t = time_ms(fn)
+            print(f"{name:58s} {f'{tokens} x {n}':>22s} {t:9.3f} {'':>8s}")
+        del H2, A2, wsa
         m = 4096
         W = synth.make_weights_device(m, n, 0, f"w{n}", dev)
         t = time_ms(lambda: B.gptaq_permute_columns_f32(W, perm))

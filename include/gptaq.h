@@ -210,13 +210,32 @@ int gptaq_quantize_layer_ex(float* W, int64_t m, int64_t n, int64_t ldw,
  * i / group, and scales / zeros are indexed by that group.
  *
  * gptaq_act_order: perm[r] = index of the input with the r-th largest H[i][i]; equal diagonals keep
- *   their index order.  perm: n x int32 (device).
+ *   their index order.  perm: n x int32 (device).  ldh == 0: H points at the n diagonal entries themselves.
  * gptaq_permute_hessian: in place H[i][j] <- H[perm[i]][perm[j]] (upper triangle in; the whole symmetric
  *   matrix out) and dXXT[i][j] <- dXXT[perm[i]][perm[j]];  ws: gptaq_permute_hessian_workspace_bytes(n).
  * gptaq_permute_columns_{f32,u8}: inverse == 0: out[r][i] = in[r][perm[i]];
  *   inverse != 0: out[r][perm[i]] = in[r][i].  in and out must not overlap.
  */
 int gptaq_act_order(const float* H, int64_t n, int64_t ldh, int32_t* perm, void* stream);
+
+/* act_order with the upper-triangle accumulation (gptaq_accumulate_upper): the order has to be known BEFORE the sums
+ * are taken, because which of dXXT[a][b] and dXXT[b][a] Eq. 17 reads depends on which of a and b comes first.  Two
+ * passes over the layer's calibration inputs:
+ *   pass 1: gptaq_accumulate_diag for every chunk (diag[j] += sum_t X[t][j]^2, the diagonal of H; diag: n x fp32,
+ *           zero-initialised by the caller); gptaq_act_order(diag, n, 0, perm); gptaq_invert_permutation(perm, n, inv)
+ *           (inv[perm[r]] = r; perm must be a permutation of 0 .. n-1);
+ *   pass 2: gptaq_accumulate_upper_permuted for every chunk: gptaq_accumulate_upper on the inputs with their channels
+ *           reordered, H[i][j] = sum_t X[t][perm[i]] X[t][perm[j]], dXXT likewise: what gptaq_permute_hessian makes
+ *           of the full sums, on and above the diagonal, bit for bit, with no n x n permutation pass and two fifths
+ *           less matrix-core work.  Then gptaq_prepare, Wp = W[:, perm], gptaq_quantize_layer as above.
+ * The diagonal of pass 1 is summed in another order than the one inside H, so two inputs whose diagonals agree to
+ * fp32 rounding may swap places against gptaq_act_order(H); any order is a valid one for the solve.
+ * Other arguments as for gptaq_accumulate_upper.  inv_perm: n x int32 (device). */
+int gptaq_accumulate_diag(const uint16_t* X, int64_t tokens, int64_t n, int64_t ldx, float* diag, void* stream);
+int gptaq_invert_permutation(const int32_t* perm, int64_t n, int32_t* inv, void* stream);
+int gptaq_accumulate_upper_permuted(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                                    int64_t ldx, const int32_t* inv_perm, float* H, float* dXXT, int64_t ldh,
+                                    void* ws, size_t ws_bytes, void* stream);
 size_t gptaq_permute_hessian_workspace_bytes(int64_t n);
 int gptaq_permute_hessian(float* H, float* dXXT, int64_t n, int64_t ldh, const int32_t* perm,
                           void* ws, size_t ws_bytes, void* stream);

@@ -51,6 +51,11 @@ _SIGS = {
                                            _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_void_p, _c.c_size_t,
                                            _c.c_void_p, _c.c_int, _c.c_int, _c.c_int]),
     "gptaq_act_order": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p]),
+    "gptaq_accumulate_diag": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p]),
+    "gptaq_invert_permutation": (_c.c_int, [_c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_void_p]),
+    "gptaq_accumulate_upper_permuted": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_int64, _c.c_void_p,
+                                                   _c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_void_p, _c.c_size_t,
+                                                   _c.c_void_p]),
     "gptaq_permute_hessian_workspace_bytes": (_c.c_size_t, [_c.c_int64]),
     "gptaq_permute_hessian": (_c.c_int, [_c.c_void_p, _c.c_void_p, _c.c_int64, _c.c_int64, _c.c_void_p, _c.c_void_p,
                                          _c.c_size_t, _c.c_void_p]),
@@ -111,6 +116,11 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 def _need(t: torch.Tensor, dtype, name: str) -> None:
     if not t.is_cuda or t.dtype != dtype or t.dim() != 2 or t.stride(1) != 1:
         raise GptaqError(f"{name}: expected a 2-D row-major {dtype} CUDA tensor")
+
+
+def _need_vec(t: torch.Tensor, dtype, name: str) -> None:
+    if not t.is_cuda or t.dtype != dtype or t.dim() != 1 or not t.is_contiguous():
+        raise GptaqError(f"{name}: expected a contiguous 1-D {dtype} CUDA tensor")
 
 
 def workspace(nbytes: int, device="cuda") -> torch.Tensor:
@@ -276,12 +286,48 @@ def gptaq_measure_hbm_copy(nbytes: int = 1 << 30, reps: int = 10) -> float:
 
 
 def gptaq_act_order(H: torch.Tensor) -> torch.Tensor:
-    """perm (int32, device): inputs in the order of decreasing H[i][i]."""
-    _need(H, torch.float32, "H")
+    """perm (int32, device): inputs in the order of decreasing H[i][i]; a 1-D H is the diagonal itself."""
+    if H.dim() == 1:
+        _need_vec(H, torch.float32, "H")
+    else:
+        _need(H, torch.float32, "H")
     n = H.shape[0]
     perm = torch.empty(n, dtype=torch.int32, device=H.device)
-    _check(load().gptaq_act_order(_ptr(H), n, H.stride(0), _ptr(perm), _stream()), "gptaq_act_order")
+    _check(load().gptaq_act_order(_ptr(H), n, H.stride(0) if H.dim() == 2 else 0, _ptr(perm), _stream()), "gptaq_act_order")
     return perm
+
+
+def gptaq_accumulate_diag(X: torch.Tensor, diag: torch.Tensor) -> None:
+    """diag[j] += sum_t X[t][j]^2 (the diagonal of H) for token-major bf16 X."""
+    _need(X, torch.bfloat16, "X"); _need_vec(diag, torch.float32, "diag")
+    tokens, n = X.shape
+    if diag.shape != (n,):
+        raise GptaqError("gptaq_accumulate_diag: shape mismatch")
+    _check(load().gptaq_accumulate_diag(_ptr(X), tokens, n, X.stride(0), _ptr(diag), _stream()), "gptaq_accumulate_diag")
+
+
+def gptaq_invert_permutation(perm: torch.Tensor) -> torch.Tensor:
+    """inv with inv[perm[r]] = r (int32, device)."""
+    if perm.dtype != torch.int32 or perm.dim() != 1 or not perm.is_contiguous():
+        raise GptaqError("gptaq_invert_permutation: perm must be a contiguous int32 vector")
+    inv = torch.empty_like(perm)
+    _check(load().gptaq_invert_permutation(_ptr(perm), perm.numel(), _ptr(inv), _stream()), "gptaq_invert_permutation")
+    return inv
+
+
+def gptaq_accumulate_upper_permuted(X: torch.Tensor, Xtilde: torch.Tensor, inv_perm: torch.Tensor, H: torch.Tensor,
+                                    dXXT: torch.Tensor, ws: torch.Tensor) -> None:
+    """gptaq_accumulate_upper on the inputs with their channels reordered: input channel j is row / column inv_perm[j]."""
+    _need(X, torch.bfloat16, "X"); _need(Xtilde, torch.bfloat16, "Xtilde")
+    _need(H, torch.float32, "H"); _need(dXXT, torch.float32, "dXXT")
+    tokens, n = X.shape
+    if Xtilde.shape != X.shape or Xtilde.stride(0) != X.stride(0) or H.shape != (n, n) or dXXT.shape != (n, n) \
+            or H.stride(0) != dXXT.stride(0) or inv_perm.dtype != torch.int32 or inv_perm.shape != (n,) \
+            or not inv_perm.is_contiguous():
+        raise GptaqError("gptaq_accumulate_upper_permuted: shape mismatch")
+    _check(load().gptaq_accumulate_upper_permuted(_ptr(X), _ptr(Xtilde), tokens, n, X.stride(0), _ptr(inv_perm), _ptr(H),
+                                                  _ptr(dXXT), H.stride(0), _ptr(ws), ws.numel(), _stream()),
+           "gptaq_accumulate_upper_permuted")
 
 
 def gptaq_permute_hessian_workspace_bytes(n: int) -> int:

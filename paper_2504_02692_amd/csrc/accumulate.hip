@@ -28,7 +28,8 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float f) {
 __global__ __launch_bounds__(256) void split_transpose_kernel(
     const uint16_t* __restrict__ X, const uint16_t* __restrict__ Xt, int64_t ldx,
     int tokens, int n, uint16_t* __restrict__ oX, uint16_t* __restrict__ oHi,
-    uint16_t* __restrict__ oLo, int64_t ldo /* padded rows */, int tile0 /* first 64-token tile of the output */) {
+    uint16_t* __restrict__ oLo, int64_t ldo /* padded rows */, int tile0 /* first 64-token tile of the output */,
+    const int32_t* __restrict__ row_of /* NULL, or operand row of input column j (a permutation of 0 .. n-1) */) {
   constexpr int LS = 72;                                  // padded LDS row, 144 bytes
   __shared__ __attribute__((aligned(16))) uint16_t sx[64 * LS], sh[64 * LS], sl[64 * LS];
   const int n0 = blockIdx.x * 64, t0 = blockIdx.y * 64;
@@ -58,7 +59,12 @@ __global__ __launch_bounds__(256) void split_transpose_kernel(
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
     const int nl = r + 32 * p;
-    const int64_t g = (((int64_t)(blockIdx.y + tile0) * 2 + (c >> 2)) * ldo + n0 + nl) * 32 + (c & 3) * 8;   // k-tile-major
+    int64_t row = n0 + nl;                                  // (padding rows stay where they are)
+    if (row_of && row < n) {
+      const int32_t rr = row_of[row];
+      if (rr >= 0 && rr < n) row = rr;                      // (an entry out of range cannot send a write out of bounds)
+    }
+    const int64_t g = (((int64_t)(blockIdx.y + tile0) * 2 + (c >> 2)) * ldo + row) * 32 + (c & 3) * 8;   // k-tile-major
     *reinterpret_cast<u32x4*>(oX + g) = *reinterpret_cast<const u32x4*>(sx + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oHi + g) = *reinterpret_cast<const u32x4*>(sh + nl * LS + c * 8);
     *reinterpret_cast<u32x4*>(oLo + g) = *reinterpret_cast<const u32x4*>(sl + nl * LS + c * 8);
@@ -74,6 +80,40 @@ __global__ void symmetrize_kernel(float* H, int n, int64_t ldh) {
   __syncthreads();
   const int li = bj * 32 + threadIdx.y, lj = bi * 32 + threadIdx.x;   // transposed position
   if (li < n && lj < n && li > lj) H[(int64_t)li * ldh + lj] = t[threadIdx.x][threadIdx.y];
+}
+
+// diag[j] += sum_t X[t][j]^2 (the diagonal of H) for the 64 columns of a workgroup: thread = (token lane, 8 columns),
+// 32 token lanes; products of bf16 numbers are exact in fp32, the sums are taken in a fixed order.
+__global__ __launch_bounds__(256) void column_sumsq_kernel(const uint16_t* __restrict__ X, int64_t ldx, int tokens, int n,
+                                                           float* __restrict__ diag) {
+  __shared__ float part[32][65];
+  const int oct = threadIdx.x & 7, tl = threadIdx.x >> 3, col = blockIdx.x * 64 + oct * 8;
+  float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (col < n)
+    for (int t = tl; t < tokens; t += 32) {
+      const u32x4 a = *reinterpret_cast<const u32x4*>(X + (int64_t)t * ldx + col);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float x = bf16_to_f32((a[e >> 1] >> ((e & 1) * 16)) & 0xffffu);
+        acc[e] = fmaf(x, x, acc[e]);
+      }
+    }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[tl][oct * 8 + e] = acc[e];
+  __syncthreads();
+  if (threadIdx.x < 64 && blockIdx.x * 64 + threadIdx.x < n) {
+    float sum = 0.f;
+    for (int l = 0; l < 32; ++l) sum += part[l][threadIdx.x];
+    diag[blockIdx.x * 64 + threadIdx.x] += sum;
+  }
+}
+
+__global__ void invert_permutation_kernel(const int32_t* perm, int n, int32_t* inv) {
+  const int r = blockIdx.x * 256 + threadIdx.x;
+  if (r < n) {
+    const int32_t i = perm[r];
+    if (i >= 0 && i < n) inv[i] = r;
+  }
 }
 
 static int64_t padded_n(int64_t n) { return round_up(n, gemm_tile_for(n, n)); }
@@ -123,7 +163,8 @@ static int accumulate_args(const uint16_t* X, const uint16_t* Xtilde, int64_t to
 }
 
 static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n, int64_t ldx, float* H,
-                           float* dXXT, int64_t ldh, bool dxxt_upper, void* ws, size_t ws_bytes, void* stream) {
+                           float* dXXT, int64_t ldh, bool dxxt_upper, void* ws, size_t ws_bytes, void* stream,
+                           const int32_t* row_of = nullptr) {
   if (!ws) return GPTAQ_ENULL;
   if (const int rc = accumulate_args(X, Xtilde, tokens, n, ldx, H, dXXT, ldh)) return rc;
   if ((uintptr_t)ws & 255) return GPTAQ_EWORKSPACE;
@@ -143,7 +184,7 @@ static int accumulate_impl(const uint16_t* X, const uint16_t* Xtilde, int64_t to
       ProfScope ps(kProfAccumSplit, s);
       hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)),
                          dim3(256), 0, s, X + t0 * ldx, Xtilde + t0 * ldx, ldx, (int)c, (int)n,
-                         oX, oHi, oLo, np, 0);
+                         oX, oHi, oLo, np, 0, row_of);
     }
     GPTAQ_LAUNCH_CHECK();
     hipError_t e = launch_products(oX, oHi, oLo, np, cp, n, H, dXXT, ldh, dxxt_upper, s);
@@ -156,6 +197,33 @@ extern "C" int gptaq_accumulate(const uint16_t* X, const uint16_t* Xtilde, int64
                                 int64_t n, int64_t ldx, float* H, float* dXXT, int64_t ldh,
                                 void* ws, size_t ws_bytes, void* stream) {
   return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, false, ws, ws_bytes, stream);
+}
+
+extern "C" int gptaq_accumulate_upper_permuted(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens, int64_t n,
+                                               int64_t ldx, const int32_t* inv_perm, float* H, float* dXXT, int64_t ldh,
+                                               void* ws, size_t ws_bytes, void* stream) {
+  if (!inv_perm) return GPTAQ_ENULL;
+  return accumulate_impl(X, Xtilde, tokens, n, ldx, H, dXXT, ldh, true, ws, ws_bytes, stream, inv_perm);
+}
+
+extern "C" int gptaq_accumulate_diag(const uint16_t* X, int64_t tokens, int64_t n, int64_t ldx, float* diag, void* stream) {
+  if (!X || !diag) return GPTAQ_ENULL;
+  if (tokens < 0 || n <= 0 || n % 8 || ldx < n || ldx % 8 || n > (1 << 20) || tokens > (int64_t)1 << 30) return GPTAQ_EDIM;
+  if ((uintptr_t)X & 15) return GPTAQ_EDIM;
+  if (tokens == 0) return GPTAQ_OK;
+  hipLaunchKernelGGL(column_sumsq_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, (hipStream_t)stream, X, ldx,
+                     (int)tokens, (int)n, diag);
+  GPTAQ_LAUNCH_CHECK();
+  return GPTAQ_OK;
+}
+
+extern "C" int gptaq_invert_permutation(const int32_t* perm, int64_t n, int32_t* inv, void* stream) {
+  if (!perm || !inv) return GPTAQ_ENULL;
+  if (n <= 0 || n > (1 << 24)) return GPTAQ_EDIM;
+  hipLaunchKernelGGL(invert_permutation_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, perm,
+                     (int)n, inv);
+  GPTAQ_LAUNCH_CHECK();
+  return GPTAQ_OK;
 }
 
 extern "C" int gptaq_accumulate_upper(const uint16_t* X, const uint16_t* Xtilde, int64_t tokens,
@@ -213,7 +281,7 @@ static int accumulate_staged_impl(const uint16_t* X, const uint16_t* Xtilde, int
     {
       ProfScope ps(kProfAccumSplit, s);
       hipLaunchKernelGGL(split_transpose_kernel, dim3((unsigned)(np / 64), (unsigned)(cp / 64)), dim3(256), 0, s,
-                         X + done * ldx, Xtilde + done * ldx, ldx, (int)take, (int)n, oX, oHi, oLo, np, (int)(pend / 64));
+                         X + done * ldx, Xtilde + done * ldx, ldx, (int)take, (int)n, oX, oHi, oLo, np, (int)(pend / 64), (const int32_t*)nullptr);
     }
     GPTAQ_LAUNCH_CHECK();
     done += take;

@@ -58,7 +58,7 @@ using namespace gptaq;
 
 extern "C" int gptaq_act_order(const float* H, int64_t n, int64_t ldh, int32_t* perm, void* stream) {
   if (!H || !perm) return GPTAQ_ENULL;
-  if (n <= 0 || ldh < n || n > (1 << 20)) return GPTAQ_EDIM;
+  if (n <= 0 || (ldh != 0 && ldh < n) || n > (1 << 20)) return GPTAQ_EDIM;     // ldh == 0: H is the diagonal itself
   hipLaunchKernelGGL(rank_diag_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, H, ldh,
                      (int)n, perm);
   GPTAQ_LAUNCH_CHECK();

@@ -58,6 +58,12 @@ int main() {
   EXPECT(gptaq_accumulate_upper(h, h, 64, 64, 64, f, f, 64, ws, 16, nullptr), GPTAQ_EWORKSPACE);
   EXPECT(gptaq_accumulate_staged_upper(h, h, 64, 64, 64, f, f, 64, ws, 1 << 20, nullptr, 0, nullptr), GPTAQ_ENULL);
   EXPECT(gptaq_accumulate_staged_upper(h, h, 64, 64, 64, f, f, 64, ws, 1 << 20, &pending, 0, nullptr), GPTAQ_EDIM);
+  EXPECT(gptaq_accumulate_upper_permuted(h, h, 64, 64, 64, nullptr, f, f, 64, ws, 1 << 20, nullptr), GPTAQ_ENULL);
+  EXPECT(gptaq_accumulate_upper_permuted(h, h, 64, 64, 64, i32, f, f, 8, ws, 1 << 20, nullptr), GPTAQ_EDIM);
+  EXPECT(gptaq_accumulate_diag(nullptr, 64, 64, 64, f, nullptr), GPTAQ_ENULL);
+  EXPECT(gptaq_accumulate_diag(h, 64, 60, 64, f, nullptr), GPTAQ_EDIM);
+  EXPECT(gptaq_invert_permutation(nullptr, 64, i32, nullptr), GPTAQ_ENULL);
+  EXPECT(gptaq_invert_permutation(i32, -1, i32, nullptr), GPTAQ_EDIM);
   EXPECT(gptaq_symmetrize(nullptr, 64, 64, nullptr), GPTAQ_ENULL);
   EXPECT(gptaq_symmetrize(f, 64, 8, nullptr), GPTAQ_EDIM);
 

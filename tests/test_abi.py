@@ -65,6 +65,13 @@ def test_argument_errors_are_reported_before_any_launch(lib):
         assert f(one, one, 64, 64, 64, one, one, 64, one, 16, null) == -4               # workspace
         assert f(one, one, 64, 64, 64, one, one, 64, ctypes.c_void_p(264), 1 << 20, null) == -4
         assert f(one, one, 0, 64, 64, one, one, 64, one, 1 << 20, null) == 0            # empty chunk: no-op
+    assert lib.gptaq_accumulate_upper_permuted(one, one, 64, 64, 64, null, one, one, 64, one, 1 << 20, null) == -1   # inv_perm
+    assert lib.gptaq_accumulate_upper_permuted(one, one, 64, 60, 64, one, one, one, 64, one, 1 << 20, null) == -2
+    assert lib.gptaq_accumulate_diag(null, 64, 64, 64, one, null) == -1
+    assert lib.gptaq_accumulate_diag(one, 64, 64, 32, one, null) == -2                  # ldx < n
+    assert lib.gptaq_accumulate_diag(one, 0, 64, 64, one, null) == 0
+    assert lib.gptaq_invert_permutation(one, 0, one, null) == -2
+    assert lib.gptaq_act_order(one, 64, 32, one, null) == -2                            # 0 < ldh < n
     big = 6 * 256 * 32768
     for g in (lib.gptaq_accumulate_staged, lib.gptaq_accumulate_staged_upper):
         pend = ctypes.c_int64(0)

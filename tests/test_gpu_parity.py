@@ -372,6 +372,47 @@ def test_act_order_path():
     assert np.array_equal(What.cpu().numpy()[:, ref["perm"]], got["What"])
 
 
+@pytest.mark.parametrize("tokens,n,chunks", [(3000, 384, None), (1500, 1096, [0, 700, 1500]), (900, 2304, None)])
+def test_act_order_with_the_upper_triangle_accumulation(tokens, n, chunks):
+    """The two-pass route: the diagonal of H first, the order from it, then H and the upper triangle of dXXT of the
+    reordered inputs directly.  Against the one-pass route (full sums, gptaq_act_order, gptaq_permute_hessian): the same
+    order, the same H and dXXT on and above the diagonal bit for bit, hence the same factors."""
+    from paper_2504_02692_amd import binding as B
+    Xb, Xtb = synth.make_activations(tokens, n, 21, "ao2", 3, 30.0)
+    X, Xt = PU.to_dev_bf16(Xb), PU.to_dev_bf16(Xtb)
+    bounds = chunks or [0, tokens]
+    # one pass
+    Hf, Af = PU.gpu_accumulate(Xb, Xtb, chunks=chunks)
+    perm1 = B.gptaq_act_order(Hf)
+    # two passes
+    diag = torch.zeros(n, device="cuda")
+    for t0, t1 in zip(bounds[:-1], bounds[1:]):
+        B.gptaq_accumulate_diag(X[t0:t1], diag)
+    H64, _ = O.accumulate(Xb, Xtb)
+    assert PU.rel_fro(diag.cpu().numpy(), np.diag(H64)) <= 1e-6
+    perm = B.gptaq_act_order(diag)
+    # the order of the fp64 diagonal, up to swaps of inputs whose diagonals agree to fp32 rounding (the two routes sum
+    # the diagonal in different orders); from here on both routes use this one
+    p = perm.cpu().numpy()
+    d64 = np.diag(H64)[p]
+    assert sorted(p.tolist()) == list(range(n)) and np.all(d64[:-1] >= d64[1:] * (1 - 1e-5))
+    assert np.mean(p == perm1.cpu().numpy()) > 0.99 and np.mean(p == O.act_order_permutation(H64)) > 0.99
+    perm1 = perm
+    inv = B.gptaq_invert_permutation(perm)
+    assert np.array_equal(inv.cpu().numpy()[perm.cpu().numpy()], np.arange(n))
+    Hp = torch.zeros((n, n), device="cuda"); Ap = torch.zeros_like(Hp)
+    for t0, t1 in zip(bounds[:-1], bounds[1:]):
+        B.gptaq_accumulate_upper_permuted(X[t0:t1], Xt[t0:t1], inv, Hp, Ap, B.workspace(B.gptaq_accumulate_workspace_bytes(t1 - t0, n)))
+    B.gptaq_permute_hessian(Hf, Af, perm1, B.workspace(B.gptaq_permute_hessian_workspace_bytes(n)))
+    torch.cuda.synchronize()
+    assert np.array_equal(np.triu(Hp.cpu().numpy()), np.triu(Hf.cpu().numpy()))
+    assert np.array_equal(np.triu(Ap.cpu().numpy()), np.triu(Af.cpu().numpy()))
+    d1, i1 = PU.gpu_prepare(Hf, Af, 0.1)
+    d2, i2 = PU.gpu_prepare(Hp, Ap, 0.1)
+    assert i1.cpu().tolist() == [0, 0] and i2.cpu().tolist() == [0, 0]
+    assert torch.equal(Hp, Hf) and torch.equal(Ap, Af)                   # U and P
+
+
 @pytest.mark.parametrize("bits,group,sym", [(4, 128, False), (3, 64, True), (4, 0, False)])
 def test_clip_range_search(c1, bits, group, sym):
     """Section 5.1's MSE-searched clipping range (grid 100, 80 steps) against the oracle."""
