@@ -350,7 +350,11 @@ def main() -> int:
         "other_kernels": other,
         "stages_ms_per_step": stage_ms,
         "accumulate_ms_per_step_by_form": {"dxxt_upper": acc_ms["upper"], "dxxt_full": acc_ms["full"],
-                                           "timed_path_uses": "dxxt_upper" if upper else "dxxt_full"},
+                                           "timed_path_uses": "dxxt_upper" if upper else "dxxt_full",
+                                           "ms_per_step_with_the_other_form": ms_per_step + (acc_ms["full"] - acc_ms["upper"]) * (1 if upper else -1),
+                                           "note": "the step is timed with one form; the accumulation alone is then timed in both, and the "
+                                                   "difference gives what the step would take with the other (every entry of dXXT is "
+                                                   "what act_order in one pass needs)"},
         "kernels_ms_per_step": {k: v[1] for k, v in prof.items()},
         "kernel_launches_per_step": {k: v[0] for k, v in prof.items()},
     }
