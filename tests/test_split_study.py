@@ -50,3 +50,11 @@ def test_cheaper_treatments_of_the_dx_split():
     assert e_diff > 1e-4                           # cancellation of two fp32 sums: outside the bar
     assert e_fp8 > 1e-5                            # lo and X in fp8 (the matrix cores take no bf16 x fp8 pair): just outside the bar
     assert err(prod(hi, X) + prod(_e4m3(lo), X)) < 1e-5      # (with a full-precision X it would pass: the X rounding is what breaks it)
+    # fp16 keeps 11 bits of dX: one fp16 product is still outside the bar; with its remainder as an fp8 product it would
+    # be inside, at the price of fp16 operands (a range of 65504, against bf16's, for activations of any scale)
+    h16 = dX.astype(np.float16).astype(np.float32)
+    X16 = X.astype(np.float16).astype(np.float32)
+    e_h16 = err(prod(h16, X16))
+    e_h16_fp8 = err(prod(h16, X16) + prod(_e4m3(dX - h16), _e4m3(X)))
+    print(f"fp16 hi only {e_h16:.1e}  fp16 hi + fp8 remainder {e_h16_fp8:.1e}")
+    assert e_h16 > 1e-5 and e_h16_fp8 < 2e-6
