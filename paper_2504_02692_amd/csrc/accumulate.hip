@@ -82,15 +82,15 @@ __global__ void symmetrize_kernel(float* H, int n, int64_t ldh) {
   if (li < n && lj < n && li > lj) H[(int64_t)li * ldh + lj] = t[threadIdx.x][threadIdx.y];
 }
 
-// diag[j] += sum_t X[t][j]^2 (the diagonal of H) for the 64 columns of a workgroup: thread = (token lane, 8 columns),
-// 32 token lanes; products of bf16 numbers are exact in fp32, the sums are taken in a fixed order.
+// diag[j] += sum_t X[t][j]^2 (the diagonal of H) for the 32 columns of a workgroup: thread = (token lane, 8 columns),
+// 64 token lanes; products of bf16 numbers are exact in fp32, the sums are taken in a fixed order.
 __global__ __launch_bounds__(256) void column_sumsq_kernel(const uint16_t* __restrict__ X, int64_t ldx, int tokens, int n,
                                                            float* __restrict__ diag) {
-  __shared__ float part[32][65];
-  const int oct = threadIdx.x & 7, tl = threadIdx.x >> 3, col = blockIdx.x * 64 + oct * 8;
+  __shared__ float part[64][33];
+  const int oct = threadIdx.x & 3, tl = threadIdx.x >> 2, col = blockIdx.x * 32 + oct * 8;
   float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   if (col < n)
-    for (int t = tl; t < tokens; t += 32) {
+    for (int t = tl; t < tokens; t += 64) {
       const u32x4 a = *reinterpret_cast<const u32x4*>(X + (int64_t)t * ldx + col);
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
@@ -101,10 +101,10 @@ __global__ __launch_bounds__(256) void column_sumsq_kernel(const uint16_t* __res
 #pragma unroll
   for (int e = 0; e < 8; ++e) part[tl][oct * 8 + e] = acc[e];
   __syncthreads();
-  if (threadIdx.x < 64 && blockIdx.x * 64 + threadIdx.x < n) {
+  if (threadIdx.x < 32 && blockIdx.x * 32 + threadIdx.x < n) {
     float sum = 0.f;
-    for (int l = 0; l < 32; ++l) sum += part[l][threadIdx.x];
-    diag[blockIdx.x * 64 + threadIdx.x] += sum;
+    for (int l = 0; l < 64; ++l) sum += part[l][threadIdx.x];
+    diag[blockIdx.x * 32 + threadIdx.x] += sum;
   }
 }
 
@@ -211,7 +211,7 @@ extern "C" int gptaq_accumulate_diag(const uint16_t* X, int64_t tokens, int64_t 
   if (tokens < 0 || n <= 0 || n % 8 || ldx < n || ldx % 8 || n > (1 << 20) || tokens > (int64_t)1 << 30) return GPTAQ_EDIM;
   if ((uintptr_t)X & 15) return GPTAQ_EDIM;
   if (tokens == 0) return GPTAQ_OK;
-  hipLaunchKernelGGL(column_sumsq_kernel, dim3((unsigned)((n + 63) / 64)), dim3(256), 0, (hipStream_t)stream, X, ldx,
+  hipLaunchKernelGGL(column_sumsq_kernel, dim3((unsigned)((n + 31) / 32)), dim3(256), 0, (hipStream_t)stream, X, ldx,
                      (int)tokens, (int)n, diag);
   GPTAQ_LAUNCH_CHECK();
   return GPTAQ_OK;
