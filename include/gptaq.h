@@ -99,7 +99,7 @@ int gptaq_accumulate_staged(const uint16_t* X, const uint16_t* Xtilde, int64_t t
  * input channels are processed in their natural order.  Theorem 4.2 / Eq. 17 build P from dXXT L masked to its
  * STRICTLY UPPER triangle, with L lower triangular: entry (i, j) of the masked product is a sum over k >= j > i
  * of dXXT[i][k] L[k][j], so no entry of dXXT on or below its diagonal ever reaches P, U or a quantised weight.
- * These calls leave the products for that half out (a third of the matrix-core work of a launch):
+ * These calls leave the products for that half out (two fifths of the matrix-core work of a launch):
  *   dXXT : on return the entries with col >= row hold the same sums, bit for bit, as after the full call; the
  *          entries below the diagonal are in an unspecified state (some tiles updated, others untouched).
  *          gptaq_prepare reads only the entries with col > row, so it returns the same U and P, bit for bit,

@@ -131,7 +131,7 @@ extern "C" size_t gptaq_accumulate_workspace_bytes(int64_t tokens, int64_t n) {
 // H += X X^T (upper tiles) and dXXT += (hi + lo) X^T over cp tokens of split operands, as one launch.
 // dxxt_upper: only the tiles of dXXT that touch its upper triangle.  Eq. 17 masks dXXT L to its strictly upper part and
 // L is lower triangular, so entry (i, k) of dXXT reaches P only through sums over k >= j > i: in the natural column
-// order nothing on or below the diagonal is ever read, and a third of the products of the launch can be left out.
+// order nothing on or below the diagonal is ever read, and two fifths of the products of the launch can be left out.
 static hipError_t launch_products(const uint16_t* oX, const uint16_t* oHi, const uint16_t* oLo, int64_t np, int64_t cp,
                                   int64_t n, float* H, float* dXXT, int64_t ldh, bool dxxt_upper, hipStream_t s) {
   const int tile = gemm_tile_for(n, n);
