@@ -503,7 +503,15 @@ def test_bench_line_on_the_small_workload():
     r = line["roofline"]
     assert r["bound"] == "mfma" and r["unit"] == "TFLOP/s" and r["peak"] == 2500.0
     assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0 < r["frac"] < 1
-    assert "workload" in line["config"]
+    assert "workload" in line["config"] and "col >= row" in line["config"]["workload"]
+    forms = line["accumulate_ms_per_step_by_form"]
+    assert forms["timed_path_uses"] == "dxxt_upper" and forms["dxxt_upper"] > 0 and forms["dxxt_full"] > 0
+    # the other form of the accumulation on request
+    out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "c1", "--steps", "1", "--warmup", "1",
+                          "--no-cpu-baseline", "--full-dxxt"], capture_output=True, text=True, timeout=110, cwd=root)
+    assert out.returncode == 0, out.stderr[-2000:]
+    full = json.loads(out.stdout.strip().splitlines()[-1])
+    assert full["accumulate_ms_per_step_by_form"]["timed_path_uses"] == "dxxt_full" and "all entries" in full["config"]["workload"]
     # more than one GPU is refused with a message
     out = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
                          timeout=60, cwd=root)
